@@ -1,0 +1,99 @@
+/*
+ * polydl.h -- C ABI of the MI355X (gfx950) convolution / matrix-product library.
+ *
+ * The library computes the two loop nests PolyDL (arXiv 2006.02230) optimises: the forward 2-D
+ * convolution of a CNN layer (figure "The 2-D Convolution code", section "Convolutions") and
+ * the matrix multiplication at its core (figure "Matrix multiplication code", section
+ * "Notation"; C = beta*C + alpha*A*B in section "GEMM").  Argument names follow the paper's
+ * loop bounds: N = nImg, C = nIfm, K = nOfm, H/W = input height/width, R/S = kh/kw,
+ * P/Q = ofh/ofw.
+ *
+ * Conventions common to every entry point
+ *   - every data pointer is a DEVICE pointer (HBM), owned by the caller; the library neither
+ *     frees nor keeps it after the work it enqueued has run, except where a handle says so;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); all work is
+ *     enqueued on it and the call returns without synchronising;
+ *   - the return value is POLYDL_OK (0) or a negative polydl_status; on an argument error
+ *     nothing is enqueued and no output byte is written;
+ *   - tensors are dense, contiguous float32 unless stated; input and output must not overlap.
+ */
+#ifndef POLYDL_H
+#define POLYDL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum polydl_status {
+    POLYDL_OK = 0,
+    POLYDL_ERR_NULL_POINTER = -1,   /* a required pointer is NULL */
+    POLYDL_ERR_BAD_DIMENSION = -2,  /* a size <= 0, stride <= 0, pad < 0, or no output (P or Q <= 0) */
+    POLYDL_ERR_UNSUPPORTED = -3,    /* valid problem outside the kernels' index range, bad override */
+    POLYDL_ERR_LAUNCH = -4,         /* the HIP runtime refused the launch or an allocation */
+    POLYDL_ERR_NO_DEVICE = -5       /* no gfx950 device is current */
+} polydl_status;
+
+/* Element-wise operator applied to every output after the reduction (section "Operator
+ * Fusion": the operator is placed in the peeled last iteration of the reduction loops, which
+ * on this hardware is the kernel's epilogue).  ReLU y = max(x,0); ReLU6 y = min(max(x,0),6)
+ * (section "Evaluation of Operator Fusion"). */
+typedef enum polydl_act { POLYDL_ACT_NONE = 0, POLYDL_ACT_RELU = 1, POLYDL_ACT_RELU6 = 2 } polydl_act;
+
+/* A point of the variant space (section "Compile Time Selection of Top performing code
+ * version": variants differ in tile sizes and loop order; figure "A code version generated for
+ * PolyDL": two tiling levels around the microkernel).  Here level 2 is the workgroup tile of
+ * the implicit GEMM, level 1 the tile one 64-lane wave keeps in accumulator registers.
+ * For convolution the GEMM is out[K][N*P*Q] = wt[K][C*R*S] * im2col[C*R*S][N*P*Q], so
+ * bm tiles output channels and bn tiles output pixels; for SGEMM bm tiles M and bn tiles N. */
+typedef struct polydl_tile_cfg {
+    int bm, bn, bk;   /* workgroup tile: bm x bn outputs, bk reduction elements per stage      */
+    int wm, wn;       /* wave tile (multiples of 32); the workgroup has (bm/wm)*(bn/wn) waves  */
+    int split_k;      /* >= 1: the reduction is cut into this many parts summed with atomics   */
+    int layout;       /* 0: read NCHW / KCRS directly; 1: via blocked NCHWc / KCRSck copies    */
+    int raster;       /* 0: workgroups walk M fastest; 1: chunked per XCD, grouped for L2 reuse */
+} polydl_tile_cfg;
+
+/* ---- forward convolution ------------------------------------------------------------------
+ * out[n][k][p][q] = act( bias[k] + sum_{c,r,s} in[n][c][p*stride+r-pad][q*stride+s-pad] * wt[k][c][r][s] )
+ * with taps outside the image contributing zero (the paper's listing has no padding; logical
+ * zero padding is this library's reading), no filter flip, the same stride and pad on both
+ * axes, P = floor((H+2*pad-R)/stride)+1 and Q likewise from W and S.
+ *   in   N*C*H*W floats, NCHW.      wt  K*C*R*S floats, KCRS.
+ *   bias K floats or NULL (= none). out N*K*P*Q floats, NKPQ, overwritten.
+ *   fuse_relu: 0 = no activation, 1 = ReLU.  (polydl_conv2d_fwd_act takes any polydl_act.)
+ * Accumulation is float32 on the matrix cores; the summation order is unspecified. */
+int polydl_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      const float *in, const float *wt, const float *bias, float *out,
+                      int fuse_relu, void *stream);
+
+int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                          const float *in, const float *wt, const float *bias, float *out,
+                          int act /* polydl_act */, void *stream);
+
+/* ---- matrix product ------------------------------------------------------------------------
+ * C[i][j] += sum_k A[i][k] * B[k][j]   (alpha = beta = 1, the reading taken of section "GEMM").
+ * Row-major, A is M x K, B is K x N, C is M x N and is read and accumulated into.  K = 0 is
+ * allowed (C is left as it is). */
+int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream);
+
+/* ---- variant control (the sweep forces a variant; reports read back the one used) -----------
+ * polydl_set_tile_override: cfg != NULL forces that variant for every later call of the
+ * calling process (POLYDL_ERR_UNSUPPORTED if it is not a compiled variant; a later problem it
+ * cannot serve returns POLYDL_ERR_UNSUPPORTED); cfg == NULL returns to the reuse-model pick.
+ * polydl_get_last_tile: the variant the most recent successful conv/sgemm call launched.
+ * polydl_num_variants / polydl_get_variant: enumerate the compiled family
+ * (kind 0 = convolution, 1 = sgemm). */
+int polydl_set_tile_override(const polydl_tile_cfg *cfg);
+int polydl_get_last_tile(polydl_tile_cfg *cfg);
+int polydl_num_variants(int kind);
+int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg);
+
+const char *polydl_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLYDL_H */

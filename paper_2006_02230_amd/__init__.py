@@ -1,0 +1,11 @@
+"""MI355X (gfx950) forward convolution and SGEMM behind the C ABI of include/polydl.h.
+
+The Python layer only marshals arguments (device pointers, sizes, the current HIP stream) into
+libpolydl.so; every arithmetic step runs in the HIP kernels.  There is no CPU fallback: if the
+library has not been built, importing this package raises.
+"""
+from .binding import (lib, PolydlError, TileCfg, conv2d_fwd, sgemm, set_tile_override,
+                      get_last_tile, variants, status_string, LIB_PATH)
+
+__all__ = ["lib", "PolydlError", "TileCfg", "conv2d_fwd", "sgemm", "set_tile_override",
+           "get_last_tile", "variants", "status_string", "LIB_PATH"]

@@ -1,0 +1,129 @@
+"""ctypes binding of libpolydl.so: same names as the C entry points, argument marshalling only."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpolydl.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libpolydl.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(or python paper_2006_02230_amd/build.py) first; there is no fallback path")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+ACT = {None: 0, "none": 0, "relu": 1, "relu6": 2, 0: 0, 1: 1, 2: 2, False: 0, True: 1}
+
+
+class PolydlError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, status_string(status), status))
+
+
+class TileCfg(ctypes.Structure):
+    """Mirror of polydl_tile_cfg."""
+    _fields_ = [(n, ctypes.c_int) for n in ("bm", "bn", "bk", "wm", "wn", "split_k", "layout", "raster")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+    def __repr__(self):
+        return "TileCfg(%s)" % ", ".join("%s=%d" % kv for kv in self.as_dict().items())
+
+
+_i, _p = ctypes.c_int, ctypes.c_void_p
+lib.polydl_conv2d_fwd.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
+lib.polydl_conv2d_fwd_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
+lib.polydl_sgemm.argtypes = [_i, _i, _i, _p, _p, _p, _p]
+lib.polydl_set_tile_override.argtypes = [ctypes.POINTER(TileCfg)]
+lib.polydl_get_last_tile.argtypes = [ctypes.POINTER(TileCfg)]
+lib.polydl_num_variants.argtypes = [_i]
+lib.polydl_get_variant.argtypes = [_i, _i, ctypes.POINTER(TileCfg)]
+lib.polydl_status_string.argtypes = [_i]
+lib.polydl_status_string.restype = ctypes.c_char_p
+for _f in (lib.polydl_conv2d_fwd, lib.polydl_conv2d_fwd_act, lib.polydl_sgemm,
+           lib.polydl_set_tile_override, lib.polydl_get_last_tile, lib.polydl_num_variants,
+           lib.polydl_get_variant):
+    _f.restype = _i
+
+
+def status_string(status):
+    return lib.polydl_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise PolydlError(status, where)
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t, name):
+    """Device pointer of a contiguous float32 CUDA/HIP tensor (None passes NULL)."""
+    if t is None:
+        return None
+    if not (t.is_cuda and t.is_contiguous() and t.dtype.is_floating_point and t.element_size() == 4):
+        raise TypeError("%s must be a contiguous float32 tensor in device memory" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None):
+    """polydl_conv2d_fwd_act on torch device tensors x (NCHW), w (KCRS); returns out (NKPQ)."""
+    import torch
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    if out is None:
+        out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.float32, device=x.device)
+    st = lib.polydl_conv2d_fwd_act(N, C, H, W, K, R, S, stride, pad, _dev(x, "x"), _dev(w, "w"),
+                                   _dev(bias, "bias"), _dev(out, "out"), ACT[act], _stream_ptr(stream))
+    _check(st, "polydl_conv2d_fwd")
+    return out
+
+
+def sgemm(A, B, C, stream=None):
+    """polydl_sgemm: C += A @ B in place on torch device tensors (row-major)."""
+    M, K = A.shape
+    K2, N = B.shape
+    if K2 != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    st = lib.polydl_sgemm(M, N, K, _dev(A, "A"), _dev(B, "B"), _dev(C, "C"), _stream_ptr(stream))
+    _check(st, "polydl_sgemm")
+    return C
+
+
+def set_tile_override(cfg=None, **kw):
+    """Force a variant (TileCfg or keyword fields) for later calls; None returns to the picker."""
+    if cfg is None and not kw:
+        _check(lib.polydl_set_tile_override(None), "polydl_set_tile_override")
+        return
+    if cfg is None:
+        cfg = TileCfg(kw["bm"], kw["bn"], kw["bk"], kw["wm"], kw["wn"], kw.get("split_k", 1),
+                      kw.get("layout", 0), kw.get("raster", 0))
+    _check(lib.polydl_set_tile_override(ctypes.byref(cfg)), "polydl_set_tile_override")
+
+
+def get_last_tile():
+    cfg = TileCfg()
+    _check(lib.polydl_get_last_tile(ctypes.byref(cfg)), "polydl_get_last_tile")
+    return cfg
+
+
+def variants(kind=0):
+    """The compiled variant family (kind 0 = convolution, 1 = sgemm) as a list of TileCfg."""
+    n = lib.polydl_num_variants(kind)
+    if n < 0:
+        raise PolydlError(n, "polydl_num_variants")
+    out = []
+    for i in range(n):
+        c = TileCfg()
+        _check(lib.polydl_get_variant(kind, i, ctypes.byref(c)), "polydl_get_variant")
+        out.append(c)
+    return out

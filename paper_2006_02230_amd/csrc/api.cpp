@@ -1,0 +1,194 @@
+// The C ABI: argument checks, variant choice, launch.  No data is touched on the host.
+#include <hip/hip_runtime.h>
+#include <atomic>
+#include <mutex>
+#include "internal.hpp"
+#include "variants.hpp"
+
+namespace polydl {
+
+POLYDL_TILE_FAMILY(POLYDL_DECLARE_LAUNCHERS)
+
+#define POLYDL_VARIANT_ROW(BM, BN, BK, WM, WN)                                                     \
+    {BM, BN, BK, WM, WN, (BM / WM) * (BN / WN) * 64, 2 * (BM * (BK + 4) + BK * (BN + 4)) * 4,      \
+     sgemm_launch_##BM##x##BN##x##BK##_##WM##x##WN, conv_launch_##BM##x##BN##x##BK##_##WM##x##WN},
+const Variant kVariants[] = {POLYDL_TILE_FAMILY(POLYDL_VARIANT_ROW)};
+const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+static std::mutex g_mu;
+static bool g_have_override = false;
+static polydl_tile_cfg g_override;
+static polydl_tile_cfg g_last = {0, 0, 0, 0, 0, 0, 0, 0};
+
+static const Variant *find_variant(const polydl_tile_cfg &c)
+{
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.bm == c.bm && v.bn == c.bn && v.bk == c.bk && v.wm == c.wm && v.wn == c.wn) return &v;
+    }
+    return nullptr;
+}
+
+static void cfg_of(const Variant &v, int split_k, int layout, int raster, polydl_tile_cfg *c)
+{
+    c->bm = v.bm; c->bn = v.bn; c->bk = v.bk; c->wm = v.wm; c->wn = v.wn;
+    c->split_k = split_k; c->layout = layout; c->raster = raster;
+}
+
+// Placeholder choice until the reuse model is wired in: the largest square-ish tile that still
+// yields at least one workgroup per compute unit, else the smallest tile.
+static polydl_tile_cfg default_pick(long Mg, long Ng)
+{
+    polydl_tile_cfg best;
+    cfg_of(kVariants[0], 1, 0, 0, &best);
+    long best_area = 0;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.bk != 16 || v.threads != 256) continue;
+        long tiles = ((Mg + v.bm - 1) / v.bm) * ((Ng + v.bn - 1) / v.bn);
+        long area = (long)v.bm * v.bn;
+        if (tiles >= 512 && area > best_area && area <= 128 * 128) {
+            best_area = area;
+            cfg_of(v, 1, 0, 0, &best);
+        }
+    }
+    return best;
+}
+
+static int sgemm_impl(int M, int N, int K, const float *A, const float *B, float *C, void *stream)
+{
+    if (M <= 0 || N <= 0 || K < 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!C || (K > 0 && (!A || !B))) return POLYDL_ERR_NULL_POINTER;
+    if (K == 0) return POLYDL_OK;
+    polydl_tile_cfg cfg;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        cfg = g_have_override ? g_override : default_pick(M, N);
+    }
+    const Variant *v = find_variant(cfg);
+    if (!v) return POLYDL_ERR_UNSUPPORTED;
+    // 32-bit byte offsets inside one workgroup's slice of A (bm rows) and of B (bk rows)
+    if ((uint64_t)v->bm * (uint64_t)K * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;
+    if ((uint64_t)v->bk * (uint64_t)N * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;
+    uint64_t tiles = (uint64_t)((M + v->bm - 1) / v->bm) * (uint64_t)((N + v->bn - 1) / v->bn);
+    if (tiles >= 0x7FFFFFFFull || cfg.split_k > 65535) return POLYDL_ERR_UNSUPPORTED;
+    SgemmProblem q{M, N, K, A, B, C};
+    hipError_t e = v->sgemm(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
+    if (e != hipSuccess) return POLYDL_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_last = cfg;
+    return POLYDL_OK;
+}
+
+static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                     const float *in, const float *wt, const float *bias, float *out, int act,
+                     void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+        return POLYDL_ERR_BAD_DIMENSION;
+    if (H + 2 * (int64_t)pad < R || W + 2 * (int64_t)pad < S) return POLYDL_ERR_BAD_DIMENSION;
+    const int64_t P = (H + 2 * (int64_t)pad - R) / stride + 1, Q = (W + 2 * (int64_t)pad - S) / stride + 1;
+    if (P <= 0 || Q <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!in || !wt || !out) return POLYDL_ERR_NULL_POINTER;
+    if (act != POLYDL_ACT_NONE && act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6)
+        return POLYDL_ERR_UNSUPPORTED;
+    // index ranges of the kernels: filter taps as bit masks, 32-bit pixel counts and offsets,
+    // exact magic division of reduction indices
+    const int64_t Kg = (int64_t)C * R * S, Ng = (int64_t)N * P * Q, CHW = (int64_t)C * H * W;
+    if (R > 32 || S > 32 || pad > 0x3FFFFF || stride > 0x3FFFFF) return POLYDL_ERR_UNSUPPORTED;
+    if (Ng >= 0x7FFF0000ll || Kg >= (1ll << 22) || Kg * R * S >= (1ll << 32)) return POLYDL_ERR_UNSUPPORTED;
+    polydl_tile_cfg cfg;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        cfg = g_have_override ? g_override : default_pick(K, Ng);
+    }
+    const Variant *v = find_variant(cfg);
+    if (!v || cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
+    // a tile of bn pixels spans at most bn/PQ + 2 images; their offsets must fit 31 bits
+    const int64_t span = (v->bn / (P * Q) + 2) * CHW * 4;
+    if (span >= 0x7FFFFFF0ll || (int64_t)v->bm * Kg * 4 >= 0x7FFFFFF0ll) return POLYDL_ERR_UNSUPPORTED;
+    if (cfg.split_k > 1 && act != POLYDL_ACT_NONE) return POLYDL_ERR_UNSUPPORTED;
+    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act};
+    hipError_t e = v->conv(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
+    if (e != hipSuccess) return POLYDL_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_last = cfg;
+    return POLYDL_OK;
+}
+
+}  // namespace polydl
+
+using namespace polydl;
+
+extern "C" {
+
+int polydl_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                      const float *in, const float *wt, const float *bias, float *out,
+                      int fuse_relu, void *stream)
+{
+    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out,
+                     fuse_relu ? POLYDL_ACT_RELU : POLYDL_ACT_NONE, stream);
+}
+
+int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                          const float *in, const float *wt, const float *bias, float *out, int act,
+                          void *stream)
+{
+    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, act, stream);
+}
+
+int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream)
+{
+    return sgemm_impl(M, N, K, A, B, C, stream);
+}
+
+int polydl_set_tile_override(const polydl_tile_cfg *cfg)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!cfg) {
+        g_have_override = false;
+        return POLYDL_OK;
+    }
+    if (!find_variant(*cfg) || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
+        cfg->raster > 1)
+        return POLYDL_ERR_UNSUPPORTED;
+    g_override = *cfg;
+    g_have_override = true;
+    return POLYDL_OK;
+}
+
+int polydl_get_last_tile(polydl_tile_cfg *cfg)
+{
+    if (!cfg) return POLYDL_ERR_NULL_POINTER;
+    std::lock_guard<std::mutex> lk(g_mu);
+    *cfg = g_last;
+    return POLYDL_OK;
+}
+
+int polydl_num_variants(int kind)
+{
+    return (kind == 0 || kind == 1) ? kNumVariants : POLYDL_ERR_UNSUPPORTED;
+}
+
+int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg)
+{
+    if (!cfg) return POLYDL_ERR_NULL_POINTER;
+    if ((kind != 0 && kind != 1) || index < 0 || index >= kNumVariants) return POLYDL_ERR_UNSUPPORTED;
+    cfg_of(kVariants[index], 1, 0, 0, cfg);
+    return POLYDL_OK;
+}
+
+const char *polydl_status_string(int status)
+{
+    switch (status) {
+    case POLYDL_OK: return "ok";
+    case POLYDL_ERR_NULL_POINTER: return "null pointer";
+    case POLYDL_ERR_BAD_DIMENSION: return "bad dimension";
+    case POLYDL_ERR_UNSUPPORTED: return "unsupported configuration";
+    case POLYDL_ERR_LAUNCH: return "HIP launch failed";
+    case POLYDL_ERR_NO_DEVICE: return "no device";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

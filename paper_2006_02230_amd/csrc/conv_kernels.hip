@@ -1,0 +1,240 @@
+// Forward convolution as an implicit GEMM on the fp32 matrix cores.
+//
+// The paper's convolution nest (figure "The 2-D Convolution code") contains a GEMM in its three
+// inner loops; here the whole nest is one GEMM  out[K][N*P*Q] = wt[K][C*R*S] * X[C*R*S][N*P*Q]
+// where X is the im2col view of the input, never materialised: its elements are gathered from
+// the NCHW tensor while the B stage is filled.  Rows (output channels) come from the KCRS filter
+// tensor, which already is a row-major K x (C*R*S) matrix.  Output columns (n, p, q) are
+// contiguous in NKPQ for a fixed channel, so the accumulator tile is stored without a transpose.
+// The element-wise tail (bias, ReLU / ReLU6) runs on the accumulators before the store: the
+// peeled last reduction iteration of algorithm "Perform operator fusion".
+#include "gemm_core.hpp"
+#include "internal.hpp"
+#include "variants.hpp"
+
+namespace polydl {
+
+struct ConvKArgs {
+    const float *in, *wt, *bias;
+    float *out;
+    int C, H, W, K, R, S, stride, pad, P, Q;
+    int PQ, RS, HW, CHW;
+    int Kg, Ng;                 // reduction length C*R*S, number of output pixels N*P*Q
+    uint32_t magic_RS, magic_S; // exact division of a reduction index by R*S and by S,
+    uint32_t one_RS, one_S;     // see fast_div(): magic multiplier and the all-ones mask for d == 1
+    uint64_t in_bytes;
+    int tiles_m, tiles_n;
+    int split_k, k_per_split;
+    int raster, act;
+};
+
+// ---- B operand: on-the-fly im2col gather from NCHW --------------------------------------------
+// A thread owns one output pixel (one column of the stage) for the whole reduction; per stage it
+// loads BK / (NT/BN) reduction rows of that column.  The reduction row is the same for all lanes
+// of a wave, so its split into (c, r, s) is scalar work.  Whether tap (r, s) falls inside the
+// image for this pixel is kept as one bit per filter row and per filter column.
+// n / d without a branch: (n * magic) >> 32 is exact for n*d < 2^32 when d > 1; for d == 1 the
+// magic is 0 and the all-ones mask passes n through.
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic, uint32_t ones_if_d1)
+{
+    return __umulhi(n, magic) + (n & ones_if_d1);
+}
+
+template <class T>
+struct BLoaderIm2col {
+    static constexpr int KSTEP = T::NT / T::BN;  // reduction rows covered by one pass of the workgroup
+    static constexpr int ITERS = T::BK / KSTEP;
+    static_assert(T::BK % KSTEP == 0, "stage depth must be a multiple of the rows loaded per pass");
+    float regs[ITERS];
+    __amdgpu_buffer_rsrc_t rsrc;
+    int pix_off;      // element offset of tap (0,0), channel 0 of this pixel from the descriptor base
+    uint32_t rmask, smask;
+    int krow0, lds_off;
+    int RS, S, HW, W;
+    uint32_t magic_RS, magic_S, one_RS, one_S;
+
+    __device__ __forceinline__ void init(const ConvKArgs &p, int tid, int n0)
+    {
+        RS = p.RS; S = p.S; HW = p.HW; W = p.W;
+        magic_RS = p.magic_RS; magic_S = p.magic_S; one_RS = p.one_RS; one_S = p.one_S;
+        const int col = tid % T::BN;
+        krow0 = __builtin_amdgcn_readfirstlane(tid / T::BN);
+        lds_off = krow0 * T::LDB + col;
+        // the descriptor starts at the first image this tile touches: offsets stay small
+        const int img0 = n0 / p.PQ;
+        const uint64_t skip = (uint64_t)img0 * p.CHW * 4;
+        rsrc = make_rsrc(reinterpret_cast<const char *>(p.in) + skip, p.in_bytes - skip);
+        const int colg = n0 + col;
+        rmask = 0; smask = 0; pix_off = 0;
+        if (colg < p.Ng) {
+            int img = colg / p.PQ, pq = colg - img * p.PQ;
+            int op = pq / p.Q, oq = pq - op * p.Q;
+            int ih0 = op * p.stride - p.pad, iw0 = oq * p.stride - p.pad;
+            pix_off = (img - img0) * p.CHW + ih0 * p.W + iw0;
+            for (int r = 0; r < p.R; ++r)
+                if (ih0 + r >= 0 && ih0 + r < p.H) rmask |= 1u << r;
+            for (int s = 0; s < p.S; ++s)
+                if (iw0 + s >= 0 && iw0 + s < p.W) smask |= 1u << s;
+        }
+    }
+    __device__ __forceinline__ void load(int k0, int kend)
+    {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            uint32_t kg = (uint32_t)(k0 + krow0 + i * KSTEP);  // wave-uniform
+            uint32_t c = fast_div(kg, magic_RS, one_RS);
+            uint32_t rs = kg - c * (uint32_t)RS;
+            uint32_t r = fast_div(rs, magic_S, one_S);
+            uint32_t s = rs - r * (uint32_t)S;
+            int koff = (int)c * HW + (int)r * W + (int)s;
+            uint32_t ok = (uint32_t)((int)kg < kend) & (rmask >> r) & (smask >> s) & 1u;
+            // not ok -> set the top bit: at or beyond 2^31 every descriptor reads as zero
+            uint32_t off = ((uint32_t)(pix_off + koff) * 4u) | ((ok ^ 1u) << 31);
+            regs[i] = buf_load1(rsrc, off);
+        }
+    }
+    __device__ __forceinline__ void store(float *Bs, int) const
+    {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) Bs[lds_off + i * KSTEP * T::LDB] = regs[i];
+    }
+};
+
+__device__ __forceinline__ float apply_act(float v, int act)
+{
+    if (act != POLYDL_ACT_NONE) v = fmaxf(v, 0.f);
+    if (act == POLYDL_ACT_RELU6) v = fminf(v, 6.f);
+    return v;
+}
+
+template <class T, int AVEC>
+__global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
+{
+    __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int tm, tn;
+    tile_coords(blockIdx.x, p.raster, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int wm0 = (wave % T::WAVES_M) * T::WM, wn0 = (wave / T::WAVES_M) * T::WN;
+    const int kbegin = blockIdx.y * p.k_per_split;
+    const int kend = min(p.Kg, kbegin + p.k_per_split);
+
+    ALoader<T, AVEC> al;
+    BLoaderIm2col<T> bl;
+    al.init(p.wt, tid, m0, p.K, p.Kg, p.Kg);
+    bl.init(p, tid, n0);
+
+    v16f acc[T::MB][T::NB];
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+
+    gemm_mainloop<T>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
+
+    // epilogue.  The lane owns NB adjacent pixels starting at colg for 16*MB output channels.
+    const int colg = n0 + wn0 + T::NB * (lane & 31);
+    if (colg >= p.Ng) return;
+    const int img = colg / p.PQ, pq = colg - img * p.PQ;
+    // the NB pixels are one vector store when they lie in one image and keep the alignment
+    const bool vec = (p.PQ % T::NB == 0) && (((uintptr_t)p.out & 15) == 0) && p.split_k == 1;
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int k = m0 + acc_row(wm0, bi, r, lane);
+            if (k >= p.K) continue;
+            const float b = p.bias ? p.bias[k] : 0.f;
+            float *o = p.out + ((size_t)img * p.K + k) * p.PQ + pq;
+            if (p.split_k > 1) {
+                // partial sums meet in a zero-filled output; bias joins through the first part,
+                // and an activation cannot be applied here (the launcher refuses that case)
+#pragma unroll
+                for (int bj = 0; bj < T::NB; ++bj) {
+                    int cg = colg + bj;
+                    if (cg >= p.Ng) break;
+                    int im = cg / p.PQ, q = cg - im * p.PQ;
+                    float v = acc[bi][bj][r] + (blockIdx.y == 0 ? b : 0.f);
+                    unsafeAtomicAdd(p.out + ((size_t)im * p.K + k) * p.PQ + q, v);
+                }
+            } else if (vec) {
+                if constexpr (T::NB == 4) {
+                    v4f v = {apply_act(acc[bi][0][r] + b, p.act), apply_act(acc[bi][1][r] + b, p.act),
+                             apply_act(acc[bi][2][r] + b, p.act), apply_act(acc[bi][3][r] + b, p.act)};
+                    *reinterpret_cast<v4f *>(o) = v;
+                } else if constexpr (T::NB == 2) {
+                    v2f v = {apply_act(acc[bi][0][r] + b, p.act), apply_act(acc[bi][1][r] + b, p.act)};
+                    *reinterpret_cast<v2f *>(o) = v;
+                } else {
+                    *o = apply_act(acc[bi][0][r] + b, p.act);
+                }
+            } else {
+#pragma unroll
+                for (int bj = 0; bj < T::NB; ++bj) {
+                    int cg = colg + bj;
+                    if (cg >= p.Ng) break;
+                    int im = cg / p.PQ, q = cg - im * p.PQ;
+                    p.out[((size_t)im * p.K + k) * p.PQ + q] = apply_act(acc[bi][bj][r] + b, p.act);
+                }
+            }
+        }
+}
+
+// Zero fill of the output before a split reduction (a kernel, not a memset node, so the call
+// sequence can be captured in a graph).
+__global__ void fill_zero_kernel(float *p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) p[i] = 0.f;
+}
+
+template <class T>
+static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hipStream_t stream)
+{
+    ConvKArgs a;
+    a.in = q.in; a.wt = q.wt; a.bias = q.bias; a.out = q.out;
+    a.C = q.C; a.H = q.H; a.W = q.W; a.K = q.K; a.R = q.R; a.S = q.S;
+    a.stride = q.stride; a.pad = q.pad; a.P = q.P; a.Q = q.Q;
+    a.PQ = q.P * q.Q; a.RS = q.R * q.S; a.HW = q.H * q.W; a.CHW = q.C * q.H * q.W;
+    a.Kg = q.C * q.R * q.S;
+    a.Ng = q.N * a.PQ;
+    a.magic_RS = div_magic((uint32_t)a.RS);
+    a.magic_S = div_magic((uint32_t)q.S);
+    a.one_RS = a.RS == 1 ? 0xFFFFFFFFu : 0u;
+    a.one_S = q.S == 1 ? 0xFFFFFFFFu : 0u;
+    a.in_bytes = (uint64_t)q.N * a.CHW * 4;
+    a.tiles_m = (q.K + T::BM - 1) / T::BM;
+    a.tiles_n = (a.Ng + T::BN - 1) / T::BN;
+    int stages = (a.Kg + T::BK - 1) / T::BK;
+    if (split_k < 1) split_k = 1;
+    if (split_k > stages) split_k = stages;
+    int stages_per = (stages + split_k - 1) / split_k;
+    a.k_per_split = stages_per * T::BK;
+    a.split_k = (stages + stages_per - 1) / stages_per;
+    a.raster = raster;
+    a.act = q.act;
+    if (a.split_k > 1) {
+        if (q.act != POLYDL_ACT_NONE) return hipErrorInvalidValue;
+        size_t n = (size_t)q.N * q.K * a.PQ;
+        unsigned blocks = (unsigned)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, q.out, n);
+    }
+    dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
+    const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
+    if (avec) hipLaunchKernelGGL((conv_kernel<T, 4>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((conv_kernel<T, 1>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+#define POLYDL_DEFINE_CONV(BM, BN, BK, WM, WN)                                                            \
+    hipError_t conv_launch_##BM##x##BN##x##BK##_##WM##x##WN(const ConvProblem &q, int s, int r,           \
+                                                            hipStream_t st)                              \
+    {                                                                                                    \
+        return conv_launch<Tile<BM, BN, BK, WM, WN>>(q, s, r, st);                                        \
+    }
+POLYDL_TILE_FAMILY(POLYDL_DEFINE_CONV)
+
+}  // namespace polydl

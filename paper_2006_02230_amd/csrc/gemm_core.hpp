@@ -1,0 +1,292 @@
+// Tiled matrix-core GEMM main loop shared by the SGEMM and implicit-GEMM convolution kernels.
+//
+// Structure (figure "A code version generated for PolyDL", section "GEMM"): the outer tiling
+// level is the workgroup tile BM x BN x BK staged through LDS, the inner level is the wave tile
+// WM x WN held in accumulator registers for the whole reduction -- the role of the register
+// resident microkernel of algorithm "The GEMM Microkernel" (load C once, a chain of rank-k
+// updates, store C once).  Each rank-2 update is one v_mfma_f32_32x32x2_f32.
+//
+// Operand order inside a stage: the microkernel may visit the reduction in any order as long as
+// both operands agree (section "Microkernel Specification": only the data set touched has to be
+// the same).  A lane therefore reads four consecutive k of A with one 128-bit LDS read and uses
+// them in four successive MFMAs; the lane's upper half (lane/32) takes the next four k.  B is
+// read with k-slot (lane/32)*4+t to match.  Columns are permuted the same way: one LDS read of
+// NB consecutive columns feeds the NB column blocks of the wave, so a lane ends up owning NB
+// adjacent output columns and the epilogue stores them as one vector.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace polydl {
+
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Offset that is out of range for every buffer descriptor built here (num_records < 2^31):
+// a raw buffer load at or beyond num_records returns zero, which is how padding, ragged tile
+// edges and the reduction tail are filled without branches.
+static constexpr uint32_t kOobOffset = 0x80000000u;
+static constexpr uint64_t kMaxRecords = 0x7FFFFFF0ull;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint64_t bytes)
+{
+    uint32_t rec = bytes > kMaxRecords ? (uint32_t)kMaxRecords : (uint32_t)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), (short)0, (int)rec, 0x00020000);
+}
+__device__ __forceinline__ float buf_load1(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0);
+}
+__device__ __forceinline__ v4f buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    v4i v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+    return __builtin_bit_cast(v4f, v);
+}
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
+    static constexpr int NT = WAVES_M * WAVES_N * 64;
+    static constexpr int MB = WM / 32, NB = WN / 32;  // 32x32 MFMA blocks per wave tile
+    static constexpr int LDA = BK + 4;                 // LDS row pitch of the A stage [BM][LDA]
+    static constexpr int LDB = BN + 4;                 // LDS row pitch of the B stage [BK][LDB]
+    static constexpr int A_STAGE = BM * LDA, B_STAGE = BK * LDB;
+    static constexpr int LDS_FLOATS = 2 * (A_STAGE + B_STAGE);
+    static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    static_assert(BK % 8 == 0, "a stage is consumed in chunks of 8 reduction elements");
+    static_assert(NB == 1 || NB == 2 || NB == 4, "column blocks per wave");
+    static_assert(BN % 64 == 0 && NT % BN == 0, "gather loaders: one column per thread");
+    static_assert(NT <= 512 && LDS_FLOATS * 4 <= 64 * 1024, "workgroup limits");
+};
+
+// ---- A operand: row-major [Mg][lda], reduction index contiguous ------------------------------
+// VEC = 4: 128-bit loads (needs lda % 4 == 0 and a 16-byte aligned base); VEC = 1: dword loads.
+// The descriptor is rebuilt per stage at A + m0*lda + k0, so offsets stay below BM*lda*4 bytes.
+template <class T, int VEC>
+struct ALoader {
+    static constexpr int UNITS = T::BM * T::BK / VEC;  // load units in one stage
+    static constexpr int ITERS = (UNITS + T::NT - 1) / T::NT;
+    static constexpr int UPR = T::BK / VEC;            // units per tile row
+    static constexpr bool RAGGED = UNITS % T::NT != 0;
+    const float *base;   // A + m0*lda
+    uint64_t bytes;      // bytes from base to the end of A
+    float regs[ITERS * VEC];
+    uint32_t off0[ITERS];  // byte offset of the unit at k0 = 0, or kOobOffset if its row is outside
+    int kcol[ITERS];       // first reduction index of the unit inside the stage
+    int lds_off[ITERS];
+
+    __device__ __forceinline__ void init(const float *A, int tid, int m0, int Mg, int Kg, int lda)
+    {
+        base = A + (size_t)m0 * lda;
+        bytes = ((size_t)(Mg - m0 - 1) * lda + Kg) * 4;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            int u = tid + i * T::NT;
+            int row = u / UPR, kc = (u % UPR) * VEC;
+            bool ok = (!RAGGED || u < UNITS) && (m0 + row < Mg);
+            off0[i] = ok ? ((uint32_t)row * (uint32_t)lda + (uint32_t)kc) * 4u : kOobOffset;
+            kcol[i] = kc;
+            lds_off[i] = row * T::LDA + kc;
+        }
+    }
+    // loads reduction indices [k0, k0+BK) of which only those below kend exist
+    __device__ __forceinline__ void load(int k0, int kend)
+    {
+        __amdgpu_buffer_rsrc_t rsrc = make_rsrc(base + k0, bytes - (uint64_t)k0 * 4);
+        int krem = kend - k0;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            uint32_t off = (kcol[i] < krem) ? off0[i] : kOobOffset;
+            if constexpr (VEC == 4) {
+                v4f v = buf_load4(rsrc, off);
+                regs[4 * i] = v.x; regs[4 * i + 1] = v.y; regs[4 * i + 2] = v.z; regs[4 * i + 3] = v.w;
+            } else {
+                regs[i] = buf_load1(rsrc, off);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(float *As, int tid) const
+    {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            if (RAGGED && tid + i * T::NT >= UNITS) continue;
+            if constexpr (VEC == 4) {
+                v4f v = {regs[4 * i], regs[4 * i + 1], regs[4 * i + 2], regs[4 * i + 3]};
+                *reinterpret_cast<v4f *>(As + lds_off[i]) = v;
+            } else {
+                As[lds_off[i]] = regs[i];
+            }
+        }
+    }
+};
+
+// ---- B operand of a plain GEMM: row-major [Kg][ldb], column index contiguous ------------------
+// VEC = 4: 128-bit loads along the columns (needs ldb % 4 == 0, Ng % 4 == 0, aligned base);
+// VEC = 1: dword loads.  The descriptor is rebuilt per stage at B + k0*ldb + n0.
+template <class T, int VEC>
+struct BLoaderRows {
+    static constexpr int UNITS = T::BK * T::BN / VEC;
+    static constexpr int ITERS = (UNITS + T::NT - 1) / T::NT;
+    static constexpr int UPR = T::BN / VEC;
+    static constexpr bool RAGGED = UNITS % T::NT != 0;
+    const float *base;  // B + n0
+    int Kg, ldb, ncols;  // ncols = Ng - n0
+    float regs[ITERS * VEC];
+    uint32_t off0[ITERS];
+    int krow[ITERS];
+    int lds_off[ITERS];
+
+    __device__ __forceinline__ void init(const float *B, int tid, int n0, int Ng, int Kg_, int ldb_)
+    {
+        base = B + n0;
+        Kg = Kg_;
+        ldb = ldb_;
+        ncols = Ng - n0;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            int u = tid + i * T::NT;
+            int kr = u / UPR, nc = (u % UPR) * VEC;
+            bool ok = (!RAGGED || u < UNITS) && (n0 + nc < Ng);
+            off0[i] = ok ? ((uint32_t)kr * (uint32_t)ldb + (uint32_t)nc) * 4u : kOobOffset;
+            krow[i] = kr;
+            lds_off[i] = kr * T::LDB + nc;
+        }
+    }
+    __device__ __forceinline__ void load(int k0, int kend)
+    {
+        // valid bytes from the stage's base: up to the last element of the last row of B
+        uint64_t bytes = ((uint64_t)(Kg - k0 - 1) * ldb + ncols) * 4;
+        __amdgpu_buffer_rsrc_t rsrc = make_rsrc(base + (size_t)k0 * ldb, bytes);
+        int krem = kend - k0;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            uint32_t off = (krow[i] < krem) ? off0[i] : kOobOffset;
+            if constexpr (VEC == 4) {
+                v4f v = buf_load4(rsrc, off);
+                regs[4 * i] = v.x; regs[4 * i + 1] = v.y; regs[4 * i + 2] = v.z; regs[4 * i + 3] = v.w;
+            } else {
+                regs[i] = buf_load1(rsrc, off);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(float *Bs, int tid) const
+    {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            if (RAGGED && tid + i * T::NT >= UNITS) continue;
+            if constexpr (VEC == 4) {
+                v4f v = {regs[4 * i], regs[4 * i + 1], regs[4 * i + 2], regs[4 * i + 3]};
+                *reinterpret_cast<v4f *>(Bs + lds_off[i]) = v;
+            } else {
+                Bs[lds_off[i]] = regs[i];
+            }
+        }
+    }
+};
+
+// ---- the MFMA stage: consume one LDS stage, WM x WN x BK per wave ----------------------------
+template <class T>
+__device__ __forceinline__ void mma_stage(const float *__restrict__ As, const float *__restrict__ Bs,
+                                          v16f (&acc)[T::MB][T::NB], int wm0, int wn0, int lane)
+{
+    const int li = lane & 31, lh = lane >> 5;
+#pragma unroll
+    for (int kc = 0; kc < T::BK / 8; ++kc) {
+        v4f a[T::MB];
+#pragma unroll
+        for (int bi = 0; bi < T::MB; ++bi)
+            a[bi] = *reinterpret_cast<const v4f *>(As + (wm0 + 32 * bi + li) * T::LDA + kc * 8 + 4 * lh);
+        float b[4][T::NB];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float *p = Bs + (kc * 8 + 4 * lh + t) * T::LDB + wn0 + T::NB * li;
+            if constexpr (T::NB == 4) {
+                v4f v = *reinterpret_cast<const v4f *>(p);
+                b[t][0] = v.x; b[t][1] = v.y; b[t][2] = v.z; b[t][3] = v.w;
+            } else if constexpr (T::NB == 2) {
+                v2f v = *reinterpret_cast<const v2f *>(p);
+                b[t][0] = v.x; b[t][1] = v.y;
+            } else {
+                b[t][0] = *p;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < T::NB; ++bj)
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi][t], b[t][bj], acc[bi][bj], 0, 0, 0);
+    }
+}
+
+// Software-pipelined reduction over [kbegin, kend): while the matrix cores work on LDS stage
+// t&1, the global loads of stage t+1 are in flight into registers; they are written to the other
+// LDS stage after the MFMAs were issued, and one barrier per step publishes them.  A loader that
+// runs past kend fills with zeros, so the last step needs no special case.
+template <class T, class AL, class BL>
+__device__ __forceinline__ void gemm_mainloop(float *lds, AL &al, BL &bl, v16f (&acc)[T::MB][T::NB],
+                                              int kbegin, int kend, int tid, int wm0, int wn0)
+{
+    float *As = lds;
+    float *Bs = lds + 2 * T::A_STAGE;
+    const int lane = tid & 63;
+    al.load(kbegin, kend);
+    bl.load(kbegin, kend);
+    al.store(As, tid);
+    bl.store(Bs, tid);
+    __syncthreads();
+    int cur = 0;
+    for (int k0 = kbegin; k0 < kend; k0 += T::BK) {
+        const bool more = k0 + T::BK < kend;  // workgroup-uniform
+        if (more) {
+            al.load(k0 + T::BK, kend);
+            bl.load(k0 + T::BK, kend);
+        }
+        mma_stage<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, acc, wm0, wn0, lane);
+        if (more) {
+            al.store(As + (cur ^ 1) * T::A_STAGE, tid);
+            bl.store(Bs + (cur ^ 1) * T::B_STAGE, tid);
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+}
+
+// Row (inside the workgroup tile) of accumulator register r of row block bi for this lane: a
+// 32x32 result keeps column lane%32 in every register and row 8*(r/4) + 4*(lane/32) + r%4 in
+// register r.  With the column permutation above the lane's NB blocks are the NB adjacent
+// columns starting at NB*(lane%32) of the wave tile.
+__device__ __forceinline__ int acc_row(int wm0, int bi, int r, int lane)
+{
+    return wm0 + 32 * bi + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+}
+
+// Workgroup index -> tile coordinates.  raster 0: tile rows fastest.  raster 1: the hardware
+// deals consecutive workgroups round-robin to the 8 XCDs, each with its own L2; give every XCD
+// one contiguous chunk of the tile sequence and walk the sequence in bands of 8 tile rows, so
+// that tiles resident together share A row panels and B column panels in that L2.
+__device__ __forceinline__ void tile_coords(int pid, int raster, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    if (raster == 1) {
+        const int XCD = 8, GROUP = 8;
+        int total = tiles_m * tiles_n;
+        int per = total / XCD, rem = total % XCD;
+        int x = pid % XCD, local = pid / XCD;
+        int seq = x * per + (x < rem ? x : rem) + local;
+        int band = GROUP * tiles_n;
+        int g = seq / band, first_m = g * GROUP;
+        int gsz = tiles_m - first_m < GROUP ? tiles_m - first_m : GROUP;
+        int in_band = seq - g * band;
+        tm = first_m + in_band % gsz;
+        tn = in_band / gsz;
+    } else {
+        tm = pid % tiles_m;
+        tn = pid / tiles_m;
+    }
+}
+
+}  // namespace polydl

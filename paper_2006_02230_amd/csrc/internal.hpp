@@ -1,0 +1,43 @@
+// Host-side declarations shared by the API file and the kernel files (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/polydl.h"
+
+namespace polydl {
+
+struct SgemmProblem {
+    int M, N, K;
+    const float *A, *B;
+    float *C;
+};
+
+struct ConvProblem {
+    int N, C, H, W, K, R, S, stride, pad, P, Q;
+    const float *in, *wt, *bias;
+    float *out;
+    int act;
+};
+
+// One compiled variant: its tile parameters and the launchers instantiated for it.
+struct Variant {
+    int bm, bn, bk, wm, wn;
+    int threads;
+    int lds_bytes;
+    hipError_t (*sgemm)(const SgemmProblem &, int split_k, int raster, hipStream_t);
+    hipError_t (*conv)(const ConvProblem &, int split_k, int raster, hipStream_t);
+};
+
+extern const Variant kVariants[];
+extern const int kNumVariants;
+
+// filled in by the kernel files
+#define POLYDL_DECLARE_LAUNCHERS(BM, BN, BK, WM, WN)                                                          \
+    hipError_t sgemm_launch_##BM##x##BN##x##BK##_##WM##x##WN(const SgemmProblem &, int, int, hipStream_t);     \
+    hipError_t conv_launch_##BM##x##BN##x##BK##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t);
+
+// Exact unsigned division by a runtime constant d for dividends n with n*d < 2^32:
+// n / d == (n * magic) >> 32 with magic = floor(2^32 / d) + 1.
+inline uint32_t div_magic(uint32_t d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
+
+}  // namespace polydl

@@ -1,0 +1,124 @@
+// SGEMM C += A*B on the fp32 matrix cores (figure "Matrix multiplication code", section
+// "Notation"; two-level tiling as in figure "A code version generated for PolyDL").
+#include "gemm_core.hpp"
+#include "internal.hpp"
+#include "variants.hpp"
+
+namespace polydl {
+
+struct SgemmKArgs {
+    const float *A, *B;
+    float *C;
+    int M, N, K;
+    int tiles_m, tiles_n;
+    int split_k, k_per_split;  // k_per_split is a multiple of the stage depth
+    int raster;
+};
+
+// AVEC / BVEC: 4 when the operand allows 128-bit loads, else 1.  CVEC: the lane's NB adjacent
+// output columns are read and written as one vector when N % NB == 0 and C is 16-byte aligned.
+template <class T, int AVEC, int BVEC, bool CVEC>
+__global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
+{
+    __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int tm, tn;
+    tile_coords(blockIdx.x, p.raster, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int wm0 = (wave % T::WAVES_M) * T::WM, wn0 = (wave / T::WAVES_M) * T::WN;
+    const int kbegin = blockIdx.y * p.k_per_split;
+    const int kend = min(p.K, kbegin + p.k_per_split);
+
+    ALoader<T, AVEC> al;
+    BLoaderRows<T, BVEC> bl;
+    al.init(p.A, tid, m0, p.M, p.K, p.K);
+    bl.init(p.B, tid, n0, p.N, p.K, p.N);
+
+    v16f acc[T::MB][T::NB];
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+
+    if (kbegin < kend) gemm_mainloop<T>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
+
+    // epilogue: C += acc.  With the reduction split over blockIdx.y the parts meet in C through
+    // float atomics (C already holds the caller's values, so no zero fill is needed).
+    const int col = n0 + wn0 + T::NB * (lane & 31);
+    const bool atomic = p.split_k > 1;
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            int row = m0 + acc_row(wm0, bi, r, lane);
+            if (row >= p.M) continue;
+            float *c = p.C + (size_t)row * p.N + col;
+            if (atomic) {
+#pragma unroll
+                for (int bj = 0; bj < T::NB; ++bj)
+                    if (col + bj < p.N) unsafeAtomicAdd(c + bj, acc[bi][bj][r]);
+            } else if (CVEC && T::NB == 4) {
+                if (col < p.N) {
+                    v4f v = *reinterpret_cast<v4f *>(c);
+                    v.x += acc[bi][0][r]; v.y += acc[bi][1][r]; v.z += acc[bi][2][r]; v.w += acc[bi][3][r];
+                    *reinterpret_cast<v4f *>(c) = v;
+                }
+            } else if (CVEC && T::NB == 2) {
+                if (col < p.N) {
+                    v2f v = *reinterpret_cast<v2f *>(c);
+                    v.x += acc[bi][0][r]; v.y += acc[bi][1][r];
+                    *reinterpret_cast<v2f *>(c) = v;
+                }
+            } else {
+#pragma unroll
+                for (int bj = 0; bj < T::NB; ++bj)
+                    if (col + bj < p.N) c[bj] += acc[bi][bj][r];
+            }
+        }
+}
+
+template <class T>
+static hipError_t sgemm_launch(const SgemmProblem &q, int split_k, int raster, hipStream_t stream)
+{
+    SgemmKArgs a;
+    a.A = q.A; a.B = q.B; a.C = q.C;
+    a.M = q.M; a.N = q.N; a.K = q.K;
+    a.tiles_m = (q.M + T::BM - 1) / T::BM;
+    a.tiles_n = (q.N + T::BN - 1) / T::BN;
+    int stages = (q.K + T::BK - 1) / T::BK;
+    if (split_k < 1) split_k = 1;
+    if (split_k > stages) split_k = stages > 0 ? stages : 1;
+    int stages_per = (stages + split_k - 1) / split_k;
+    if (stages_per < 1) stages_per = 1;
+    a.k_per_split = stages_per * T::BK;
+    split_k = stages > 0 ? (stages + stages_per - 1) / stages_per : 1;
+    a.split_k = split_k;
+    a.raster = raster;
+    dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k), block(T::NT);
+    const bool avec = (q.K % 4 == 0) && ((uintptr_t)q.A % 16 == 0);
+    const bool bvec = (q.N % 4 == 0) && ((uintptr_t)q.B % 16 == 0);
+    const bool cvec = (q.N % T::NB == 0) && ((uintptr_t)q.C % 16 == 0);
+#define POLYDL_GO(AV, BV, CV) hipLaunchKernelGGL((sgemm_kernel<T, AV, BV, CV>), grid, block, 0, stream, a)
+    if (avec && bvec && cvec) POLYDL_GO(4, 4, true);
+    else if (avec && bvec) POLYDL_GO(4, 4, false);
+    else if (avec && cvec) POLYDL_GO(4, 1, true);
+    else if (avec) POLYDL_GO(4, 1, false);
+    else if (bvec && cvec) POLYDL_GO(1, 4, true);
+    else if (bvec) POLYDL_GO(1, 4, false);
+    else if (cvec) POLYDL_GO(1, 1, true);
+    else POLYDL_GO(1, 1, false);
+#undef POLYDL_GO
+    return hipGetLastError();
+}
+
+#define POLYDL_DEFINE_SGEMM(BM, BN, BK, WM, WN)                                                            \
+    hipError_t sgemm_launch_##BM##x##BN##x##BK##_##WM##x##WN(const SgemmProblem &q, int s, int r,          \
+                                                             hipStream_t st)                              \
+    {                                                                                                     \
+        return sgemm_launch<Tile<BM, BN, BK, WM, WN>>(q, s, r, st);                                        \
+    }
+POLYDL_TILE_FAMILY(POLYDL_DEFINE_SGEMM)
+
+}  // namespace polydl

@@ -1,0 +1,145 @@
+"""GPU parity of polydl_conv2d_fwd against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import FP32_TOL, dev, host, sample_indices
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2006_02230_amd as p
+    yield p
+    p.set_tile_override(None)
+
+
+def run_conv(P, s, x, w, b=None, act=None):
+    return host(P.conv2d_fwd(dev(x), dev(w), dev(b), stride=s.stride, pad=s.pad, act=act))
+
+
+SMALL = [
+    synth.ConvShape("k3", 2, 8, 14, 14, 16, 3, 3, 1, 1),
+    synth.ConvShape("odd", 3, 5, 13, 9, 7, 3, 3, 1, 1),        # C*R*S = 45: dword filter loads
+    synth.ConvShape("s2", 2, 12, 17, 15, 70, 3, 3, 2, 1),
+    synth.ConvShape("7x7", 2, 3, 30, 30, 64, 7, 7, 2, 3),      # stem-like
+    synth.ConvShape("1x1", 3, 64, 7, 7, 130, 1, 1, 1, 0),      # P*Q = 49: odd pixel count
+    synth.ConvShape("1x1s2", 2, 32, 14, 14, 64, 1, 1, 2, 0),
+    synth.ConvShape("rect", 1, 4, 9, 20, 5, 2, 5, 1, 2),       # R != S, pad > (R-1)/2
+    synth.ConvShape("nopad", 1, 16, 12, 12, 32, 5, 5, 3, 0),
+    synth.ConvShape("tiny", 1, 1, 1, 1, 1, 1, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("s", SMALL, ids=lambda s: s.name)
+def test_all_variants_random(P, s):
+    x, w, b = synth.conv_inputs(s, seed=31, dist="normal", bias=True)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+    for v in P.variants(0):
+        for raster in (0, 1):
+            v.raster = raster
+            P.set_tile_override(v)
+            got = run_conv(P, s, x, w, b, act="relu")
+            assert got.shape == want.shape
+            err = oracle.scaled_error(got, want, ab)
+            assert err <= FP32_TOL, (v, err)
+    P.set_tile_override(None)
+
+
+@pytest.mark.parametrize("s", SMALL[:6], ids=lambda s: s.name)
+def test_all_variants_small_integers_exact(P, s):
+    x, w, b = synth.conv_inputs(s, seed=32, dist="ints", bias=True)
+    want, _ = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad)
+    for v in P.variants(0):
+        for split_k in (1, 2):
+            v.split_k = split_k
+            P.set_tile_override(v)
+            got = run_conv(P, s, x, w, b)
+            assert np.array_equal(got.astype(np.float64), want), v
+    P.set_tile_override(None)
+
+
+@pytest.mark.parametrize("s", SMALL[:7], ids=lambda s: s.name)
+def test_one_hot_filter_is_exact_shifted_copy(P, s):
+    x, _, _ = synth.conv_inputs(s, seed=33, dist="normal")
+    w = np.zeros((s.K, s.C, s.R, s.S), np.float32)
+    k0, c0, r0, s0 = s.K - 1, s.C // 2, s.R - 1, s.S // 2
+    w[k0, c0, r0, s0] = 1.0
+    want, _ = oracle.conv2d_fwd(x, w, stride=s.stride, pad=s.pad)
+    got = run_conv(P, s, x, w)
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+def test_activation_tails(P):
+    s = synth.ConvShape("act", 2, 16, 10, 10, 24, 3, 3, 1, 1)
+    x, w, b = synth.conv_inputs(s, seed=34, dist="uniform", bias=True)
+    w = w * 4.0   # make some outputs exceed 6
+    for act in (None, "relu", "relu6"):
+        want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1, act=act)
+        got = run_conv(P, s, x, w, b, act=act)
+        assert oracle.scaled_error(got, want, ab) <= FP32_TOL
+        if act == "relu6":
+            assert got.max() == 6.0 and got.min() == 0.0
+    # no bias pointer
+    want, ab = oracle.conv2d_fwd(x, w, stride=1, pad=1, act="relu")
+    assert oracle.scaled_error(run_conv(P, s, x, w, None, act="relu"), want, ab) <= FP32_TOL
+
+
+def test_config1_full_compare(P):
+    s = synth.CONFIG1
+    x, w, _ = synth.conv_inputs(s, seed=0, dist="uniform")
+    want, ab = oracle.conv2d_fwd(x, w, stride=s.stride, pad=s.pad)
+    got = run_conv(P, s, x, w)
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL
+
+
+@pytest.mark.parametrize("layer", range(8))
+def test_resnet_suite_full_size_sampled(P, layer):
+    # batch 32, the picker's own configuration (what the benchmark times); the oracle evaluates
+    # sampled outputs one by one
+    s = synth.RESNET50_SUITE(32)[layer]
+    x, w, b = synth.conv_inputs(s, seed=100 + layer, dist="normal", bias=True)
+    got = run_conv(P, s, x, w, b, act="relu")
+    Pq, Qq = synth.out_hw(s)
+    assert got.shape == (s.N, s.K, Pq, Qq)
+    idx = sample_indices(got.size, 30000, seed=layer)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu", at=idx)
+    assert oracle.scaled_error(got.ravel()[idx], want, ab) <= FP32_TOL
+    # property at full size: summing the output over channels equals convolving with the summed
+    # filter (linearity in the filter), checked without the activation on a second call
+    got0 = run_conv(P, s, x, w)
+    wsum = w.astype(np.float64).sum(axis=0, keepdims=True).astype(np.float32)
+    ref, refab = oracle.conv2d_fwd(x[:1], wsum, stride=s.stride, pad=s.pad)
+    tot = got0[:1].astype(np.float64).sum(axis=1, keepdims=True)
+    scale = np.abs(got0[:1]).astype(np.float64).sum(axis=1, keepdims=True) + refab
+    assert np.max(np.abs(tot - ref) / scale) <= 1e-4
+
+
+def test_split_k_random(P):
+    s = synth.ConvShape("split", 2, 64, 7, 7, 96, 3, 3, 1, 1)
+    x, w, b = synth.conv_inputs(s, seed=35, dist="normal", bias=True)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1)
+    for v in P.variants(0):
+        v.split_k = 4
+        P.set_tile_override(v)
+        got = run_conv(P, s, x, w, b)
+        assert oracle.scaled_error(got, want, ab) <= FP32_TOL, v
+    P.set_tile_override(None)
+
+
+def test_argument_errors(P):
+    import ctypes
+    z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
+    f = P.lib.polydl_conv2d_fwd
+    assert f(0, 1, 4, 4, 1, 3, 3, 1, 1, one, one, z, one, 0, z) == -2
+    assert f(1, 1, 4, 4, 1, 3, 3, 0, 1, one, one, z, one, 0, z) == -2
+    assert f(1, 1, 4, 4, 1, 3, 3, 1, -1, one, one, z, one, 0, z) == -2
+    assert f(1, 1, 2, 2, 1, 3, 3, 1, 0, one, one, z, one, 0, z) == -2   # no output pixel
+    assert f(1, 1, 4, 4, 1, 3, 3, 1, 1, z, one, z, one, 0, z) == -1
+    assert f(1, 1, 4, 4, 1, 3, 3, 1, 1, one, one, z, z, 0, z) == -1
+    assert P.lib.polydl_conv2d_fwd_act(1, 1, 4, 4, 1, 3, 3, 1, 1, one, one, z, one, 7, z) == -3

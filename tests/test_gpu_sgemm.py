@@ -1,0 +1,119 @@
+"""GPU parity of polydl_sgemm against the fp64 oracle (C += A.B, row-major)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import FP32_TOL, dev, host, sample_indices
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2006_02230_amd as p
+    yield p
+    p.set_tile_override(None)
+
+
+def run_sgemm(P, A, B, C0):
+    C = dev(C0.copy())
+    P.sgemm(dev(A), dev(B), C)
+    return host(C)
+
+
+def variant_ids(P):
+    return [(v.bm, v.bn, v.bk, v.wm, v.wn) for v in P.variants(1)]
+
+
+SHAPES = [(256, 256, 64), (200, 136, 75), (130, 260, 17), (64, 64, 8), (1, 1, 1), (33, 1000, 129),
+          (300, 70, 256), (129, 127, 1)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_all_variants_random(P, M, N, K):
+    A, B, C0 = synth.sgemm_inputs(M, N, K, seed=M + N + K, c0="random")
+    want, ab = oracle.gemm(A, B, C0)
+    for v in P.variants(1):
+        for split_k, raster in ((1, 0), (3, 1)):
+            v.split_k, v.raster = split_k, raster
+            P.set_tile_override(v)
+            got = run_sgemm(P, A, B, C0)
+            err = oracle.scaled_error(got, want, ab)
+            assert err <= FP32_TOL, (v, err)
+    P.set_tile_override(None)
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 384, 512), (131, 67, 300)])
+def test_all_variants_small_integers_exact(P, M, N, K):
+    # |a|,|b| <= 3 and K*9 < 2^24: every partial sum is exact in fp32 in any order
+    A, B, C0 = synth.sgemm_inputs(M, N, K, seed=5, dist="ints", c0="random")
+    want, _ = oracle.gemm(A, B, C0)
+    for v in P.variants(1):
+        for split_k in (1, 2):
+            v.split_k = split_k
+            P.set_tile_override(v)
+            got = run_sgemm(P, A, B, C0)
+            assert np.array_equal(got.astype(np.float64), want), v
+    P.set_tile_override(None)
+
+
+def test_identity_gives_exact_copy(P):
+    M = N = K = 192
+    A, _, C0 = synth.sgemm_inputs(M, N, K, seed=9, c0="random")
+    got = run_sgemm(P, A, np.eye(K, dtype=np.float32), np.zeros((M, N), np.float32))
+    assert np.array_equal(got, A)
+
+
+def test_unaligned_base_pointers(P):
+    # operands that start 4 bytes into an allocation take the dword-load paths
+    import torch
+    M, N, K = 96, 72, 40
+    A, B, C0 = synth.sgemm_inputs(M, N, K, seed=12, c0="random")
+    want, ab = oracle.gemm(A, B, C0)
+    bufA = torch.zeros(M * K + 1, device="cuda"); bufA[1:] = dev(A).ravel()
+    bufB = torch.zeros(K * N + 1, device="cuda"); bufB[1:] = dev(B).ravel()
+    bufC = torch.zeros(M * N + 1, device="cuda"); bufC[1:] = dev(C0).ravel()
+    import ctypes
+    st = P.lib.polydl_sgemm(M, N, K, ctypes.c_void_p(bufA.data_ptr() + 4), ctypes.c_void_p(bufB.data_ptr() + 4),
+                            ctypes.c_void_p(bufC.data_ptr() + 4), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert st == 0
+    got = host(bufC)[1:].reshape(M, N)
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL
+    assert host(bufC)[0] == 0.0
+
+
+@pytest.mark.parametrize("n", [256, 1024])
+def test_square_full_compare(P, n):
+    A, B, C0 = synth.sgemm_inputs(n, n, n, seed=n)
+    want, ab = oracle.gemm(A, B, C0)
+    got = run_sgemm(P, A, B, C0)
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL
+
+
+@pytest.mark.parametrize("n", [2048, 4096])
+def test_square_sampled_compare(P, n):
+    # full-size runs in the picker's own configuration; the oracle computes sampled elements
+    A, B, C0 = synth.sgemm_inputs(n, n, n, seed=n)
+    got = run_sgemm(P, A, B, C0)
+    idx = sample_indices(n * n, 20000, seed=n)
+    want, ab = oracle.gemm(A, B, C0, at=idx)
+    assert oracle.scaled_error(got.ravel()[idx], want, ab) <= FP32_TOL
+    # property that holds at any size: row sums of C equal A . (B . 1) to fp32 accumulation accuracy
+    rs = (A.astype(np.float64) @ B.astype(np.float64).sum(axis=1))
+    scale = (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64).sum(axis=1))
+    assert np.max(np.abs(got.astype(np.float64).sum(axis=1) - rs) / scale) <= FP32_TOL
+
+
+def test_argument_errors(P):
+    import ctypes
+    z = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)
+    assert P.lib.polydl_sgemm(0, 4, 4, one, one, one, z) == -2
+    assert P.lib.polydl_sgemm(4, -1, 4, one, one, one, z) == -2
+    assert P.lib.polydl_sgemm(4, 4, 4, z, one, one, z) == -1
+    assert P.lib.polydl_sgemm(4, 4, 4, one, one, z, z) == -1
+    assert P.lib.polydl_sgemm(4, 4, 0, z, z, one, z) == 0   # K = 0: nothing to add
