@@ -37,7 +37,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
 }
 __device__ __forceinline__ float buf_load1(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
 {
-    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0);
+    // the builtin returns the raw 32 bits as an integer
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
 }
 __device__ __forceinline__ v4f buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
 {
