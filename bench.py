@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time every compiled variant per layer")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-sgemm", action="store_true")
+    ap.add_argument("--layers", default="", help="comma list of suite layers to run (default: all eight); "
+                    "a subset is for profiling one kernel and changes the workload the line reports")
+    ap.add_argument("--tile", default="", help="force a variant bm,bn,bk,wm,wn[,split_k[,layout[,raster]]] (profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on one GPU; --gpus %d is not supported "
@@ -69,14 +72,22 @@ def main():
     torch.cuda.set_device(0)
 
     suite = synth.RESNET50_SUITE(args.batch)
+    chosen = [int(t) for t in args.layers.split(",") if t != ""] or list(range(len(suite)))
+    forced = None
+    if args.tile:
+        t = [int(v) for v in args.tile.split(",")]
+        t += [1, 0, 0][len(t) - 5:]
+        forced = P.TileCfg(*t)
     layers = []
     for i, s in enumerate(suite):
+        if i not in chosen:
+            continue
         x, w, b = synth.conv_inputs(s, seed=100 + i, dist="normal", bias=True)
         Pq, Qq = synth.out_hw(s)
         layers.append(dict(shape=s, P=Pq, Q=Qq, x=torch.from_numpy(x).cuda(), w=torch.from_numpy(w).cuda(),
                            b=torch.from_numpy(b).cuda(),
                            out=torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda"),
-                           flops=conv_flops(s, Pq, Qq), bytes=conv_bytes(s, Pq, Qq), host=(x, w, b)))
+                           index=i, flops=conv_flops(s, Pq, Qq), bytes=conv_bytes(s, Pq, Qq), host=(x, w, b)))
 
     def run_layer(L):
         s = L["shape"]
@@ -86,7 +97,7 @@ def main():
         for L in layers:
             run_layer(L)
 
-    P.set_tile_override(None)
+    P.set_tile_override(forced)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -105,7 +116,8 @@ def main():
     # per-layer kernel time: back-to-back launches of one layer between two events on the launch stream
     rows = []
     kern_ms_sum = 0.0
-    for i, L in enumerate(layers):
+    for L in layers:
+        i = L["index"]
         reps = 30
         ms = time_calls(torch, lambda L=L: run_layer(L), reps)
         tile = P.get_last_tile().as_dict()
@@ -119,18 +131,22 @@ def main():
         kern_ms_sum += ms
         if args.sweep:
             best = None
+            allv = []
             for v in P.variants(0):
-                for split_k in (1,):
-                    v.split_k = split_k
+                for cb in ((2, 4, 8, 16, 32) if v.algo == 1 else (0,)):
+                    v.cb = cb
                     try:
                         P.set_tile_override(v)
                         run_layer(L)
                         vms = time_calls(torch, lambda L=L: run_layer(L), 10)
                     except P.PolydlError:
                         continue
+                    allv.append((round(vms * 1e3, 2), "%dx%d/%dx%d a%d cb%d bk%d" % (
+                        v.bm, v.bn, v.wm, v.wn, v.algo, v.cb, v.bk)))
                     if best is None or vms < best[0]:
                         best = (vms, v.as_dict())
-            P.set_tile_override(None)
+            rows[-1]["sweep_all"] = sorted(allv)[:8]
+            P.set_tile_override(forced)
             rows[-1]["sweep_best_us"] = round(best[0] * 1e3, 2)
             rows[-1]["sweep_best_tile"] = best[1]
             rows[-1]["pick_over_best"] = round(best[0] / ms, 4)
@@ -171,8 +187,9 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "configs[2]: ResNet-50-shaped conv suite, fp32 NCHW, N=%d, 8 layers, "
-                               "in N(0,1), wt N(0,2/(CRS)), bias U[-0.1,0.1), ReLU" % args.batch,
+        "config": {"workload": "configs[2]: ResNet-50-shaped conv suite, fp32 NCHW, N=%d, layers %s, "
+                               "in N(0,1), wt N(0,2/(CRS)), bias U[-0.1,0.1), ReLU"
+                               % (args.batch, "0-7 (all eight)" if len(chosen) == 8 else str(chosen)),
                    "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,

@@ -54,6 +54,10 @@ typedef struct polydl_tile_cfg {
     int split_k;      /* >= 1: the reduction is cut into this many parts summed with atomics   */
     int layout;       /* 0: read NCHW / KCRS directly; 1: via blocked NCHWc / KCRSck copies    */
     int raster;       /* 0: workgroups walk M fastest; 1: chunked per XCD, grouped for L2 reuse */
+    int algo;         /* convolution only.  0: im2col columns gathered element by element from
+                         HBM (any shape); 1: input rows staged once per workgroup in LDS and the
+                         taps formed on the LDS read (bk is ignored, the stage is cb channels)  */
+    int cb;           /* algo 1: input channels per stage, even, >= 2; 0 lets the library choose */
 } polydl_tile_cfg;
 
 /* ---- forward convolution ------------------------------------------------------------------

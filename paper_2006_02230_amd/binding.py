@@ -22,7 +22,8 @@ class PolydlError(RuntimeError):
 
 class TileCfg(ctypes.Structure):
     """Mirror of polydl_tile_cfg."""
-    _fields_ = [(n, ctypes.c_int) for n in ("bm", "bn", "bk", "wm", "wn", "split_k", "layout", "raster")]
+    _fields_ = [(n, ctypes.c_int) for n in ("bm", "bn", "bk", "wm", "wn", "split_k", "layout", "raster",
+                                            "algo", "cb")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -105,8 +106,8 @@ def set_tile_override(cfg=None, **kw):
         _check(lib.polydl_set_tile_override(None), "polydl_set_tile_override")
         return
     if cfg is None:
-        cfg = TileCfg(kw["bm"], kw["bn"], kw["bk"], kw["wm"], kw["wn"], kw.get("split_k", 1),
-                      kw.get("layout", 0), kw.get("raster", 0))
+        cfg = TileCfg(kw["bm"], kw["bn"], kw.get("bk", 0), kw["wm"], kw["wn"], kw.get("split_k", 1),
+                      kw.get("layout", 0), kw.get("raster", 0), kw.get("algo", 0), kw.get("cb", 0))
     _check(lib.polydl_set_tile_override(ctypes.byref(cfg)), "polydl_set_tile_override")
 
 

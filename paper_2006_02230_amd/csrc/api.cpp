@@ -8,6 +8,7 @@
 namespace polydl {
 
 POLYDL_TILE_FAMILY(POLYDL_DECLARE_LAUNCHERS)
+POLYDL_PATCH_FAMILY(POLYDL_DECLARE_PATCH_LAUNCHER)
 
 #define POLYDL_VARIANT_ROW(BM, BN, BK, WM, WN)                                                     \
     {BM, BN, BK, WM, WN, (BM / WM) * (BN / WN) * 64, 2 * (BM * (BK + 4) + BK * (BN + 4)) * 4,      \
@@ -15,10 +16,15 @@ POLYDL_TILE_FAMILY(POLYDL_DECLARE_LAUNCHERS)
 const Variant kVariants[] = {POLYDL_TILE_FAMILY(POLYDL_VARIANT_ROW)};
 const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
+#define POLYDL_PATCH_ROW(BM, BN, BK, WM, WN) \
+    {BM, BN, WM, WN, (BM / WM) * (BN / WN) * 64, conv_patch_launch_##BM##x##BN##_##WM##x##WN},
+const PatchVariant kPatchVariants[] = {POLYDL_PATCH_FAMILY(POLYDL_PATCH_ROW)};
+const int kNumPatchVariants = (int)(sizeof(kPatchVariants) / sizeof(kPatchVariants[0]));
+
 static std::mutex g_mu;
 static bool g_have_override = false;
 static polydl_tile_cfg g_override;
-static polydl_tile_cfg g_last = {0, 0, 0, 0, 0, 0, 0, 0};
+static polydl_tile_cfg g_last = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
 static const Variant *find_variant(const polydl_tile_cfg &c)
 {
@@ -29,10 +35,67 @@ static const Variant *find_variant(const polydl_tile_cfg &c)
     return nullptr;
 }
 
+static const PatchVariant *find_patch_variant(const polydl_tile_cfg &c)
+{
+    for (int i = 0; i < kNumPatchVariants; ++i) {
+        const PatchVariant &v = kPatchVariants[i];
+        if (v.bm == c.bm && v.bn == c.bn && v.wm == c.wm && v.wn == c.wn) return &v;
+    }
+    return nullptr;
+}
+
 static void cfg_of(const Variant &v, int split_k, int layout, int raster, polydl_tile_cfg *c)
 {
     c->bm = v.bm; c->bn = v.bn; c->bk = v.bk; c->wm = v.wm; c->wn = v.wn;
     c->split_k = split_k; c->layout = layout; c->raster = raster;
+    c->algo = 0; c->cb = 0;
+}
+
+static void cfg_of_patch(const PatchVariant &v, int cb, int raster, polydl_tile_cfg *c)
+{
+    c->bm = v.bm; c->bn = v.bn; c->bk = 0; c->wm = v.wm; c->wn = v.wn;
+    c->split_k = 1; c->layout = 0; c->raster = raster;
+    c->algo = 1; c->cb = cb;
+}
+
+// Largest even channel count per stage the patch kernel can hold for this problem and tile,
+// preferring stages of at most 72 reduction elements; 0 if none fits.
+static int choose_cb(const PatchVariant &v, const ConvProblem &q)
+{
+    int cpad = (q.C + 1) & ~1;
+    int best = 0;
+    for (int cb = 2; cb <= cpad && cb <= 64; cb += 2) {
+        if (cpad % cb != 0 && cb != cpad) continue;
+        if (cb * q.R * q.S > 72 && best != 0) break;
+        if (v.conv(q, cb, 0, nullptr, true) == hipSuccess) best = cb;
+    }
+    return best;
+}
+
+// Placeholder choice for convolution until the reuse model is wired in: the patch tile with the
+// fewest wasted output-channel rows and at least two workgroups per compute unit.
+static bool default_conv_pick(const ConvProblem &q, polydl_tile_cfg *out)
+{
+    const long Ng = (long)q.N * q.P * q.Q;
+    const PatchVariant *best = nullptr;
+    double best_score = -1;
+    int best_cb = 0;
+    for (int i = 0; i < kNumPatchVariants; ++i) {
+        const PatchVariant &v = kPatchVariants[i];
+        int cb = choose_cb(v, q);
+        if (!cb) continue;
+        long tm = (q.K + v.bm - 1) / v.bm, tn = (Ng + v.bn - 1) / v.bn;
+        double useful = (double)q.K * Ng / ((double)tm * v.bm * tn * v.bn);
+        long tiles = tm * tn;
+        double waves = (double)tiles / 256.0;
+        double quant = waves / (double)((tiles + 255) / 256);
+        double wave_tile = (double)(v.wm * v.wn) / (64.0 * 64.0);
+        double score = useful * quant * (0.6 + 0.4 * (wave_tile > 1 ? 1 : wave_tile));
+        if (score > best_score) { best_score = score; best = &v; best_cb = cb; }
+    }
+    if (!best) return false;
+    cfg_of_patch(*best, best_cb, 0, out);
+    return true;
 }
 
 // Placeholder choice until the reuse model is wired in: the largest square-ish tile that still
@@ -97,18 +160,33 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     const int64_t Kg = (int64_t)C * R * S, Ng = (int64_t)N * P * Q, CHW = (int64_t)C * H * W;
     if (R > 32 || S > 32 || pad > 0x3FFFFF || stride > 0x3FFFFF) return POLYDL_ERR_UNSUPPORTED;
     if (Ng >= 0x7FFF0000ll || Kg >= (1ll << 22) || Kg * R * S >= (1ll << 32)) return POLYDL_ERR_UNSUPPORTED;
+    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act};
     polydl_tile_cfg cfg;
+    bool forced;
     {
         std::lock_guard<std::mutex> lk(g_mu);
-        cfg = g_have_override ? g_override : default_pick(K, Ng);
+        forced = g_have_override;
+        cfg = g_override;
+    }
+    if (!forced && !default_conv_pick(q, &cfg)) cfg = default_pick(K, Ng);
+    if (cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
+    if (cfg.algo == 1) {
+        const PatchVariant *pv = find_patch_variant(cfg);
+        if (!pv || cfg.split_k > 1) return POLYDL_ERR_UNSUPPORTED;
+        if (cfg.cb == 0) cfg.cb = choose_cb(*pv, q);
+        if (cfg.cb < 2 || (cfg.cb & 1)) return POLYDL_ERR_UNSUPPORTED;
+        if (pv->conv(q, cfg.cb, cfg.raster, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
+        if (pv->conv(q, cfg.cb, cfg.raster, (hipStream_t)stream, false) != hipSuccess) return POLYDL_ERR_LAUNCH;
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_last = cfg;
+        return POLYDL_OK;
     }
     const Variant *v = find_variant(cfg);
-    if (!v || cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
+    if (!v) return POLYDL_ERR_UNSUPPORTED;
     // a tile of bn pixels spans at most bn/PQ + 2 images; their offsets must fit 31 bits
     const int64_t span = (v->bn / (P * Q) + 2) * CHW * 4;
     if (span >= 0x7FFFFFF0ll || (int64_t)v->bm * Kg * 4 >= 0x7FFFFFF0ll) return POLYDL_ERR_UNSUPPORTED;
     if (cfg.split_k > 1 && act != POLYDL_ACT_NONE) return POLYDL_ERR_UNSUPPORTED;
-    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act};
     hipError_t e = v->conv(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
     if (e != hipSuccess) return POLYDL_ERR_LAUNCH;
     std::lock_guard<std::mutex> lk(g_mu);
@@ -149,8 +227,10 @@ int polydl_set_tile_override(const polydl_tile_cfg *cfg)
         g_have_override = false;
         return POLYDL_OK;
     }
-    if (!find_variant(*cfg) || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
-        cfg->raster > 1)
+    const bool known = cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
+                                      : (cfg->algo == 0 && find_variant(*cfg) != nullptr);
+    if (!known || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
+        cfg->raster > 1 || cfg->cb < 0 || (cfg->cb & 1))
         return POLYDL_ERR_UNSUPPORTED;
     g_override = *cfg;
     g_have_override = true;
@@ -167,14 +247,16 @@ int polydl_get_last_tile(polydl_tile_cfg *cfg)
 
 int polydl_num_variants(int kind)
 {
-    return (kind == 0 || kind == 1) ? kNumVariants : POLYDL_ERR_UNSUPPORTED;
+    if (kind == 0) return kNumVariants + kNumPatchVariants;
+    return kind == 1 ? kNumVariants : POLYDL_ERR_UNSUPPORTED;
 }
 
 int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg)
 {
     if (!cfg) return POLYDL_ERR_NULL_POINTER;
-    if ((kind != 0 && kind != 1) || index < 0 || index >= kNumVariants) return POLYDL_ERR_UNSUPPORTED;
-    cfg_of(kVariants[index], 1, 0, 0, cfg);
+    if ((kind != 0 && kind != 1) || index < 0 || index >= polydl_num_variants(kind)) return POLYDL_ERR_UNSUPPORTED;
+    if (index < kNumVariants) cfg_of(kVariants[index], 1, 0, 0, cfg);
+    else cfg_of_patch(kPatchVariants[index - kNumVariants], 0, 0, cfg);
     return POLYDL_OK;
 }
 

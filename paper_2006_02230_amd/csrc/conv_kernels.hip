@@ -45,7 +45,7 @@ struct BLoaderIm2col {
     static constexpr int KSTEP = T::NT / T::BN;  // reduction rows covered by one pass of the workgroup
     static constexpr int ITERS = T::BK / KSTEP;
     static_assert(T::BK % KSTEP == 0, "stage depth must be a multiple of the rows loaded per pass");
-    float regs[ITERS];
+    float regs[2][ITERS];
     __amdgpu_buffer_rsrc_t rsrc;
     int pix_off;      // element offset of tap (0,0), channel 0 of this pixel from the descriptor base
     uint32_t rmask, smask;
@@ -77,6 +77,7 @@ struct BLoaderIm2col {
                 if (iw0 + s >= 0 && iw0 + s < p.W) smask |= 1u << s;
         }
     }
+    template <int SET>
     __device__ __forceinline__ void load(int k0, int kend)
     {
 #pragma unroll
@@ -90,13 +91,14 @@ struct BLoaderIm2col {
             uint32_t ok = (uint32_t)((int)kg < kend) & (rmask >> r) & (smask >> s) & 1u;
             // not ok -> set the top bit: at or beyond 2^31 every descriptor reads as zero
             uint32_t off = ((uint32_t)(pix_off + koff) * 4u) | ((ok ^ 1u) << 31);
-            regs[i] = buf_load1(rsrc, off);
+            regs[SET][i] = buf_load1(rsrc, off);
         }
     }
+    template <int SET>
     __device__ __forceinline__ void store(float *Bs, int) const
     {
 #pragma unroll
-        for (int i = 0; i < ITERS; ++i) Bs[lds_off + i * KSTEP * T::LDB] = regs[i];
+        for (int i = 0; i < ITERS; ++i) Bs[lds_off + i * KSTEP * T::LDB] = regs[SET][i];
     }
 };
 

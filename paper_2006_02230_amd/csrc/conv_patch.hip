@@ -1,0 +1,398 @@
+// Forward convolution on the fp32 matrix cores with the input staged through LDS as row patches.
+//
+// Same GEMM view as conv_kernels.hip: out[K][N*P*Q] = wt[K][C*R*S] * X[C*R*S][N*P*Q].  Here the
+// im2col matrix X is not gathered element by element from HBM.  A workgroup owns BN consecutive
+// output pixels (a run of output rows, possibly crossing into the next images); per stage it
+// copies, for CB input channels, exactly the input rows those pixels need into LDS, each row
+// widened by the zero padding so no tap ever needs a bounds test.  The R*S taps are then formed
+// while the matrix-core operand is read from LDS: a lane's pixel has one base address in the
+// patch and tap (r, s) of channel c is at a wave-uniform offset from it.  Every input element is
+// fetched from HBM/L2 once per workgroup instead of once per tap -- the reuse the paper's outer
+// loop tiling is after (section "Working set size computation": a reuse is realised when the
+// data touched between source and target iteration stays in the fast memory).
+//
+// Reduction order inside a stage: channel pairs outermost, then filter row, filter column.  One
+// v_mfma_f32_32x32x2_f32 consumes one tap of one channel pair: lanes 0-31 carry the even
+// channel, lanes 32-63 the odd one.  The filter rows of the workgroup's BM output channels are
+// copied as they lie in KCRS (C*R*S contiguous per output channel); the LDS row pitch is odd so
+// that 32 lanes reading one column of 32 rows hit 32 different banks.
+#include "gemm_core.hpp"
+#include "internal.hpp"
+#include "variants.hpp"
+
+namespace polydl {
+
+struct ConvPatchKArgs {
+    const float *in, *wt, *bias;
+    float *out;
+    int C, H, W, K, R, S, stride, pad, P, Q;
+    int PQ, RS, HW, CHW, Kg, Ng;
+    int Wp;          // W + 2*pad: pitch of a patch row
+    int CB;          // input channels per stage (even)
+    int nstages;     // ceil(C / CB)
+    int D;           // CB*R*S: reduction elements per stage
+    int LDA;         // LDS pitch of a filter row: D + 1 (odd, so a column read has no bank conflict)
+    int rows_full;   // input rows one whole image contributes: (P-1)*stride + R
+    int a_stage;     // floats reserved per LDS filter stage (BM*LDA rounded up to the workgroup size)
+    int b_stage;     // floats reserved per LDS patch stage (rounded up likewise)
+    uint32_t magic_Wp, one_Wp, magic_rf, one_rf, magic_lda;
+    uint64_t in_bytes, wt_bytes;
+    int tiles_m, tiles_n, raster, act;
+};
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic, uint32_t ones_if_d1)
+{
+    return __umulhi(n, magic) + (n & ones_if_d1);
+}
+
+__device__ __forceinline__ float act_apply(float v, int act)
+{
+    if (act != POLYDL_ACT_NONE) v = fmaxf(v, 0.f);
+    if (act == POLYDL_ACT_RELU6) v = fminf(v, 6.f);
+    return v;
+}
+
+// One channel pair of a stage: R*S taps, each one rank-2 update of every accumulator block.
+// With the filter size known at compile time (RC, SC > 0) the taps are unrolled, so the LDS
+// reads of later taps are in flight while the matrix cores work on earlier ones.
+template <class T, int RC, int SC>
+__device__ __forceinline__ void patch_pair(const float *__restrict__ A, const float *__restrict__ B,
+                                           const int (&a_base)[T::MB], const int (&b_base)[T::NB],
+                                           int ka, int kb, int R, int S, int Wp, v16f (&acc)[T::MB][T::NB])
+{
+    constexpr int MB = T::MB, NB = T::NB;
+    if constexpr (RC > 0) {
+#pragma unroll
+        for (int r = 0; r < RC; ++r)
+#pragma unroll
+            for (int s = 0; s < SC; ++s) {
+                float fa[MB], fb[NB];
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi) fa[bi] = A[a_base[bi] + ka + r * SC + s];
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj) fb[bj] = B[b_base[bj] + kb + r * Wp + s];
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+                    for (int bj = 0; bj < NB; ++bj)
+                        acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
+            }
+    } else {
+        for (int r = 0; r < R; ++r) {
+            for (int s = 0; s < S; ++s) {
+                float fa[MB], fb[NB];
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi) fa[bi] = A[a_base[bi] + ka];
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj) fb[bj] = B[b_base[bj] + kb + s];
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+                    for (int bj = 0; bj < NB; ++bj)
+                        acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
+                ++ka;
+            }
+            kb += Wp;
+        }
+    }
+}
+
+// Loads go straight from HBM/L2 into LDS (buffer_load ... lds): lane i of a wave instruction
+// fills LDS dword base + i, so a workgroup-wide pass fills NT consecutive dwords and the LDS
+// image is simply "dword e of the stage" for e = thread + pass*NT.  No staging registers, no
+// ds_write, and the data of stage t+1 streams in while the matrix cores work on stage t.
+// Out-of-range lanes (padding, rows outside the image, channel or filter tails) read as zero.
+// MAXA / MAXP: passes a thread may need for the filter block / the input patch of one stage.
+// RC, SC: filter size when known at compile time, 0 for any size.
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+template <class T, int MAXA, int MAXP, int RC, int SC>
+__global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    constexpr int NT = T::NT, MB = T::MB, NB = T::NB;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lh = lane >> 5;
+    int tm, tn;
+    tile_coords(blockIdx.x, p.raster, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int wm0 = (wave % T::WAVES_M) * T::WM, wn0 = (wave / T::WAVES_M) * T::WN;
+
+    // ---- geometry of this workgroup's pixel run (uniform) ---------------------------------
+    const int nlast = min(n0 + T::BN, p.Ng) - 1;
+    const int img_a = n0 / p.PQ, p_a = (n0 - img_a * p.PQ) / p.Q;
+    const int img_b = nlast / p.PQ, p_b = (nlast - img_b * p.PQ) / p.Q;
+    int nrows0, total_rows;
+    if (img_a == img_b) {
+        nrows0 = (p_b - p_a) * p.stride + p.R;
+        total_rows = nrows0;
+    } else {
+        nrows0 = (p.P - 1 - p_a) * p.stride + p.R;
+        total_rows = nrows0 + (img_b - img_a - 1) * p.rows_full + p_b * p.stride + p.R;
+    }
+    const int ihb0 = p_a * p.stride - p.pad;       // first input row held for the first image
+    const int chs = total_rows * p.Wp;             // patch floats per channel
+    const int patch_elems = p.CB * chs;
+    const uint32_t magic_chs = chs > 1 ? 0xFFFFFFFFu / (uint32_t)chs + 1u : 0u;
+    const uint32_t one_chs = chs > 1 ? 0u : 0xFFFFFFFFu;
+
+    const int a_stage = p.a_stage;                 // floats: BM rows of pitch LDA, rounded up to NT
+    float *As = lds;                               // [2][a_stage]
+    float *Bs = lds + 2 * a_stage;                 // [2][b_stage]
+    const int a_elems = T::BM * p.LDA;
+
+    // ---- per-thread patch elements: LDS dword e <-> one input element or a zero -------------
+    uint32_t p_goff[MAXP];
+#pragma unroll
+    for (int i = 0; i < MAXP; ++i) {
+        uint32_t e = (uint32_t)(tid + i * NT);
+        uint32_t c_l = fdiv(e, magic_chs, one_chs);
+        uint32_t rem = e - c_l * (uint32_t)chs;
+        uint32_t row = fdiv(rem, p.magic_Wp, p.one_Wp);
+        int col = (int)(rem - row * (uint32_t)p.Wp);
+        int ii = 0, rr = (int)row, ihb = ihb0;
+        if ((int)row >= nrows0) {
+            uint32_t d = row - (uint32_t)nrows0;
+            uint32_t j = fdiv(d, p.magic_rf, p.one_rf);
+            ii = 1 + (int)j;
+            rr = (int)(d - j * (uint32_t)p.rows_full);
+            ihb = -p.pad;
+        }
+        int ih = ihb + rr, iw = col - p.pad;
+        bool ok = ((int)e < patch_elems) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+        p_goff[i] = ok ? (uint32_t)(((ii * p.C + (int)c_l) * p.HW + ih * p.W + iw) * 4) : kOobOffset;
+    }
+
+    // ---- per-thread filter elements: LDS dword e = m*LDA + kk <-> wt[m0+m][k0+kk] ------------
+    uint32_t a_goff[MAXA];
+#pragma unroll
+    for (int i = 0; i < MAXA; ++i) {
+        uint32_t e = (uint32_t)(tid + i * NT);
+        uint32_t m = fdiv(e, p.magic_lda, 0u);
+        int kk = (int)(e - m * (uint32_t)p.LDA);
+        bool ok = (int)e < a_elems && m0 + (int)m < p.K && kk < p.D;
+        a_goff[i] = ok ? (uint32_t)(((int)m * p.Kg + kk) * 4) : kOobOffset;
+    }
+
+    // ---- per-lane operand bases ---------------------------------------------------------------
+    // filter operand: row wm0 + 32*bi + lane%32, column offset (lane/32)*RS selects the odd channel
+    int a_base[MB];
+#pragma unroll
+    for (int bi = 0; bi < MB; ++bi) a_base[bi] = (wm0 + 32 * bi + li) * p.LDA + lh * p.RS;
+    // pixel operand: the lane's NB blocks are NB adjacent pixels (so the epilogue stores them as
+    // one vector); patch position of tap (0,0), channel parity lane/32
+    int b_base[NB];
+    int px_img[NB], px_pq[NB];
+#pragma unroll
+    for (int bj = 0; bj < NB; ++bj) {
+        int colg = n0 + wn0 + NB * li + bj;
+        int base = 0;
+        px_img[bj] = -1;
+        px_pq[bj] = 0;
+        if (colg < p.Ng) {
+            int img = colg / p.PQ, pq = colg - img * p.PQ;
+            int op = pq / p.Q, oq = pq - op * p.Q;
+            int ii = img - img_a;
+            int slot0 = ii == 0 ? 0 : nrows0 + (ii - 1) * p.rows_full;
+            int ihb = ii == 0 ? ihb0 : -p.pad;
+            base = (slot0 + op * p.stride - p.pad - ihb) * p.Wp + oq * p.stride;
+            px_img[bj] = img;
+            px_pq[bj] = pq;
+        }
+        b_base[bj] = base + lh * chs;
+    }
+
+    v16f acc[MB][NB];
+#pragma unroll
+    for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+
+    auto load_stage = [&](int t, int buf) {
+        const int c0 = t * p.CB;
+        const int k0 = c0 * p.RS;
+        const int krem = p.Kg - k0;     // reduction elements that exist from k0 on
+        const int crem = p.C - c0;      // channels that exist from c0 on
+        const uint64_t a_skip = ((uint64_t)m0 * p.Kg + k0) * 4;
+        __amdgpu_buffer_rsrc_t ra = make_rsrc(reinterpret_cast<const char *>(p.wt) + a_skip, p.wt_bytes - a_skip);
+        float *A = As + buf * a_stage + wave * 64;
+#pragma unroll
+        for (int i = 0; i < MAXA; ++i)
+            if (i * NT < a_elems) {
+                uint32_t off = a_goff[i];
+                if (krem < p.D) {       // last stage of a channel count that is no multiple of CB
+                    uint32_t e = (uint32_t)(tid + i * NT);
+                    uint32_t m = fdiv(e, p.magic_lda, 0u);
+                    int kk = (int)(e - m * (uint32_t)p.LDA);
+                    off = kk < krem ? off : kOobOffset;
+                }
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(A + i * NT), 4, (int)off, 0, 0, 0);
+            }
+        const uint64_t b_skip = ((uint64_t)img_a * p.C + c0) * p.HW * 4;
+        __amdgpu_buffer_rsrc_t rb = make_rsrc(reinterpret_cast<const char *>(p.in) + b_skip, p.in_bytes - b_skip);
+        float *B = Bs + buf * p.b_stage + wave * 64;
+#pragma unroll
+        for (int i = 0; i < MAXP; ++i)
+            if (i * NT < patch_elems) {
+                uint32_t off = p_goff[i];
+                if (crem < p.CB) {
+                    uint32_t c_l = fdiv((uint32_t)(tid + i * NT), magic_chs, one_chs);
+                    off = (int)c_l < crem ? off : kOobOffset;
+                }
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr_t)(B + i * NT), 4, (int)off, 0, 0, 0);
+            }
+    };
+
+    const int npairs = p.CB >> 1;
+
+    load_stage(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's direct-to-LDS loads have landed
+    __syncthreads();
+    for (int t = 0; t < p.nstages; ++t) {
+        const int buf = t & 1;
+        // buffer buf^1 was last read in stage t-1, which every wave has left (barrier below)
+        if (t + 1 < p.nstages) load_stage(t + 1, buf ^ 1);
+
+        const float *A = As + buf * a_stage;
+        const float *B = Bs + buf * p.b_stage;
+        if constexpr (RC == 1 && SC == 1) {
+            // 1x1 filters: a pair is a single tap, so unroll over pairs instead
+            int cp = 0;
+            for (; cp + 4 <= npairs; cp += 4) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    patch_pair<T, 1, 1>(A, B, a_base, b_base, (cp + u) * 2, (cp + u) * 2 * chs, 1, 1, p.Wp, acc);
+            }
+            for (; cp < npairs; ++cp)
+                patch_pair<T, 1, 1>(A, B, a_base, b_base, cp * 2, cp * 2 * chs, 1, 1, p.Wp, acc);
+        } else {
+            for (int cp = 0; cp < npairs; ++cp)
+                patch_pair<T, RC, SC>(A, B, a_base, b_base, cp * 2 * p.RS, cp * 2 * chs, p.R, p.S, p.Wp, acc);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+    }
+
+    // ---- epilogue: bias, activation, store NKPQ ------------------------------------------------
+    // The lane's NB pixels are one vector store when they lie in one image and keep the alignment.
+    // A lane holds 16*MB output channels; their biases are fetched together before any store.
+    const bool vec = NB > 1 && (p.PQ % NB == 0) && (((uintptr_t)p.out & 15) == 0);
+    const bool full_rows = m0 + T::BM <= p.K;   // uniform: no channel of this tile is outside K
+    float bias[MB][16];
+#pragma unroll
+    for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int k = m0 + acc_row(wm0, bi, r, lane);
+            bias[bi][r] = (p.bias && (full_rows || k < p.K)) ? p.bias[k] : 0.f;
+        }
+    if (px_img[0] >= 0) {
+        // element offset of channel 0 for the lane's first pixel; channel k adds k*PQ
+        const size_t obase = (size_t)px_img[0] * p.K * p.PQ + px_pq[0];
+#pragma unroll
+        for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = m0 + acc_row(wm0, bi, r, lane);
+                if (!full_rows && k >= p.K) continue;
+                const float b = bias[bi][r];
+                float *o = p.out + obase + (size_t)k * p.PQ;
+                if (vec && px_img[NB - 1] >= 0) {
+                    if constexpr (NB == 4) {
+                        v4f v = {act_apply(acc[bi][0][r] + b, p.act), act_apply(acc[bi][1][r] + b, p.act),
+                                 act_apply(acc[bi][2][r] + b, p.act), act_apply(acc[bi][3][r] + b, p.act)};
+                        *reinterpret_cast<v4f *>(o) = v;
+                    } else if constexpr (NB == 2) {
+                        v2f v = {act_apply(acc[bi][0][r] + b, p.act), act_apply(acc[bi][1][r] + b, p.act)};
+                        *reinterpret_cast<v2f *>(o) = v;
+                    }
+                } else {
+                    o[0] = act_apply(acc[bi][0][r] + b, p.act);
+#pragma unroll
+                    for (int bj = 1; bj < NB; ++bj)
+                        if (px_img[bj] >= 0)
+                            p.out[((size_t)px_img[bj] * p.K + k) * p.PQ + px_pq[bj]] =
+                                act_apply(acc[bi][bj][r] + b, p.act);
+                }
+            }
+    }
+}
+
+// Input rows a run of bn consecutive output pixels can need at most (all images it touches).
+static int patch_rows_bound(const ConvProblem &q, int bn)
+{
+    const long PQ = (long)q.P * q.Q, Ng = (long)q.N * PQ;
+    long run = bn < Ng ? bn : Ng;
+    long rows_out = (run - 1 + q.Q - 1) / q.Q + 1;
+    if (rows_out > (long)q.N * q.P) rows_out = (long)q.N * q.P;
+    long imgs = (run - 1 + PQ - 1) / PQ + 1;
+    if (imgs > q.N) imgs = q.N;
+    long extra = q.R > q.stride ? q.R - q.stride : 0;
+    long bound = rows_out * q.stride + imgs * extra;
+    if (q.R < q.stride) bound = (rows_out - 1) * q.stride + q.R > bound ? (rows_out - 1) * q.stride + q.R : bound;
+    return (int)bound;
+}
+
+template <class T, int MAXA, int MAXP>
+static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int raster, hipStream_t stream, bool dry)
+{
+    ConvPatchKArgs a;
+    a.in = q.in; a.wt = q.wt; a.bias = q.bias; a.out = q.out;
+    a.C = q.C; a.H = q.H; a.W = q.W; a.K = q.K; a.R = q.R; a.S = q.S;
+    a.stride = q.stride; a.pad = q.pad; a.P = q.P; a.Q = q.Q;
+    a.PQ = q.P * q.Q; a.RS = q.R * q.S; a.HW = q.H * q.W; a.CHW = q.C * q.H * q.W;
+    a.Kg = q.C * a.RS;
+    a.Ng = q.N * a.PQ;
+    a.Wp = q.W + 2 * q.pad;
+    a.CB = cb;
+    a.nstages = (q.C + cb - 1) / cb;
+    a.D = cb * a.RS;
+    a.LDA = a.D + 1;   // D is even (cb is), so the pitch is odd and at least 3
+    a.rows_full = (q.P - 1) * q.stride + q.R;
+    const int rows_alloc = patch_rows_bound(q, T::BN);
+    a.a_stage = (T::BM * a.LDA + T::NT - 1) / T::NT * T::NT;
+    a.b_stage = (cb * rows_alloc * a.Wp + T::NT - 1) / T::NT * T::NT;
+    a.magic_Wp = div_magic((uint32_t)a.Wp); a.one_Wp = a.Wp == 1 ? 0xFFFFFFFFu : 0u;
+    a.magic_rf = div_magic((uint32_t)a.rows_full); a.one_rf = a.rows_full == 1 ? 0xFFFFFFFFu : 0u;
+    a.magic_lda = div_magic((uint32_t)a.LDA);
+    a.in_bytes = (uint64_t)q.N * a.CHW * 4;
+    a.wt_bytes = (uint64_t)q.K * a.Kg * 4;
+    a.tiles_m = (q.K + T::BM - 1) / T::BM;
+    a.tiles_n = (a.Ng + T::BN - 1) / T::BN;
+    a.raster = raster;
+    a.act = q.act;
+    // what one thread may hold, and the LDS a workgroup may take
+    if ((long)a.a_stage > (long)MAXA * T::NT) return hipErrorInvalidConfiguration;
+    if ((long)a.b_stage > (long)MAXP * T::NT) return hipErrorInvalidConfiguration;
+    const size_t lds_bytes = (size_t)2 * ((size_t)a.a_stage + a.b_stage) * 4;
+    if (lds_bytes > 64 * 1024) return hipErrorInvalidConfiguration;
+    // 31-bit byte offsets: filter rows of one tile, and the images one pixel run touches
+    const long PQl = a.PQ;
+    const long imgs = (T::BN - 1 + PQl - 1) / PQl + 1;
+    if ((long)T::BM * a.Kg * 4 >= 0x7FFFFFF0l || (imgs * q.C + cb) * (long)a.HW * 4 >= 0x7FFFFFF0l)
+        return hipErrorInvalidConfiguration;
+    if (dry) return hipSuccess;
+    dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(T::NT);
+    if (q.R == 1 && q.S == 1)
+        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 1, 1>), grid, block, lds_bytes, stream, a);
+    else if (q.R == 3 && q.S == 3)
+        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 3, 3>), grid, block, lds_bytes, stream, a);
+    else if (q.R == 7 && q.S == 7)
+        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 7, 7>), grid, block, lds_bytes, stream, a);
+    else
+        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 0, 0>), grid, block, lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+#define POLYDL_DEFINE_CONV_PATCH(BM, BN, BK, WM, WN)                                                     \
+    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb, int r,            \
+                                                           hipStream_t st, bool dry)                     \
+    {                                                                                                    \
+        return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 40, 16>(q, cb, r, st, dry);                       \
+    }
+POLYDL_PATCH_FAMILY(POLYDL_DEFINE_CONV_PATCH)
+
+}  // namespace polydl

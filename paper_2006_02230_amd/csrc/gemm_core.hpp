@@ -74,7 +74,7 @@ struct ALoader {
     static constexpr bool RAGGED = UNITS % T::NT != 0;
     const float *base;   // A + m0*lda
     uint64_t bytes;      // bytes from base to the end of A
-    float regs[ITERS * VEC];
+    float regs[2][ITERS * VEC];  // two register sets: loads run two stages ahead
     uint32_t off0[ITERS];  // byte offset of the unit at k0 = 0, or kOobOffset if its row is outside
     int kcol[ITERS];       // first reduction index of the unit inside the stage
     int lds_off[ITERS];
@@ -93,32 +93,36 @@ struct ALoader {
             lds_off[i] = row * T::LDA + kc;
         }
     }
-    // loads reduction indices [k0, k0+BK) of which only those below kend exist
+    // loads reduction indices [k0, k0+BK), of which only those below kend exist, into set `set`
+    template <int SET>
     __device__ __forceinline__ void load(int k0, int kend)
     {
-        __amdgpu_buffer_rsrc_t rsrc = make_rsrc(base + k0, bytes - (uint64_t)k0 * 4);
+        // past the end every lane reads out of range: clamp the base so it stays inside A
+        const int kb = k0 < kend ? k0 : 0;
+        __amdgpu_buffer_rsrc_t rsrc = make_rsrc(base + kb, bytes - (uint64_t)kb * 4);
         int krem = kend - k0;
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
             uint32_t off = (kcol[i] < krem) ? off0[i] : kOobOffset;
             if constexpr (VEC == 4) {
                 v4f v = buf_load4(rsrc, off);
-                regs[4 * i] = v.x; regs[4 * i + 1] = v.y; regs[4 * i + 2] = v.z; regs[4 * i + 3] = v.w;
+                regs[SET][4 * i] = v.x; regs[SET][4 * i + 1] = v.y; regs[SET][4 * i + 2] = v.z; regs[SET][4 * i + 3] = v.w;
             } else {
-                regs[i] = buf_load1(rsrc, off);
+                regs[SET][i] = buf_load1(rsrc, off);
             }
         }
     }
+    template <int SET>
     __device__ __forceinline__ void store(float *As, int tid) const
     {
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
             if (RAGGED && tid + i * T::NT >= UNITS) continue;
             if constexpr (VEC == 4) {
-                v4f v = {regs[4 * i], regs[4 * i + 1], regs[4 * i + 2], regs[4 * i + 3]};
+                v4f v = {regs[SET][4 * i], regs[SET][4 * i + 1], regs[SET][4 * i + 2], regs[SET][4 * i + 3]};
                 *reinterpret_cast<v4f *>(As + lds_off[i]) = v;
             } else {
-                As[lds_off[i]] = regs[i];
+                As[lds_off[i]] = regs[SET][i];
             }
         }
     }
@@ -135,7 +139,7 @@ struct BLoaderRows {
     static constexpr bool RAGGED = UNITS % T::NT != 0;
     const float *base;  // B + n0
     int Kg, ldb, ncols;  // ncols = Ng - n0
-    float regs[ITERS * VEC];
+    float regs[2][ITERS * VEC];
     uint32_t off0[ITERS];
     int krow[ITERS];
     int lds_off[ITERS];
@@ -156,33 +160,36 @@ struct BLoaderRows {
             lds_off[i] = kr * T::LDB + nc;
         }
     }
+    template <int SET>
     __device__ __forceinline__ void load(int k0, int kend)
     {
+        const int kb = k0 < kend ? k0 : 0;   // past the end every lane reads out of range anyway
         // valid bytes from the stage's base: up to the last element of the last row of B
-        uint64_t bytes = ((uint64_t)(Kg - k0 - 1) * ldb + ncols) * 4;
-        __amdgpu_buffer_rsrc_t rsrc = make_rsrc(base + (size_t)k0 * ldb, bytes);
+        uint64_t bytes = ((uint64_t)(Kg - kb - 1) * ldb + ncols) * 4;
+        __amdgpu_buffer_rsrc_t rsrc = make_rsrc(base + (size_t)kb * ldb, bytes);
         int krem = kend - k0;
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
             uint32_t off = (krow[i] < krem) ? off0[i] : kOobOffset;
             if constexpr (VEC == 4) {
                 v4f v = buf_load4(rsrc, off);
-                regs[4 * i] = v.x; regs[4 * i + 1] = v.y; regs[4 * i + 2] = v.z; regs[4 * i + 3] = v.w;
+                regs[SET][4 * i] = v.x; regs[SET][4 * i + 1] = v.y; regs[SET][4 * i + 2] = v.z; regs[SET][4 * i + 3] = v.w;
             } else {
-                regs[i] = buf_load1(rsrc, off);
+                regs[SET][i] = buf_load1(rsrc, off);
             }
         }
     }
+    template <int SET>
     __device__ __forceinline__ void store(float *Bs, int tid) const
     {
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
             if (RAGGED && tid + i * T::NT >= UNITS) continue;
             if constexpr (VEC == 4) {
-                v4f v = {regs[4 * i], regs[4 * i + 1], regs[4 * i + 2], regs[4 * i + 3]};
+                v4f v = {regs[SET][4 * i], regs[SET][4 * i + 1], regs[SET][4 * i + 2], regs[SET][4 * i + 3]};
                 *reinterpret_cast<v4f *>(Bs + lds_off[i]) = v;
             } else {
-                Bs[lds_off[i]] = regs[i];
+                Bs[lds_off[i]] = regs[SET][i];
             }
         }
     }
@@ -224,36 +231,44 @@ __device__ __forceinline__ void mma_stage(const float *__restrict__ As, const fl
     }
 }
 
-// Software-pipelined reduction over [kbegin, kend): while the matrix cores work on LDS stage
-// t&1, the global loads of stage t+1 are in flight into registers; they are written to the other
-// LDS stage after the MFMAs were issued, and one barrier per step publishes them.  A loader that
-// runs past kend fills with zeros, so the last step needs no special case.
+// Software-pipelined reduction over [kbegin, kend).  Global loads run two stages ahead of the
+// matrix cores: while stage t is multiplied out of LDS buffer t&1, the registers of set (t+1)&1
+// already hold stage t+1 and the loads of stage t+2 are issued into set t&1.  A load therefore
+// has two full stages of MFMA work (several thousand cycles) to come back from HBM before its
+// data is copied to LDS at the end of the following stage; one barrier per stage publishes the
+// copy.  A loader that runs past kend fills with zeros, so the tail needs no special case.
+template <class T, int HALF, class AL, class BL>
+__device__ __forceinline__ void gemm_stage(float *As, float *Bs, AL &al, BL &bl, v16f (&acc)[T::MB][T::NB],
+                                           int k, int kend, int tid, int wm0, int wn0)
+{
+    // register set HALF is free (its stage is in LDS buffer HALF): fetch stage k + 2*BK into it
+    al.template load<HALF>(k + 2 * T::BK, kend);
+    bl.template load<HALF>(k + 2 * T::BK, kend);
+    mma_stage<T>(As + HALF * T::A_STAGE, Bs + HALF * T::B_STAGE, acc, wm0, wn0, tid & 63);
+    // stage k + BK sits in the other set: copy it to the other LDS buffer
+    al.template store<HALF ^ 1>(As + (HALF ^ 1) * T::A_STAGE, tid);
+    bl.template store<HALF ^ 1>(Bs + (HALF ^ 1) * T::B_STAGE, tid);
+    __syncthreads();
+}
+
 template <class T, class AL, class BL>
 __device__ __forceinline__ void gemm_mainloop(float *lds, AL &al, BL &bl, v16f (&acc)[T::MB][T::NB],
                                               int kbegin, int kend, int tid, int wm0, int wn0)
 {
     float *As = lds;
     float *Bs = lds + 2 * T::A_STAGE;
-    const int lane = tid & 63;
-    al.load(kbegin, kend);
-    bl.load(kbegin, kend);
-    al.store(As, tid);
-    bl.store(Bs, tid);
+    // stage 0 -> LDS buffer 0, stage 1 -> register set 1
+    al.template load<0>(kbegin, kend);
+    bl.template load<0>(kbegin, kend);
+    al.template load<1>(kbegin + T::BK, kend);
+    bl.template load<1>(kbegin + T::BK, kend);
+    al.template store<0>(As, tid);
+    bl.template store<0>(Bs, tid);
     __syncthreads();
-    int cur = 0;
-    for (int k0 = kbegin; k0 < kend; k0 += T::BK) {
-        const bool more = k0 + T::BK < kend;  // workgroup-uniform
-        if (more) {
-            al.load(k0 + T::BK, kend);
-            bl.load(k0 + T::BK, kend);
-        }
-        mma_stage<T>(As + cur * T::A_STAGE, Bs + cur * T::B_STAGE, acc, wm0, wn0, lane);
-        if (more) {
-            al.store(As + (cur ^ 1) * T::A_STAGE, tid);
-            bl.store(Bs + (cur ^ 1) * T::B_STAGE, tid);
-        }
-        __syncthreads();
-        cur ^= 1;
+    for (int k0 = kbegin; k0 < kend; k0 += 2 * T::BK) {
+        gemm_stage<T, 0>(As, Bs, al, bl, acc, k0, kend, tid, wm0, wn0);
+        if (k0 + T::BK < kend)   // workgroup-uniform
+            gemm_stage<T, 1>(As, Bs, al, bl, acc, k0 + T::BK, kend, tid, wm0, wn0);
     }
 }
 

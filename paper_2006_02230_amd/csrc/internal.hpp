@@ -28,13 +28,26 @@ struct Variant {
     hipError_t (*conv)(const ConvProblem &, int split_k, int raster, hipStream_t);
 };
 
+// One compiled tile of the row-patch convolution kernel.  dry = true only checks that the
+// problem fits the kernel's register, LDS and offset limits with cb channels per stage.
+struct PatchVariant {
+    int bm, bn, wm, wn;
+    int threads;
+    hipError_t (*conv)(const ConvProblem &, int cb, int raster, hipStream_t, bool dry);
+};
+
 extern const Variant kVariants[];
 extern const int kNumVariants;
+extern const PatchVariant kPatchVariants[];
+extern const int kNumPatchVariants;
 
 // filled in by the kernel files
 #define POLYDL_DECLARE_LAUNCHERS(BM, BN, BK, WM, WN)                                                          \
     hipError_t sgemm_launch_##BM##x##BN##x##BK##_##WM##x##WN(const SgemmProblem &, int, int, hipStream_t);     \
     hipError_t conv_launch_##BM##x##BN##x##BK##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t);
+
+#define POLYDL_DECLARE_PATCH_LAUNCHER(BM, BN, BK, WM, WN) \
+    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t, bool);
 
 // Exact unsigned division by a runtime constant d for dividends n with n*d < 2^32:
 // n / d == (n * magic) >> 32 with magic = floor(2^32 / d) + 1.

@@ -11,3 +11,13 @@
     X(128, 128, 8, 64, 64)    \
     X(128, 256, 16, 64, 128)  \
     X(256, 128, 16, 128, 64)
+
+// Tiles of the row-patch convolution kernel (BM output channels x BN pixels; wave tile WM x WN).
+// The third entry is unused there: the stage depth is CB*R*S with CB a run-time parameter.
+#define POLYDL_PATCH_FAMILY(X) \
+    X(64, 64, 0, 32, 32)       \
+    X(64, 128, 0, 64, 32)      \
+    X(64, 128, 0, 64, 64)      \
+    X(64, 256, 0, 64, 64)      \
+    X(128, 64, 0, 64, 32)      \
+    X(128, 128, 0, 64, 64)
