@@ -83,6 +83,27 @@ int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int s
  * allowed (C is left as it is). */
 int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream);
 
+/* ---- blocked layouts (figure "The 2-D Convolution code": the listing indexes
+ * input[img][ifm_tile][h][w][ifm] and filter[ofm_tile][ifm_tile][kj][ki][ifm][ofm]) --------------
+ * polydl_nchw_to_nchwc:  out[n][c/b][h][w][c%b] = in[n][c][h][w]; out has N*ceil(C/b)*H*W*b floats,
+ *   channels beyond C are written as zeros.  1 <= b <= 32.  polydl_nchwc_to_nchw is the inverse
+ *   (reads the blocked tensor, writes N*C*H*W floats).
+ * polydl_kcrs_to_kcrsck: out[k/bk][c/bc][r][s][c%bc][k%bk] = wt[k][c][r][s]; out has
+ *   ceil(K/bk)*ceil(C/bc)*R*S*bc*bk floats, entries beyond K or C are zeros.
+ * The paper runs only layers whose channel counts are multiples of the block; zero filling a
+ * partial last block is this library's reading.  Pure permutations: results are bit exact. */
+int polydl_nchw_to_nchwc(int N, int C, int H, int W, int b, const float *in, float *out, void *stream);
+int polydl_nchwc_to_nchw(int N, int C, int H, int W, int b, const float *in, float *out, void *stream);
+int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const float *wt, float *out, void *stream);
+
+/* ---- the element-wise operators as separate kernels (section "Operator Fusion": what the fused
+ * epilogue of polydl_conv2d_fwd replaces; kept for the fused-versus-unfused comparison) ---------
+ * polydl_bias_add:   y[n][k][p][q] += bias[k], in place on an NKPQ tensor.
+ * polydl_activation: y = max(y,0) (POLYDL_ACT_RELU) or min(max(y,0),6) (POLYDL_ACT_RELU6), in
+ *   place on `count` floats. */
+int polydl_bias_add(int N, int K, int P, int Q, float *y, const float *bias, void *stream);
+int polydl_activation(int64_t count, float *y, int act, void *stream);
+
 /* ---- variant control (the sweep forces a variant; reports read back the one used) -----------
  * polydl_set_tile_override: cfg != NULL forces that variant for every later call of the
  * calling process (POLYDL_ERR_UNSUPPORTED if it is not a compiled variant; a later problem it

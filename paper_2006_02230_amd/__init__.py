@@ -5,7 +5,9 @@ libpolydl.so; every arithmetic step runs in the HIP kernels.  There is no CPU fa
 library has not been built, importing this package raises.
 """
 from .binding import (lib, PolydlError, TileCfg, conv2d_fwd, sgemm, set_tile_override,
-                      get_last_tile, variants, status_string, LIB_PATH)
+                      get_last_tile, variants, status_string, LIB_PATH, nchw_to_nchwc,
+                      nchwc_to_nchw, kcrs_to_kcrsck, bias_add, activation)
 
 __all__ = ["lib", "PolydlError", "TileCfg", "conv2d_fwd", "sgemm", "set_tile_override",
-           "get_last_tile", "variants", "status_string", "LIB_PATH"]
+           "get_last_tile", "variants", "status_string", "LIB_PATH", "nchw_to_nchwc", "nchwc_to_nchw",
+           "kcrs_to_kcrsck", "bias_add", "activation"]

@@ -36,6 +36,14 @@ _i, _p = ctypes.c_int, ctypes.c_void_p
 lib.polydl_conv2d_fwd.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_conv2d_fwd_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_sgemm.argtypes = [_i, _i, _i, _p, _p, _p, _p]
+lib.polydl_nchw_to_nchwc.argtypes = [_i] * 5 + [_p, _p, _p]
+lib.polydl_nchwc_to_nchw.argtypes = [_i] * 5 + [_p, _p, _p]
+lib.polydl_kcrs_to_kcrsck.argtypes = [_i] * 6 + [_p, _p, _p]
+lib.polydl_bias_add.argtypes = [_i] * 4 + [_p, _p, _p]
+lib.polydl_activation.argtypes = [ctypes.c_int64, _p, _i, _p]
+for _f in (lib.polydl_nchw_to_nchwc, lib.polydl_nchwc_to_nchw, lib.polydl_kcrs_to_kcrsck,
+           lib.polydl_bias_add, lib.polydl_activation):
+    _f.restype = _i
 lib.polydl_set_tile_override.argtypes = [ctypes.POINTER(TileCfg)]
 lib.polydl_get_last_tile.argtypes = [ctypes.POINTER(TileCfg)]
 lib.polydl_num_variants.argtypes = [_i]
@@ -98,6 +106,49 @@ def sgemm(A, B, C, stream=None):
     st = lib.polydl_sgemm(M, N, K, _dev(A, "A"), _dev(B, "B"), _dev(C, "C"), _stream_ptr(stream))
     _check(st, "polydl_sgemm")
     return C
+
+
+def nchw_to_nchwc(x, b, stream=None):
+    """polydl_nchw_to_nchwc: returns the [N][ceil(C/b)][H][W][b] tensor."""
+    import torch
+    N, C, H, W = x.shape
+    out = torch.empty((N, -(-C // b), H, W, b), dtype=torch.float32, device=x.device)
+    _check(lib.polydl_nchw_to_nchwc(N, C, H, W, b, _dev(x, "x"), _dev(out, "out"), _stream_ptr(stream)),
+           "polydl_nchw_to_nchwc")
+    return out
+
+
+def nchwc_to_nchw(xb, C, stream=None):
+    """polydl_nchwc_to_nchw: returns the [N][C][H][W] tensor."""
+    import torch
+    N, Cb, H, W, b = xb.shape
+    out = torch.empty((N, C, H, W), dtype=torch.float32, device=xb.device)
+    _check(lib.polydl_nchwc_to_nchw(N, C, H, W, b, _dev(xb, "xb"), _dev(out, "out"), _stream_ptr(stream)),
+           "polydl_nchwc_to_nchw")
+    return out
+
+
+def kcrs_to_kcrsck(w, bc, bk, stream=None):
+    """polydl_kcrs_to_kcrsck: returns the [ceil(K/bk)][ceil(C/bc)][R][S][bc][bk] tensor."""
+    import torch
+    K, C, R, S = w.shape
+    out = torch.empty((-(-K // bk), -(-C // bc), R, S, bc, bk), dtype=torch.float32, device=w.device)
+    _check(lib.polydl_kcrs_to_kcrsck(K, C, R, S, bc, bk, _dev(w, "w"), _dev(out, "out"), _stream_ptr(stream)),
+           "polydl_kcrs_to_kcrsck")
+    return out
+
+
+def bias_add(y, bias, stream=None):
+    """polydl_bias_add, in place on an NKPQ tensor."""
+    N, K, P, Q = y.shape
+    _check(lib.polydl_bias_add(N, K, P, Q, _dev(y, "y"), _dev(bias, "bias"), _stream_ptr(stream)), "polydl_bias_add")
+    return y
+
+
+def activation(y, act="relu", stream=None):
+    """polydl_activation, in place."""
+    _check(lib.polydl_activation(y.numel(), _dev(y, "y"), ACT[act], _stream_ptr(stream)), "polydl_activation")
+    return y
 
 
 def set_tile_override(cfg=None, **kw):

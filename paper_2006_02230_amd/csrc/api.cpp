@@ -220,6 +220,48 @@ int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, 
     return sgemm_impl(M, N, K, A, B, C, stream);
 }
 
+int polydl_nchw_to_nchwc(int N, int C, int H, int W, int b, const float *in, float *out, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!in || !out) return POLYDL_ERR_NULL_POINTER;
+    if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
+    return launch_nchwc(in, out, N, C, H * W, b, true, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+int polydl_nchwc_to_nchw(int N, int C, int H, int W, int b, const float *in, float *out, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!in || !out) return POLYDL_ERR_NULL_POINTER;
+    if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
+    return launch_nchwc(in, out, N, C, H * W, b, false, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const float *wt, float *out, void *stream)
+{
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0 || bc <= 0 || bk <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!wt || !out) return POLYDL_ERR_NULL_POINTER;
+    const int64_t total = (int64_t)((K + bk - 1) / bk) * bk * ((C + bc - 1) / bc) * bc * R * S;
+    if (total >= (1ll << 39) || (int64_t)R * S >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
+    return launch_kcrsck(wt, out, K, C, R * S, bc, bk, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+int polydl_bias_add(int N, int K, int P, int Q, float *y, const float *bias, void *stream)
+{
+    if (N <= 0 || K <= 0 || P <= 0 || Q <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!y || !bias) return POLYDL_ERR_NULL_POINTER;
+    if ((int64_t)P * Q >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
+    return launch_bias_add(y, bias, K, P * Q, (size_t)N * K * P * Q, (hipStream_t)stream) == hipSuccess
+               ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+int polydl_activation(int64_t count, float *y, int act, void *stream)
+{
+    if (count <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!y) return POLYDL_ERR_NULL_POINTER;
+    if (act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6) return POLYDL_ERR_UNSUPPORTED;
+    return launch_act(y, (size_t)count, act, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
 int polydl_set_tile_override(const polydl_tile_cfg *cfg)
 {
     std::lock_guard<std::mutex> lk(g_mu);

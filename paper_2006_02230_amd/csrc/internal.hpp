@@ -49,6 +49,11 @@ extern const int kNumPatchVariants;
 #define POLYDL_DECLARE_PATCH_LAUNCHER(BM, BN, BK, WM, WN) \
     hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t, bool);
 
+hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int b, bool to_blocked, hipStream_t st);
+hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st);
+hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t total, hipStream_t st);
+hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
+
 // Exact unsigned division by a runtime constant d for dividends n with n*d < 2^32:
 // n / d == (n * magic) >> 32 with magic = floor(2^32 / d) + 1.
 inline uint32_t div_magic(uint32_t d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }

@@ -1,0 +1,127 @@
+// HBM-bound helper kernels: the blocked tensor layouts of the paper's convolution listing
+// (figure "The 2-D Convolution code": input[img][ifm_tile][h][w][ifm],
+// filter[ofm_tile][ifm_tile][kj][ki][ifm][ofm]) and the separate element-wise operators that the
+// fused epilogue replaces (section "Operator Fusion").
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "internal.hpp"
+
+namespace polydl {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// NCHW -> NCHWc.  One workgroup moves b channels x 256 pixels of one image: rows are read along
+// the pixels (contiguous in NCHW), transposed in LDS, and written along (pixel, channel) which
+// is contiguous in NCHWc.  Channels beyond C are written as zeros.
+template <bool TO_BLOCKED>
+__global__ __launch_bounds__(256) void nchwc_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                    int C, int HW, int b, int Cb)
+{
+    extern __shared__ float tile[];   // [b][257]
+    const int t = threadIdx.x;
+    const int hw0 = blockIdx.x * 256, cb = blockIdx.y, n = blockIdx.z;
+    const int npix = min(256, HW - hw0);
+    if (TO_BLOCKED) {
+        for (int ci = 0; ci < b; ++ci) {
+            int c = cb * b + ci;
+            float v = 0.f;
+            if (c < C && t < npix) v = src[((size_t)n * C + c) * HW + hw0 + t];
+            tile[ci * 257 + t] = v;
+        }
+        __syncthreads();
+        float *o = dst + (((size_t)n * Cb + cb) * HW + hw0) * b;
+        for (int e = t; e < npix * b; e += 256) o[e] = tile[(e % b) * 257 + e / b];
+    } else {
+        const float *i = src + (((size_t)n * Cb + cb) * HW + hw0) * b;
+        for (int e = t; e < npix * b; e += 256) tile[(e % b) * 257 + e / b] = i[e];
+        __syncthreads();
+        for (int ci = 0; ci < b; ++ci) {
+            int c = cb * b + ci;
+            if (c < C && t < npix) dst[((size_t)n * C + c) * HW + hw0 + t] = tile[ci * 257 + t];
+        }
+    }
+}
+
+// KCRS -> KCRSck: one thread per element of the blocked tensor (weights are small and packed
+// once per tensor).  Elements whose channel indices fall beyond K or C are zeros.
+__global__ void kcrsck_kernel(const float *__restrict__ wt, float *__restrict__ dst, int K, int C, int RS,
+                              int bc, int bk, int Cb, size_t total)
+{
+    size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= total) return;
+    int ki = (int)(o % bk);
+    size_t r1 = o / bk;
+    int ci = (int)(r1 % bc);
+    size_t r2 = r1 / bc;
+    int rs = (int)(r2 % RS);
+    size_t r3 = r2 / RS;
+    int cblk = (int)(r3 % Cb);
+    int kblk = (int)(r3 / Cb);
+    int k = kblk * bk + ki, c = cblk * bc + ci;
+    dst[o] = (k < K && c < C) ? wt[((size_t)k * C + c) * RS + rs] : 0.f;
+}
+
+// y[n][k][pq] += bias[k], in place.
+__global__ void bias_add_kernel(float *__restrict__ y, const float *__restrict__ bias, int K, int PQ, size_t total)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < total; i += step) y[i] += bias[(i / PQ) % K];
+}
+
+// y = max(y, 0) or min(max(y, 0), 6), in place; 128-bit accesses on the aligned body.
+__global__ void act_kernel(float *__restrict__ y, size_t total, int act)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t step = (size_t)gridDim.x * blockDim.x;
+    size_t n4 = (((uintptr_t)y & 15) == 0) ? total / 4 : 0;
+    f4 *y4 = reinterpret_cast<f4 *>(y);
+    for (size_t j = i; j < n4; j += step) {
+        f4 v = y4[j];
+        for (int c = 0; c < 4; ++c) {
+            float x = fmaxf(v[c], 0.f);
+            v[c] = act == POLYDL_ACT_RELU6 ? fminf(x, 6.f) : x;
+        }
+        y4[j] = v;
+    }
+    for (size_t j = n4 * 4 + i; j < total; j += step) {
+        float x = fmaxf(y[j], 0.f);
+        y[j] = act == POLYDL_ACT_RELU6 ? fminf(x, 6.f) : x;
+    }
+}
+
+hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int b, bool to_blocked, hipStream_t st)
+{
+    int Cb = (C + b - 1) / b;
+    dim3 grid((unsigned)((HW + 255) / 256), (unsigned)Cb, (unsigned)N);
+    size_t lds = (size_t)b * 257 * 4;
+    if (to_blocked) hipLaunchKernelGGL(nchwc_kernel<true>, grid, dim3(256), lds, st, src, dst, C, HW, b, Cb);
+    else hipLaunchKernelGGL(nchwc_kernel<false>, grid, dim3(256), lds, st, src, dst, C, HW, b, Cb);
+    return hipGetLastError();
+}
+
+hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st)
+{
+    int Kb = (K + bk - 1) / bk, Cb = (C + bc - 1) / bc;
+    size_t total = (size_t)Kb * Cb * RS * bc * bk;
+    hipLaunchKernelGGL(kcrsck_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, wt, dst, K, C, RS,
+                       bc, bk, Cb, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t total, hipStream_t st)
+{
+    unsigned blocks = (unsigned)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
+    hipLaunchKernelGGL(bias_add_kernel, dim3(blocks), dim3(256), 0, st, y, bias, K, PQ, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_act(float *y, size_t total, int act, hipStream_t st)
+{
+    size_t work = (total + 3) / 4;
+    unsigned blocks = (unsigned)((work + 255) / 256 < 8192 ? (work + 255) / 256 : 8192);
+    hipLaunchKernelGGL(act_kernel, dim3(blocks), dim3(256), 0, st, y, total, act);
+    return hipGetLastError();
+}
+
+}  // namespace polydl
