@@ -133,16 +133,17 @@ def main():
             best = None
             allv = []
             for v in P.variants(0):
-                for cb in ((2, 4, 8, 16, 32) if v.algo == 1 else (0,)):
-                    v.cb = cb
+                for cb, sk in ([(c, k) for c in (2, 4, 8, 16, 32) for k in (1, 2, 4, 8)] if v.algo == 1
+                               else [(0, 1)]):
+                    v.cb, v.split_k = cb, sk
                     try:
                         P.set_tile_override(v)
                         run_layer(L)
                         vms = time_calls(torch, lambda L=L: run_layer(L), 10)
                     except P.PolydlError:
                         continue
-                    allv.append((round(vms * 1e3, 2), "%dx%d/%dx%d a%d cb%d bk%d" % (
-                        v.bm, v.bn, v.wm, v.wn, v.algo, v.cb, v.bk)))
+                    allv.append((round(vms * 1e3, 2), "%dx%d/%dx%d a%d cb%d bk%d sk%d" % (
+                        v.bm, v.bn, v.wm, v.wn, v.algo, v.cb, v.bk, v.split_k)))
                     if best is None or vms < best[0]:
                         best = (vms, v.as_dict())
             rows[-1]["sweep_all"] = sorted(allv)[:8]

@@ -67,7 +67,7 @@ static int choose_cb(const PatchVariant &v, const ConvProblem &q)
     for (int cb = 2; cb <= cpad && cb <= 64; cb += 2) {
         if (cpad % cb != 0 && cb != cpad) continue;
         if (cb * q.R * q.S > 72 && best != 0) break;
-        if (v.conv(q, cb, 0, nullptr, true) == hipSuccess) best = cb;
+        if (v.conv(q, cb, 1, 0, nullptr, true) == hipSuccess) best = cb;
     }
     return best;
 }
@@ -172,11 +172,12 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     if (cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
     if (cfg.algo == 1) {
         const PatchVariant *pv = find_patch_variant(cfg);
-        if (!pv || cfg.split_k > 1) return POLYDL_ERR_UNSUPPORTED;
+        if (!pv) return POLYDL_ERR_UNSUPPORTED;
         if (cfg.cb == 0) cfg.cb = choose_cb(*pv, q);
         if (cfg.cb < 2 || (cfg.cb & 1)) return POLYDL_ERR_UNSUPPORTED;
-        if (pv->conv(q, cfg.cb, cfg.raster, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
-        if (pv->conv(q, cfg.cb, cfg.raster, (hipStream_t)stream, false) != hipSuccess) return POLYDL_ERR_LAUNCH;
+        const int sk = cfg.split_k < 1 ? 1 : cfg.split_k;
+        if (pv->conv(q, cfg.cb, sk, cfg.raster, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
+        if (pv->conv(q, cfg.cb, sk, cfg.raster, (hipStream_t)stream, false) != hipSuccess) return POLYDL_ERR_LAUNCH;
         std::lock_guard<std::mutex> lk(g_mu);
         g_last = cfg;
         return POLYDL_OK;

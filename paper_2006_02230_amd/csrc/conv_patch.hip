@@ -27,17 +27,21 @@ struct ConvPatchKArgs {
     float *out;
     int C, H, W, K, R, S, stride, pad, P, Q;
     int PQ, RS, HW, CHW, Kg, Ng;
-    int Wp;          // W + 2*pad: pitch of a patch row
+    int Wp;          // pitch of a patch row: W + 2*pad, or Q when S == 1 (only the columns used)
+    int prs, irs;    // patch rows per output-row step, input rows per patch row: (stride, 1), or
+                     // (1, stride) when R == 1 so that rows no tap reads are not staged
+    int pcs, ics;    // the same for columns: (stride, 1), or (1, stride) when S == 1
     int CB;          // input channels per stage (even)
     int nstages;     // ceil(C / CB)
     int D;           // CB*R*S: reduction elements per stage
     int LDA;         // LDS pitch of a filter row: D + 1 (odd, so a column read has no bank conflict)
-    int rows_full;   // input rows one whole image contributes: (P-1)*stride + R
+    int rows_full;   // patch rows one whole image contributes: (P-1)*prs + R
     int a_stage;     // floats reserved per LDS filter stage (BM*LDA rounded up to the workgroup size)
     int b_stage;     // floats reserved per LDS patch stage (rounded up likewise)
     uint32_t magic_Wp, one_Wp, magic_rf, one_rf, magic_lda;
     uint64_t in_bytes, wt_bytes;
     int tiles_m, tiles_n, raster, act;
+    int split_k, stages_per_split;   // blockIdx.y takes stages [y*stages_per_split, ...)
 };
 
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic, uint32_t ones_if_d1)
@@ -125,11 +129,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const int img_b = nlast / p.PQ, p_b = (nlast - img_b * p.PQ) / p.Q;
     int nrows0, total_rows;
     if (img_a == img_b) {
-        nrows0 = (p_b - p_a) * p.stride + p.R;
+        nrows0 = (p_b - p_a) * p.prs + p.R;
         total_rows = nrows0;
     } else {
-        nrows0 = (p.P - 1 - p_a) * p.stride + p.R;
-        total_rows = nrows0 + (img_b - img_a - 1) * p.rows_full + p_b * p.stride + p.R;
+        nrows0 = (p.P - 1 - p_a) * p.prs + p.R;
+        total_rows = nrows0 + (img_b - img_a - 1) * p.rows_full + p_b * p.prs + p.R;
     }
     const int ihb0 = p_a * p.stride - p.pad;       // first input row held for the first image
     const int chs = total_rows * p.Wp;             // patch floats per channel
@@ -159,7 +163,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             rr = (int)(d - j * (uint32_t)p.rows_full);
             ihb = -p.pad;
         }
-        int ih = ihb + rr, iw = col - p.pad;
+        int ih = ihb + rr * p.irs, iw = col * p.ics - p.pad;
         bool ok = ((int)e < patch_elems) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
         p_goff[i] = ok ? (uint32_t)(((ii * p.C + (int)c_l) * p.HW + ih * p.W + iw) * 4) : kOobOffset;
     }
@@ -195,8 +199,8 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             int op = pq / p.Q, oq = pq - op * p.Q;
             int ii = img - img_a;
             int slot0 = ii == 0 ? 0 : nrows0 + (ii - 1) * p.rows_full;
-            int ihb = ii == 0 ? ihb0 : -p.pad;
-            base = (slot0 + op * p.stride - p.pad - ihb) * p.Wp + oq * p.stride;
+            int p_lo = ii == 0 ? p_a : 0;
+            base = (slot0 + (op - p_lo) * p.prs) * p.Wp + oq * p.pcs;
             px_img[bj] = img;
             px_pq[bj] = pq;
         }
@@ -248,13 +252,15 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 
     const int npairs = p.CB >> 1;
 
-    load_stage(0, 0);
+    const int t_begin = blockIdx.y * p.stages_per_split;
+    const int t_end = min(p.nstages, t_begin + p.stages_per_split);
+    load_stage(t_begin, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's direct-to-LDS loads have landed
     __syncthreads();
-    for (int t = 0; t < p.nstages; ++t) {
-        const int buf = t & 1;
+    for (int t = t_begin; t < t_end; ++t) {
+        const int buf = (t - t_begin) & 1;
         // buffer buf^1 was last read in stage t-1, which every wave has left (barrier below)
-        if (t + 1 < p.nstages) load_stage(t + 1, buf ^ 1);
+        if (t + 1 < t_end) load_stage(t + 1, buf ^ 1);
 
         const float *A = As + buf * a_stage;
         const float *B = Bs + buf * p.b_stage;
@@ -281,6 +287,22 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     // A lane holds 16*MB output channels; their biases are fetched together before any store.
     const bool vec = NB > 1 && (p.PQ % NB == 0) && (((uintptr_t)p.out & 15) == 0);
     const bool full_rows = m0 + T::BM <= p.K;   // uniform: no channel of this tile is outside K
+    if (p.split_k > 1) {
+        // partial sums of the reduction parts meet in the zero-filled output through float
+        // atomics; bias and activation follow in a separate pass over the output
+#pragma unroll
+        for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = m0 + acc_row(wm0, bi, r, lane);
+                if (!full_rows && k >= p.K) continue;
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj)
+                    if (px_img[bj] >= 0)
+                        unsafeAtomicAdd(p.out + ((size_t)px_img[bj] * p.K + k) * p.PQ + px_pq[bj], acc[bi][bj][r]);
+            }
+        return;
+    }
     float bias[MB][16];
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
@@ -330,14 +352,29 @@ static int patch_rows_bound(const ConvProblem &q, int bn)
     if (rows_out > (long)q.N * q.P) rows_out = (long)q.N * q.P;
     long imgs = (run - 1 + PQ - 1) / PQ + 1;
     if (imgs > q.N) imgs = q.N;
-    long extra = q.R > q.stride ? q.R - q.stride : 0;
-    long bound = rows_out * q.stride + imgs * extra;
-    if (q.R < q.stride) bound = (rows_out - 1) * q.stride + q.R > bound ? (rows_out - 1) * q.stride + q.R : bound;
+    // an image with n output rows in the run holds (n-1)*prs + R patch rows
+    long prs = q.R == 1 ? 1 : q.stride;
+    long extra = q.R > prs ? q.R - prs : 0;
+    long bound = rows_out * prs + imgs * extra;
     return (int)bound;
 }
 
+// Zero fill before a split reduction and the bias/activation pass after it (kernels rather than
+// memset nodes, so the sequence can be captured in a graph).
+__global__ void patch_fill_zero_kernel(float *p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) p[i] = 0.f;
+}
+__global__ void patch_bias_act_kernel(float *y, const float *bias, int K, int PQ, size_t n, int act)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) y[i] = act_apply(y[i] + (bias ? bias[(i / PQ) % K] : 0.f), act);
+}
+
 template <class T, int MAXA, int MAXP>
-static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int raster, hipStream_t stream, bool dry)
+static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, int raster, hipStream_t stream,
+                                    bool dry)
 {
     ConvPatchKArgs a;
     a.in = q.in; a.wt = q.wt; a.bias = q.bias; a.out = q.out;
@@ -346,12 +383,14 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int raster, hi
     a.PQ = q.P * q.Q; a.RS = q.R * q.S; a.HW = q.H * q.W; a.CHW = q.C * q.H * q.W;
     a.Kg = q.C * a.RS;
     a.Ng = q.N * a.PQ;
-    a.Wp = q.W + 2 * q.pad;
+    a.Wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
+    a.prs = q.R == 1 ? 1 : q.stride; a.irs = q.R == 1 ? q.stride : 1;
+    a.pcs = q.S == 1 ? 1 : q.stride; a.ics = q.S == 1 ? q.stride : 1;
     a.CB = cb;
     a.nstages = (q.C + cb - 1) / cb;
     a.D = cb * a.RS;
     a.LDA = a.D + 1;   // D is even (cb is), so the pitch is odd and at least 3
-    a.rows_full = (q.P - 1) * q.stride + q.R;
+    a.rows_full = (q.P - 1) * a.prs + q.R;
     const int rows_alloc = patch_rows_bound(q, T::BN);
     a.a_stage = (T::BM * a.LDA + T::NT - 1) / T::NT * T::NT;
     a.b_stage = (cb * rows_alloc * a.Wp + T::NT - 1) / T::NT * T::NT;
@@ -374,8 +413,16 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int raster, hi
     const long imgs = (T::BN - 1 + PQl - 1) / PQl + 1;
     if ((long)T::BM * a.Kg * 4 >= 0x7FFFFFF0l || (imgs * q.C + cb) * (long)a.HW * 4 >= 0x7FFFFFF0l)
         return hipErrorInvalidConfiguration;
+    if (split_k < 1) split_k = 1;
+    if (split_k > a.nstages) split_k = a.nstages;
+    a.stages_per_split = (a.nstages + split_k - 1) / split_k;
+    a.split_k = (a.nstages + a.stages_per_split - 1) / a.stages_per_split;
+    if (a.split_k > 65535) return hipErrorInvalidConfiguration;
     if (dry) return hipSuccess;
-    dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(T::NT);
+    const size_t nout = (size_t)q.N * q.K * a.PQ;
+    const unsigned eblocks = (unsigned)((nout + 255) / 256 < 4096 ? (nout + 255) / 256 : 4096);
+    if (a.split_k > 1) hipLaunchKernelGGL(patch_fill_zero_kernel, dim3(eblocks), dim3(256), 0, stream, q.out, nout);
+    dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     if (q.R == 1 && q.S == 1)
         hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 1, 1>), grid, block, lds_bytes, stream, a);
     else if (q.R == 3 && q.S == 3)
@@ -384,14 +431,17 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int raster, hi
         hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 7, 7>), grid, block, lds_bytes, stream, a);
     else
         hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 0, 0>), grid, block, lds_bytes, stream, a);
+    if (a.split_k > 1 && (q.bias || q.act != POLYDL_ACT_NONE))
+        hipLaunchKernelGGL(patch_bias_act_kernel, dim3(eblocks), dim3(256), 0, stream, q.out, q.bias, q.K, a.PQ,
+                           nout, q.act);
     return hipGetLastError();
 }
 
 #define POLYDL_DEFINE_CONV_PATCH(BM, BN, BK, WM, WN)                                                     \
-    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb, int r,            \
+    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb, int sk, int r,    \
                                                            hipStream_t st, bool dry)                     \
     {                                                                                                    \
-        return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 40, 16>(q, cb, r, st, dry);                       \
+        return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, sk, r, st, dry);                   \
     }
 POLYDL_PATCH_FAMILY(POLYDL_DEFINE_CONV_PATCH)
 

@@ -33,7 +33,7 @@ struct Variant {
 struct PatchVariant {
     int bm, bn, wm, wn;
     int threads;
-    hipError_t (*conv)(const ConvProblem &, int cb, int raster, hipStream_t, bool dry);
+    hipError_t (*conv)(const ConvProblem &, int cb, int split_k, int raster, hipStream_t, bool dry);
 };
 
 extern const Variant kVariants[];
@@ -47,7 +47,7 @@ extern const int kNumPatchVariants;
     hipError_t conv_launch_##BM##x##BN##x##BK##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t);
 
 #define POLYDL_DECLARE_PATCH_LAUNCHER(BM, BN, BK, WM, WN) \
-    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t, bool);
+    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, int, hipStream_t, bool);
 
 hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int b, bool to_blocked, hipStream_t st);
 hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st);

@@ -72,8 +72,6 @@ def test_all_variants_small_integers_exact(P, s):
     want, _ = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad)
     for v in P.variants(0):
         for split_k in (1, 2):
-            if v.algo == 1 and split_k > 1:
-                continue
             v.split_k = split_k
             for cb in ((0, 2, 4) if v.algo == 1 else (0,)):
                 v.cb = cb
@@ -148,13 +146,14 @@ def test_split_k_random(P):
     s = synth.ConvShape("split", 2, 64, 7, 7, 96, 3, 3, 1, 1)
     x, w, b = synth.conv_inputs(s, seed=35, dist="normal", bias=True)
     want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1)
+    want_r, ab_r = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1, act="relu")
     for v in P.variants(0):
-        if v.algo != 0:
-            continue
         v.split_k = 4
-        P.set_tile_override(v)
-        got = run_conv(P, s, x, w, b)
-        assert oracle.scaled_error(got, want, ab) <= FP32_TOL, v
+        got = try_variant(P, v, s, x, w, b)
+        assert got is not None and oracle.scaled_error(got, want, ab) <= FP32_TOL, v
+        if v.algo == 1:   # the patch kernel applies bias and activation after the split reduction
+            got = try_variant(P, v, s, x, w, b, act="relu")
+            assert oracle.scaled_error(got, want_r, ab_r) <= FP32_TOL, v
     P.set_tile_override(None)
 
 
