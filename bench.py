@@ -52,6 +52,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--sweep", action="store_true", help="also time every compiled variant per layer")
+    ap.add_argument("--sweep-out", default="", help="with --sweep: write every candidate's time to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-sgemm", action="store_true")
     ap.add_argument("--layers", default="", help="comma list of suite layers to run (default: all eight); "
@@ -115,6 +116,7 @@ def main():
 
     # per-layer kernel time: back-to-back launches of one layer between two events on the launch stream
     rows = []
+    sweep_dump = []
     kern_ms_sum = 0.0
     for L in layers:
         i = L["index"]
@@ -130,27 +132,32 @@ def main():
                          tile=tile))
         kern_ms_sum += ms
         if args.sweep:
-            best = None
-            allv = []
-            for v in P.variants(0):
-                for cb, sk in ([(c, k) for c in (2, 4, 8, 16, 32) for k in (1, 2, 4, 8)] if v.algo == 1
-                               else [(0, 1)]):
-                    v.cb, v.split_k = cb, sk
-                    try:
-                        P.set_tile_override(v)
-                        run_layer(L)
-                        vms = time_calls(torch, lambda L=L: run_layer(L), 10)
-                    except P.PolydlError:
-                        continue
-                    allv.append((round(vms * 1e3, 2), "%dx%d/%dx%d a%d cb%d bk%d sk%d" % (
-                        v.bm, v.bn, v.wm, v.wn, v.algo, v.cb, v.bk, v.split_k)))
-                    if best is None or vms < best[0]:
-                        best = (vms, v.as_dict())
-            rows[-1]["sweep_all"] = sorted(allv)[:8]
+            # every candidate the picker ranks, timed; the model's prediction beside it
+            shape = tuple(L["shape"])[1:]
+            cands = []
+            t_sweep = time.perf_counter()
+            for v in P.conv_candidates(shape):
+                try:
+                    P.set_tile_override(v)
+                    run_layer(L)
+                    vms = time_calls(torch, lambda L=L: run_layer(L), 8, batches=2)
+                except P.PolydlError:
+                    continue
+                pred = P.model_conv2d(shape, v).predicted_us
+                cands.append(dict(us=round(vms * 1e3, 2), pred_us=round(pred, 2), cfg=v.as_dict()))
+            t_sweep = time.perf_counter() - t_sweep
             P.set_tile_override(forced)
-            rows[-1]["sweep_best_us"] = round(best[0] * 1e3, 2)
-            rows[-1]["sweep_best_tile"] = best[1]
-            rows[-1]["pick_over_best"] = round(best[0] / ms, 4)
+            cands.sort(key=lambda c: c["us"])
+            best = cands[0]
+            t_pick = time.perf_counter()
+            pcfg, prep = P.pick_conv2d(shape)
+            t_pick = time.perf_counter() - t_pick
+            rows[-1].update(sweep_best_us=best["us"], sweep_best_tile=best["cfg"],
+                            pick_over_best=round(best["us"] / (ms * 1e3), 4), candidates=len(cands),
+                            predicted_us=round(prep.predicted_us, 2), pick_seconds=round(t_pick, 5),
+                            sweep_seconds=round(t_sweep, 3))
+            sweep_dump.append(dict(layer=i, shape=list(shape), picked=pcfg.as_dict(), picked_us=round(ms * 1e3, 2),
+                                   candidates=cands))
     achieved = total_flops / (kern_ms_sum * 1e-3) / 1e12
 
     sg = []
@@ -201,6 +208,9 @@ def main():
         "sgemm": sg,
         "event_ms_per_step": round(e0.elapsed_time(e1) / args.steps, 4),
     }
+    if args.sweep and args.sweep_out:
+        with open(args.sweep_out, "w") as f:
+            json.dump(sweep_dump, f)
     print(json.dumps(result))
 
 

@@ -104,6 +104,40 @@ int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const floa
 int polydl_bias_add(int N, int K, int P, int Q, float *y, const float *bias, void *stream);
 int polydl_activation(int64_t count, float *y, int act, void *stream);
 
+/* ---- the reuse model (sections "Working set size computation" and "Poly-ranking algorithm") ------
+ * polydl_reuse_bucket: algorithm "Compute working set sizes w.r.t cache sizes": the n working set
+ *   sizes ws[] are sorted ascending and each is added to the first of the nlevels levels (fastest
+ *   first, capacities sizes[]) where it still fits beside what is already there; the rest is
+ *   summed into *mem.  levels[] receives the per-level sums.  Host pointers.
+ * polydl_reuse_cost: equation (1) with lat/bw given as one weight per level:
+ *   sum_i levels[i]*weights[i] + mem*mem_weight.  Lower is better.
+ * polydl_model_conv2d / polydl_model_sgemm: the model's report for one variant of one problem.
+ * polydl_pick_conv2d / polydl_pick_sgemm: the variant with the lowest predicted time over the
+ *   compiled family (what polydl_conv2d_fwd / polydl_sgemm use when no override is set).
+ * The report holds the working sets of the variant in bytes (accumulator tile, LDS stage, one
+ * column-tile step, the workgroups resident on one XCD, the whole problem), their placement in
+ * (accumulator registers, LDS, L2, Infinity Cache) + memory, equation (1) over that placement,
+ * and the predicted time split into its matrix-core, data and fixed parts. */
+typedef struct polydl_model_report {
+    double predicted_us, mfma_us, mem_us, fixed_us;
+    double ws[8];
+    int n_ws;
+    double level_bytes[4];
+    double mem_bytes;
+    double eq1_cost;
+    int workgroups;
+    double simd_load;   /* waves the busiest SIMD has to run one after another */
+} polydl_model_report;
+
+int polydl_reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem);
+double polydl_reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight);
+int polydl_model_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                        const polydl_tile_cfg *cfg, polydl_model_report *report);
+int polydl_model_sgemm(int M, int N, int K, const polydl_tile_cfg *cfg, polydl_model_report *report);
+int polydl_pick_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                       polydl_tile_cfg *cfg, polydl_model_report *report);
+int polydl_pick_sgemm(int M, int N, int K, polydl_tile_cfg *cfg, polydl_model_report *report);
+
 /* ---- variant control (the sweep forces a variant; reports read back the one used) -----------
  * polydl_set_tile_override: cfg != NULL forces that variant for every later call of the
  * calling process (POLYDL_ERR_UNSUPPORTED if it is not a compiled variant; a later problem it

@@ -6,8 +6,11 @@ library has not been built, importing this package raises.
 """
 from .binding import (lib, PolydlError, TileCfg, conv2d_fwd, sgemm, set_tile_override,
                       get_last_tile, variants, status_string, LIB_PATH, nchw_to_nchwc,
-                      nchwc_to_nchw, kcrs_to_kcrsck, bias_add, activation)
+                      nchwc_to_nchw, kcrs_to_kcrsck, bias_add, activation, ModelReport,
+                      reuse_bucket, reuse_cost, model_conv2d, model_sgemm, pick_conv2d, pick_sgemm,
+                      conv_candidates)
 
 __all__ = ["lib", "PolydlError", "TileCfg", "conv2d_fwd", "sgemm", "set_tile_override",
            "get_last_tile", "variants", "status_string", "LIB_PATH", "nchw_to_nchwc", "nchwc_to_nchw",
-           "kcrs_to_kcrsck", "bias_add", "activation"]
+           "kcrs_to_kcrsck", "bias_add", "activation", "ModelReport", "reuse_bucket", "reuse_cost",
+           "model_conv2d", "model_sgemm", "pick_conv2d", "pick_sgemm", "conv_candidates"]

@@ -32,6 +32,20 @@ class TileCfg(ctypes.Structure):
         return "TileCfg(%s)" % ", ".join("%s=%d" % kv for kv in self.as_dict().items())
 
 
+class ModelReport(ctypes.Structure):
+    """Mirror of polydl_model_report."""
+    _fields_ = [("predicted_us", ctypes.c_double), ("mfma_us", ctypes.c_double), ("mem_us", ctypes.c_double),
+                ("fixed_us", ctypes.c_double), ("ws", ctypes.c_double * 8), ("n_ws", ctypes.c_int),
+                ("level_bytes", ctypes.c_double * 4), ("mem_bytes", ctypes.c_double),
+                ("eq1_cost", ctypes.c_double), ("workgroups", ctypes.c_int), ("simd_load", ctypes.c_double)]
+
+    def as_dict(self):
+        return {"predicted_us": self.predicted_us, "mfma_us": self.mfma_us, "mem_us": self.mem_us,
+                "fixed_us": self.fixed_us, "ws": list(self.ws)[:self.n_ws], "level_bytes": list(self.level_bytes),
+                "mem_bytes": self.mem_bytes, "eq1_cost": self.eq1_cost, "workgroups": self.workgroups,
+                "simd_load": self.simd_load}
+
+
 _i, _p = ctypes.c_int, ctypes.c_void_p
 lib.polydl_conv2d_fwd.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_conv2d_fwd_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
@@ -43,6 +57,18 @@ lib.polydl_bias_add.argtypes = [_i] * 4 + [_p, _p, _p]
 lib.polydl_activation.argtypes = [ctypes.c_int64, _p, _i, _p]
 for _f in (lib.polydl_nchw_to_nchwc, lib.polydl_nchwc_to_nchw, lib.polydl_kcrs_to_kcrsck,
            lib.polydl_bias_add, lib.polydl_activation):
+    _f.restype = _i
+_d = ctypes.c_double
+_pd = ctypes.POINTER(ctypes.c_double)
+lib.polydl_reuse_bucket.argtypes = [_i, _pd, _i, _pd, _pd, _pd]
+lib.polydl_reuse_bucket.restype = _i
+lib.polydl_reuse_cost.argtypes = [_i, _pd, _d, _pd, _d]
+lib.polydl_reuse_cost.restype = _d
+lib.polydl_model_conv2d.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ModelReport)]
+lib.polydl_model_sgemm.argtypes = [_i] * 3 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ModelReport)]
+lib.polydl_pick_conv2d.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ModelReport)]
+lib.polydl_pick_sgemm.argtypes = [_i] * 3 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ModelReport)]
+for _f in (lib.polydl_model_conv2d, lib.polydl_model_sgemm, lib.polydl_pick_conv2d, lib.polydl_pick_sgemm):
     _f.restype = _i
 lib.polydl_set_tile_override.argtypes = [ctypes.POINTER(TileCfg)]
 lib.polydl_get_last_tile.argtypes = [ctypes.POINTER(TileCfg)]
@@ -149,6 +175,77 @@ def activation(y, act="relu", stream=None):
     """polydl_activation, in place."""
     _check(lib.polydl_activation(y.numel(), _dev(y, "y"), ACT[act], _stream_ptr(stream)), "polydl_activation")
     return y
+
+
+def reuse_bucket(ws, sizes):
+    """polydl_reuse_bucket on Python sequences: returns (per-level sums, memory sum)."""
+    n, m = len(ws), len(sizes)
+    a = (ctypes.c_double * max(n, 1))(*ws)
+    b = (ctypes.c_double * max(m, 1))(*sizes)
+    lv = (ctypes.c_double * max(m, 1))()
+    mem = ctypes.c_double()
+    _check(lib.polydl_reuse_bucket(n, a, m, b, lv, ctypes.byref(mem)), "polydl_reuse_bucket")
+    return list(lv)[:m], mem.value
+
+
+def reuse_cost(levels, mem, weights, mem_weight):
+    """polydl_reuse_cost on Python sequences."""
+    m = len(levels)
+    return lib.polydl_reuse_cost(m, (ctypes.c_double * max(m, 1))(*levels), mem,
+                                 (ctypes.c_double * max(m, 1))(*weights), mem_weight)
+
+
+def model_conv2d(shape, cfg):
+    """polydl_model_conv2d for a synth.ConvShape-like tuple (N, C, H, W, K, R, S, stride, pad)."""
+    rep = ModelReport()
+    _check(lib.polydl_model_conv2d(*[int(v) for v in shape], ctypes.byref(cfg), ctypes.byref(rep)),
+           "polydl_model_conv2d")
+    return rep
+
+
+def model_sgemm(M, N, K, cfg):
+    rep = ModelReport()
+    _check(lib.polydl_model_sgemm(M, N, K, ctypes.byref(cfg), ctypes.byref(rep)), "polydl_model_sgemm")
+    return rep
+
+
+def pick_conv2d(shape):
+    """polydl_pick_conv2d: (TileCfg, ModelReport) of the variant the reuse model ranks first."""
+    cfg, rep = TileCfg(), ModelReport()
+    _check(lib.polydl_pick_conv2d(*[int(v) for v in shape], ctypes.byref(cfg), ctypes.byref(rep)),
+           "polydl_pick_conv2d")
+    return cfg, rep
+
+
+def pick_sgemm(M, N, K):
+    cfg, rep = TileCfg(), ModelReport()
+    _check(lib.polydl_pick_sgemm(M, N, K, ctypes.byref(cfg), ctypes.byref(rep)), "polydl_pick_sgemm")
+    return cfg, rep
+
+
+def conv_candidates(shape):
+    """Every (variant, cb, split_k) the picker ranks for this problem: the sweep's search space."""
+    N, C, H, W, K, R, S, stride, pad = [int(v) for v in shape]
+    splits = (1, 2, 3, 4, 6, 8, 12, 16)
+    cpad = (C + 1) & ~1
+    out = []
+    for v in variants(0):
+        if v.algo == 1:
+            for cb in range(2, min(cpad, 64) + 1, 2):
+                if cpad % cb:
+                    continue
+                stages = -(-C // cb)
+                for sk in splits:
+                    if sk > stages:
+                        break
+                    out.append(TileCfg(v.bm, v.bn, 0, v.wm, v.wn, sk, 0, 0, 1, cb))
+        else:
+            stages = -(-(C * R * S) // v.bk)
+            for sk in splits:
+                if sk > stages or sk > 8:
+                    break
+                out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0))
+    return out
 
 
 def set_tile_override(cfg=None, **kw):

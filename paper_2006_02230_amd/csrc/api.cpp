@@ -59,7 +59,8 @@ static void cfg_of_patch(const PatchVariant &v, int cb, int raster, polydl_tile_
 }
 
 // Largest even channel count per stage the patch kernel can hold for this problem and tile,
-// preferring stages of at most 72 reduction elements; 0 if none fits.
+// preferring stages of at most 72 reduction elements; 0 if none fits.  Used when an override
+// names a patch tile but leaves cb = 0.
 static int choose_cb(const PatchVariant &v, const ConvProblem &q)
 {
     int cpad = (q.C + 1) & ~1;
@@ -72,50 +73,24 @@ static int choose_cb(const PatchVariant &v, const ConvProblem &q)
     return best;
 }
 
-// Placeholder choice for convolution until the reuse model is wired in: the patch tile with the
-// fewest wasted output-channel rows and at least two workgroups per compute unit.
-static bool default_conv_pick(const ConvProblem &q, polydl_tile_cfg *out)
+static bool conv_dims(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int64_t *P, int64_t *Q)
 {
-    const long Ng = (long)q.N * q.P * q.Q;
-    const PatchVariant *best = nullptr;
-    double best_score = -1;
-    int best_cb = 0;
-    for (int i = 0; i < kNumPatchVariants; ++i) {
-        const PatchVariant &v = kPatchVariants[i];
-        int cb = choose_cb(v, q);
-        if (!cb) continue;
-        long tm = (q.K + v.bm - 1) / v.bm, tn = (Ng + v.bn - 1) / v.bn;
-        double useful = (double)q.K * Ng / ((double)tm * v.bm * tn * v.bn);
-        long tiles = tm * tn;
-        double waves = (double)tiles / 256.0;
-        double quant = waves / (double)((tiles + 255) / 256);
-        double wave_tile = (double)(v.wm * v.wn) / (64.0 * 64.0);
-        double score = useful * quant * (0.6 + 0.4 * (wave_tile > 1 ? 1 : wave_tile));
-        if (score > best_score) { best_score = score; best = &v; best_cb = cb; }
-    }
-    if (!best) return false;
-    cfg_of_patch(*best, best_cb, 0, out);
-    return true;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return false;
+    if (H + 2 * (int64_t)pad < R || W + 2 * (int64_t)pad < S) return false;
+    *P = (H + 2 * (int64_t)pad - R) / stride + 1;
+    *Q = (W + 2 * (int64_t)pad - S) / stride + 1;
+    return *P > 0 && *Q > 0;
 }
 
-// Placeholder choice until the reuse model is wired in: the largest square-ish tile that still
-// yields at least one workgroup per compute unit, else the smallest tile.
-static polydl_tile_cfg default_pick(long Mg, long Ng)
+// index ranges of the kernels: filter taps as bit masks, 32-bit pixel counts and offsets, exact
+// magic division of reduction indices
+static bool conv_in_range(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int64_t P, int64_t Q)
 {
-    polydl_tile_cfg best;
-    cfg_of(kVariants[0], 1, 0, 0, &best);
-    long best_area = 0;
-    for (int i = 0; i < kNumVariants; ++i) {
-        const Variant &v = kVariants[i];
-        if (v.bk != 16 || v.threads != 256) continue;
-        long tiles = ((Mg + v.bm - 1) / v.bm) * ((Ng + v.bn - 1) / v.bn);
-        long area = (long)v.bm * v.bn;
-        if (tiles >= 512 && area > best_area && area <= 128 * 128) {
-            best_area = area;
-            cfg_of(v, 1, 0, 0, &best);
-        }
-    }
-    return best;
+    const int64_t Kg = (int64_t)C * R * S, Ng = (int64_t)N * P * Q;
+    if (R > 32 || S > 32 || pad > 0x3FFFFF || stride > 0x3FFFFF) return false;
+    if (Ng >= 0x7FFF0000ll || Kg >= (1ll << 22) || Kg * R * S >= (1ll << 32)) return false;
+    if ((int64_t)N * C * H * W >= (1ll << 40) || (int64_t)N * K * P * Q >= (1ll << 40)) return false;
+    return true;
 }
 
 static int sgemm_impl(int M, int N, int K, const float *A, const float *B, float *C, void *stream)
@@ -126,7 +101,12 @@ static int sgemm_impl(int M, int N, int K, const float *A, const float *B, float
     polydl_tile_cfg cfg;
     {
         std::lock_guard<std::mutex> lk(g_mu);
-        cfg = g_have_override ? g_override : default_pick(M, N);
+        cfg = g_override;
+        if (!g_have_override) {
+            polydl_model_report rep;
+            SgemmProblem pq{M, N, K, A, B, C};
+            if (!pick_sgemm(pq, &cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+        }
     }
     const Variant *v = find_variant(cfg);
     if (!v) return POLYDL_ERR_UNSUPPORTED;
@@ -147,19 +127,13 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
                      const float *in, const float *wt, const float *bias, float *out, int act,
                      void *stream)
 {
-    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
-        return POLYDL_ERR_BAD_DIMENSION;
-    if (H + 2 * (int64_t)pad < R || W + 2 * (int64_t)pad < S) return POLYDL_ERR_BAD_DIMENSION;
-    const int64_t P = (H + 2 * (int64_t)pad - R) / stride + 1, Q = (W + 2 * (int64_t)pad - S) / stride + 1;
-    if (P <= 0 || Q <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    int64_t P, Q;
+    if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
     if (!in || !wt || !out) return POLYDL_ERR_NULL_POINTER;
     if (act != POLYDL_ACT_NONE && act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6)
         return POLYDL_ERR_UNSUPPORTED;
-    // index ranges of the kernels: filter taps as bit masks, 32-bit pixel counts and offsets,
-    // exact magic division of reduction indices
-    const int64_t Kg = (int64_t)C * R * S, Ng = (int64_t)N * P * Q, CHW = (int64_t)C * H * W;
-    if (R > 32 || S > 32 || pad > 0x3FFFFF || stride > 0x3FFFFF) return POLYDL_ERR_UNSUPPORTED;
-    if (Ng >= 0x7FFF0000ll || Kg >= (1ll << 22) || Kg * R * S >= (1ll << 32)) return POLYDL_ERR_UNSUPPORTED;
+    if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
+    const int64_t Kg = (int64_t)C * R * S, CHW = (int64_t)C * H * W;
     ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act};
     polydl_tile_cfg cfg;
     bool forced;
@@ -168,7 +142,10 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         forced = g_have_override;
         cfg = g_override;
     }
-    if (!forced && !default_conv_pick(q, &cfg)) cfg = default_pick(K, Ng);
+    if (!forced) {
+        polydl_model_report rep;
+        if (!pick_conv(q, &cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+    }
     if (cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
     if (cfg.algo == 1) {
         const PatchVariant *pv = find_patch_variant(cfg);
@@ -187,7 +164,6 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     // a tile of bn pixels spans at most bn/PQ + 2 images; their offsets must fit 31 bits
     const int64_t span = (v->bn / (P * Q) + 2) * CHW * 4;
     if (span >= 0x7FFFFFF0ll || (int64_t)v->bm * Kg * 4 >= 0x7FFFFFF0ll) return POLYDL_ERR_UNSUPPORTED;
-    if (cfg.split_k > 1 && act != POLYDL_ACT_NONE) return POLYDL_ERR_UNSUPPORTED;
     hipError_t e = v->conv(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
     if (e != hipSuccess) return POLYDL_ERR_LAUNCH;
     std::lock_guard<std::mutex> lk(g_mu);
@@ -261,6 +237,75 @@ int polydl_activation(int64_t count, float *y, int act, void *stream)
     if (!y) return POLYDL_ERR_NULL_POINTER;
     if (act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6) return POLYDL_ERR_UNSUPPORTED;
     return launch_act(y, (size_t)count, act, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+int polydl_reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem)
+{
+    if (n < 0 || nlevels < 0) return POLYDL_ERR_BAD_DIMENSION;
+    if ((n > 0 && !ws) || (nlevels > 0 && (!sizes || !levels)) || !mem) return POLYDL_ERR_NULL_POINTER;
+    reuse_bucket(n, ws, nlevels, sizes, levels, mem);
+    return POLYDL_OK;
+}
+
+double polydl_reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight)
+{
+    if (nlevels < 0 || (nlevels > 0 && (!levels || !weights))) return -1.0;
+    return reuse_cost(nlevels, levels, mem, weights, mem_weight);
+}
+
+static int threads_of(const polydl_tile_cfg &c)
+{
+    if (c.wm <= 0 || c.wn <= 0 || c.bm % c.wm || c.bn % c.wn) return 0;
+    return (c.bm / c.wm) * (c.bn / c.wn) * 64;
+}
+
+int polydl_model_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                        const polydl_tile_cfg *cfg, polydl_model_report *report)
+{
+    int64_t P, Q;
+    if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
+    if (!cfg || !report) return POLYDL_ERR_NULL_POINTER;
+    const bool known = cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
+                                      : (cfg->algo == 0 && find_variant(*cfg) != nullptr);
+    if (!known || !conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
+    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
+    model_conv(q, *cfg, threads_of(*cfg), report);
+    return POLYDL_OK;
+}
+
+int polydl_model_sgemm(int M, int N, int K, const polydl_tile_cfg *cfg, polydl_model_report *report)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!cfg || !report) return POLYDL_ERR_NULL_POINTER;
+    if (!find_variant(*cfg)) return POLYDL_ERR_UNSUPPORTED;
+    SgemmProblem q{M, N, K, nullptr, nullptr, nullptr};
+    model_sgemm(q, *cfg, threads_of(*cfg), report);
+    return POLYDL_OK;
+}
+
+int polydl_pick_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                       polydl_tile_cfg *cfg, polydl_model_report *report)
+{
+    int64_t P, Q;
+    if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
+    if (!cfg) return POLYDL_ERR_NULL_POINTER;
+    if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
+    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
+    polydl_model_report rep;
+    if (!pick_conv(q, cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+    if (report) *report = rep;
+    return POLYDL_OK;
+}
+
+int polydl_pick_sgemm(int M, int N, int K, polydl_tile_cfg *cfg, polydl_model_report *report)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!cfg) return POLYDL_ERR_NULL_POINTER;
+    SgemmProblem q{M, N, K, nullptr, nullptr, nullptr};
+    polydl_model_report rep;
+    if (!pick_sgemm(q, cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+    if (report) *report = rep;
+    return POLYDL_OK;
 }
 
 int polydl_set_tile_override(const polydl_tile_cfg *cfg)

@@ -151,15 +151,14 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
             const float b = p.bias ? p.bias[k] : 0.f;
             float *o = p.out + ((size_t)img * p.K + k) * p.PQ + pq;
             if (p.split_k > 1) {
-                // partial sums meet in a zero-filled output; bias joins through the first part,
-                // and an activation cannot be applied here (the launcher refuses that case)
+                // partial sums meet in a zero-filled output; bias and activation follow in a
+                // separate pass over the output
 #pragma unroll
                 for (int bj = 0; bj < T::NB; ++bj) {
                     int cg = colg + bj;
                     if (cg >= p.Ng) break;
                     int im = cg / p.PQ, q = cg - im * p.PQ;
-                    float v = acc[bi][bj][r] + (blockIdx.y == 0 ? b : 0.f);
-                    unsafeAtomicAdd(p.out + ((size_t)im * p.K + k) * p.PQ + q, v);
+                    unsafeAtomicAdd(p.out + ((size_t)im * p.K + k) * p.PQ + q, acc[bi][bj][r]);
                 }
             } else if (vec) {
                 if constexpr (T::NB == 4) {
@@ -182,15 +181,6 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
                 }
             }
         }
-}
-
-// Zero fill of the output before a split reduction (a kernel, not a memset node, so the call
-// sequence can be captured in a graph).
-__global__ void fill_zero_kernel(float *p, size_t n)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t step = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += step) p[i] = 0.f;
 }
 
 template <class T>
@@ -218,16 +208,14 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     a.split_k = (stages + stages_per - 1) / stages_per;
     a.raster = raster;
     a.act = q.act;
-    if (a.split_k > 1) {
-        if (q.act != POLYDL_ACT_NONE) return hipErrorInvalidValue;
-        size_t n = (size_t)q.N * q.K * a.PQ;
-        unsigned blocks = (unsigned)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, q.out, n);
-    }
+    const size_t nout = (size_t)q.N * q.K * a.PQ;
+    if (a.split_k > 1 && launch_fill_zero(q.out, nout, stream) != hipSuccess) return hipGetLastError();
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
     if (avec) hipLaunchKernelGGL((conv_kernel<T, 4>), grid, block, 0, stream, a);
     else hipLaunchKernelGGL((conv_kernel<T, 1>), grid, block, 0, stream, a);
+    if (a.split_k > 1 && (q.bias || q.act != POLYDL_ACT_NONE))
+        return launch_bias_act(q.out, q.bias, q.K, a.PQ, nout, q.act, stream);
     return hipGetLastError();
 }
 

@@ -359,19 +359,6 @@ static int patch_rows_bound(const ConvProblem &q, int bn)
     return (int)bound;
 }
 
-// Zero fill before a split reduction and the bias/activation pass after it (kernels rather than
-// memset nodes, so the sequence can be captured in a graph).
-__global__ void patch_fill_zero_kernel(float *p, size_t n)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += step) p[i] = 0.f;
-}
-__global__ void patch_bias_act_kernel(float *y, const float *bias, int K, int PQ, size_t n, int act)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += step) y[i] = act_apply(y[i] + (bias ? bias[(i / PQ) % K] : 0.f), act);
-}
-
 template <class T, int MAXA, int MAXP>
 static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, int raster, hipStream_t stream,
                                     bool dry)
@@ -420,8 +407,7 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     if (a.split_k > 65535) return hipErrorInvalidConfiguration;
     if (dry) return hipSuccess;
     const size_t nout = (size_t)q.N * q.K * a.PQ;
-    const unsigned eblocks = (unsigned)((nout + 255) / 256 < 4096 ? (nout + 255) / 256 : 4096);
-    if (a.split_k > 1) hipLaunchKernelGGL(patch_fill_zero_kernel, dim3(eblocks), dim3(256), 0, stream, q.out, nout);
+    if (a.split_k > 1 && launch_fill_zero(q.out, nout, stream) != hipSuccess) return hipGetLastError();
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     if (q.R == 1 && q.S == 1)
         hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 1, 1>), grid, block, lds_bytes, stream, a);
@@ -432,8 +418,7 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     else
         hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 0, 0>), grid, block, lds_bytes, stream, a);
     if (a.split_k > 1 && (q.bias || q.act != POLYDL_ACT_NONE))
-        hipLaunchKernelGGL(patch_bias_act_kernel, dim3(eblocks), dim3(256), 0, stream, q.out, q.bias, q.K, a.PQ,
-                           nout, q.act);
+        return launch_bias_act(q.out, q.bias, q.K, a.PQ, nout, q.act, stream);
     return hipGetLastError();
 }
 

@@ -53,6 +53,16 @@ hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int 
 hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st);
 hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t total, hipStream_t st);
 hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
+hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st);
+hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n, int act, hipStream_t st);
+
+// picker.cpp
+void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem);
+double reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight);
+void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r);
+void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r);
+bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
+bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
 
 // Exact unsigned division by a runtime constant d for dividends n with n*d < 2^32:
 // n / d == (n * magic) >> 32 with magic = floor(2^32 / d) + 1.

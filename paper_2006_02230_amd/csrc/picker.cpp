@@ -1,0 +1,313 @@
+// Tile-configuration picker: the paper's reuse analysis re-derived for the CDNA4 memory hierarchy.
+//
+// PolyDL ranks loop-nest variants without running them (section "Compile Time Selection of Top
+// performing code version"): algorithm "Compute working set sizes" lists, per data reuse, how much
+// data is touched between the source and the target of the reuse; algorithm "Compute working set
+// sizes w.r.t cache sizes" places every working set in the fastest level it fits; equation (1)
+// charges each level's working sets with that level's cost per byte.  Here the variants are the
+// compiled tile family, the loop nest is fixed (workgroup tile around a register-resident wave
+// tile), so the working sets have closed forms, and the levels are accumulator registers, LDS,
+// the XCD's L2 and the Infinity Cache, with HBM as memory.
+//
+// Two additions the GPU needs, both stated by the paper as requirements of a good schedule
+// (section "Introduction": load-balanced parallel loops; section "The GEMM microkernel": the
+// microkernel must keep the vector/matrix unit busy):
+//   * a matrix-core term: the MFMA cycles of the busiest SIMD after the workgroups are dealt to
+//     256 compute units, divided by an issue efficiency that depends on the wave tile and the
+//     stage depth;
+//   * the data term weights each reuse by the bytes that actually travel (the operand panel times
+//     the number of times it is fetched) instead of by the working-set size alone.
+// The predicted time is max(matrix-core term, data term) + fixed costs; the lowest wins, as in
+// the paper's ranking (lower cost = higher rank).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+#include "internal.hpp"
+
+namespace polydl {
+
+// ---- hardware table (MI355X; capacities are public figures, rates are measured or assumed) -----
+struct Level {
+    const char *name;
+    double capacity;      // bytes available to one reuse scope at this level
+    double gbytes_per_s;  // aggregate rate the whole chip sustains from this level
+};
+static const Level kLevels[4] = {
+    {"acc", 64.0 * 1024, 1e9},              // accumulator registers of one wave (256 regs x 64 lanes)
+    {"lds", 80.0 * 1024, 60000.0},          // half of a CU's 160 KB: two workgroups share a CU
+    {"l2", 4.0 * 1024 * 1024, 16000.0},     // one XCD's L2
+    {"mall", 256.0 * 1024 * 1024, 8000.0},  // Infinity Cache
+};
+static const double kHbmGBs = 4500.0;       // sustained mixed read/write HBM rate
+static const double kAtomicGBs = 450.0;     // float atomic adds into L2 when a lane owns adjacent columns (stride-2
+                                            // or stride-4 lanes per instruction); contiguous lanes run about 6x faster
+static const double kClockHz = 2.4e9;
+static const int kCUs = 256, kSimdsPerCU = 4, kXcds = 8;
+static const double kLaunchUs = 2.5;        // one kernel launch inside a stream
+
+void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem)
+{
+    std::vector<double> sorted(ws, ws + n);
+    std::sort(sorted.begin(), sorted.end());
+    for (int i = 0; i < nlevels; ++i) levels[i] = 0;
+    *mem = 0;
+    for (double w : sorted) {
+        bool placed = false;
+        for (int i = 0; i < nlevels && !placed; ++i)
+            if (w + levels[i] <= sizes[i]) {
+                levels[i] += w;
+                placed = true;
+            }
+        if (!placed) *mem += w;
+    }
+}
+
+double reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight)
+{
+    double c = mem * mem_weight;
+    for (int i = 0; i < nlevels; ++i) c += levels[i] * weights[i];
+    return c;
+}
+
+// level index (0..3) a working set of `bytes` is served from when placed alone, 4 = memory
+static int level_of(double bytes)
+{
+    for (int i = 0; i < 4; ++i)
+        if (bytes <= kLevels[i].capacity) return i;
+    return 4;
+}
+static double rate_of(int level) { return level < 4 ? kLevels[level].gbytes_per_s : kHbmGBs; }
+
+struct Shape {   // the GEMM a candidate works on
+    double Mg, Ng, Kg;           // output rows, output columns, reduction length (padded as executed)
+    double a_bytes, b_bytes, d_bytes;   // operand and result tensors
+    double b_tile_bytes;         // B-side bytes one workgroup fetches for its whole reduction
+};
+
+struct Cand {
+    int bm, bn, wm, wn, threads;
+    int split_k;
+    double steps_per_stage;      // MFMA k-steps between two barriers
+    double lds_bytes;
+    double loop_eff;             // matrix-core share of the reduction loop's time, large wave tile, deep stage
+    double wg_overhead_cycles;   // cycles a wave spends outside the reduction loop (setup, first loads, stores)
+    double kernel_fixed_us;      // launch, first-stage latency and the store tail that nothing overlaps
+    int max_waves_per_simd;
+};
+
+// Constants below were fitted to an exhaustive sweep of the compiled family on the ResNet-50-shaped
+// suite (time against reduction length, workgroup count and wave tile).
+static void model(const Shape &s, const Cand &c, polydl_model_report *r)
+{
+    std::memset(r, 0, sizeof(*r));
+    const double tiles_m = std::ceil(s.Mg / c.bm), tiles_n = std::ceil(s.Ng / c.bn);
+    const double wgs = tiles_m * tiles_n * c.split_k;
+    const double waves_per_wg = c.threads / 64.0;
+    const double mb = c.wm / 32.0, nb = c.wn / 32.0;
+    // ---- matrix-core term -----------------------------------------------------------------
+    // Workgroups are dealt to the 256 CUs; a SIMD runs the waves it is given one after another
+    // (two at a time share its matrix core), so the busiest SIMD sets the time: this is the
+    // load-balance requirement on the parallel loops.
+    const double steps = std::ceil(s.Kg / 2.0 / c.split_k);               // rank-2 updates per wave
+    const double wgs_on_busiest_cu = std::ceil(wgs / kCUs);
+    const double waves_on_busiest_simd = std::ceil(wgs_on_busiest_cu * waves_per_wg / kSimdsPerCU);
+    double resident = std::min<double>(c.max_waves_per_simd, std::floor(2.0 * kLevels[1].capacity / c.lds_bytes) *
+                                                                 waves_per_wg / kSimdsPerCU);
+    resident = std::max(1.0, std::min(resident, waves_on_busiest_simd));
+    // issue efficiency: small wave tiles spend more issue slots per MFMA on operand reads and
+    // address updates; every stage pays a barrier and an LDS round trip; a SIMD holding a single
+    // wave cannot hide either
+    double eff = c.loop_eff * (1.0 - 0.16 / (mb * nb));
+    eff *= c.steps_per_stage / (c.steps_per_stage + 1.0 / (mb * nb));
+    if (resident < 2) eff *= 0.72;
+    else if (resident * mb * nb < 4) eff *= 0.85;   // two small waves leave gaps a third would fill
+    // setup plus an epilogue that grows with the accumulators a lane has to store
+    const double overhead = c.wg_overhead_cycles * (0.5 + 0.5 * mb * nb / 2.0);
+    const double wave_cycles = steps * mb * nb * 64.0 / eff + overhead;
+    const double mfma_us = waves_on_busiest_simd * wave_cycles / kClockHz * 1e6;
+    // ---- working sets (bytes) and where algorithm 2 places them -------------------------------
+    const double ws_acc = (double)c.wm * c.wn * 4;                         // accumulators over the reduction
+    const double ws_stage = c.lds_bytes;                                   // staged operands, shared by the waves
+    const double a_panel = c.bm * s.Kg * 4;                                // A row panel between two column tiles
+    const double ws_col_step = a_panel + s.b_tile_bytes + (double)c.bm * c.bn * 4;
+    // reuse across workgroups that run together on one XCD (the dependence spans the parallel
+    // loop): the footprint of everything resident there
+    const double res_wgs = std::min(wgs, (double)kCUs / kXcds * std::max(1.0, resident * kSimdsPerCU / waves_per_wg));
+    const double dm = std::min(tiles_m, res_wgs), dn = std::max(1.0, std::ceil(res_wgs / tiles_m));
+    const double ws_par = dm * a_panel + dn * s.b_tile_bytes;
+    const double ws_all = s.a_bytes + s.b_bytes + s.d_bytes;
+    const double ws[5] = {ws_acc, ws_stage, ws_col_step, ws_par, ws_all};
+    double sizes[4];
+    for (int i = 0; i < 4; ++i) sizes[i] = kLevels[i].capacity;
+    reuse_bucket(5, ws, 4, sizes, r->level_bytes, &r->mem_bytes);
+    double weights[4];
+    for (int i = 0; i < 4; ++i) weights[i] = 1.0 / kLevels[i].gbytes_per_s;
+    r->eq1_cost = reuse_cost(4, r->level_bytes, r->mem_bytes, weights, 1.0 / kHbmGBs);
+    r->n_ws = 5;
+    for (int i = 0; i < 5; ++i) r->ws[i] = ws[i];
+    // ---- data term: bytes that travel, charged at the level their reuse is served from -------
+    // A is fetched once per column tile, B once per row tile; each from the level that holds the
+    // footprint of the workgroups running together, else from where the whole tensor fits
+    const double a_traffic = tiles_n * s.a_bytes, b_traffic = tiles_m * tiles_n * s.b_tile_bytes;
+    const int shared_level = std::max(2, level_of(ws_par));
+    const int a_level = std::min(shared_level, std::max(2, level_of(s.a_bytes)));
+    const int b_level = std::min(shared_level, std::max(2, level_of(s.b_bytes)));
+    double mem_us = 0;
+    mem_us += (a_traffic - s.a_bytes) / rate_of(a_level) * 1e-3;           // re-fetches
+    mem_us += (b_traffic > s.b_bytes ? b_traffic - s.b_bytes : 0) / rate_of(b_level) * 1e-3;
+    mem_us += (s.a_bytes + s.b_bytes + s.d_bytes) / kHbmGBs * 1e-3;        // compulsory
+    double fixed = c.kernel_fixed_us;
+    if (c.split_k > 1) {
+        // every part adds its tile to the output with atomics; a zero fill before and a bias /
+        // activation pass after, each a launch and a sweep over the output
+        // the atomic adds run in the epilogues, after the matrix-core work, so they add to it
+        fixed += c.split_k * s.d_bytes / (nb > 1 ? kAtomicGBs : 6.0 * kAtomicGBs) * 1e-3;
+        fixed += 2 * kLaunchUs + 3.0 * s.d_bytes / kHbmGBs * 1e-3;
+    }
+    r->mfma_us = mfma_us;
+    r->mem_us = mem_us;
+    r->fixed_us = fixed;
+    r->predicted_us = std::max(mfma_us, mem_us) + fixed;
+    r->workgroups = (int)std::min(wgs, 2e9);
+    r->simd_load = waves_on_busiest_simd;
+}
+
+// ---- convolution ---------------------------------------------------------------------------------
+static double conv_patch_rows(const ConvProblem &q, int bn)
+{
+    const double PQ = (double)q.P * q.Q, Ng = q.N * PQ;
+    const double run = std::min<double>(bn, Ng);
+    const double rows_out = std::min<double>(std::ceil((run - 1) / q.Q) + 1, (double)q.N * q.P);
+    const double imgs = std::min<double>(std::ceil((run - 1) / PQ) + 1, q.N);
+    const double prs = q.R == 1 ? 1 : q.stride;
+    return rows_out * prs + imgs * std::max(0.0, q.R - prs);
+}
+
+static Shape conv_shape(const ConvProblem &q, int algo, int bn, int cb)
+{
+    Shape s;
+    const double RS = (double)q.R * q.S;
+    s.Mg = q.K;
+    s.Ng = (double)q.N * q.P * q.Q;
+    const double cexec = algo == 1 ? std::ceil((double)q.C / cb) * cb : q.C;
+    s.Kg = cexec * RS;
+    s.a_bytes = (double)q.K * q.C * RS * 4;
+    s.b_bytes = (double)q.N * q.C * q.H * q.W * 4;
+    s.d_bytes = (double)q.N * q.K * q.P * q.Q * 4;
+    if (algo == 1) {
+        const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
+        s.b_tile_bytes = q.C * conv_patch_rows(q, bn) * wp * 4;            // rows staged once per channel
+    } else {
+        s.b_tile_bytes = (double)bn * q.C * RS * 4;                        // every tap gathered again
+    }
+    return s;
+}
+
+void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r)
+{
+    const double RS = (double)q.R * q.S;
+    Cand c;
+    c.bm = cfg.bm; c.bn = cfg.bn; c.wm = cfg.wm; c.wn = cfg.wn; c.threads = threads;
+    c.split_k = std::max(1, cfg.split_k);
+    if (cfg.algo == 1) {
+        const int cb = std::max(2, cfg.cb);
+        const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
+        c.steps_per_stage = cb / 2.0 * RS;
+        c.lds_bytes = 2.0 * (cfg.bm * (cb * RS + 1) + cb * conv_patch_rows(q, cfg.bn) * wp) * 4;
+        c.loop_eff = 0.74;
+        c.wg_overhead_cycles = 9000;
+        c.kernel_fixed_us = 14.0;
+        c.max_waves_per_simd = 2;
+    } else {
+        c.steps_per_stage = cfg.bk / 2.0;
+        c.lds_bytes = 2.0 * (cfg.bm * (cfg.bk + 4) + cfg.bk * (cfg.bn + 4)) * 4;
+        c.loop_eff = 0.84;
+        c.wg_overhead_cycles = 5000;
+        c.kernel_fixed_us = 10.0;
+        c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 1 : ((cfg.wm * cfg.wn == 64 * 64) ? 2 : 4);
+    }
+    Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
+    model(s, c, r);
+}
+
+void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r)
+{
+    Shape s;
+    s.Mg = q.M; s.Ng = q.N; s.Kg = std::ceil((double)q.K / cfg.bk) * cfg.bk;
+    s.a_bytes = (double)q.M * q.K * 4;
+    s.b_bytes = (double)q.K * q.N * 4;
+    s.d_bytes = 2.0 * q.M * q.N * 4;                                       // C is read and written
+    s.b_tile_bytes = (double)cfg.bn * q.K * 4;
+    Cand c;
+    c.bm = cfg.bm; c.bn = cfg.bn; c.wm = cfg.wm; c.wn = cfg.wn; c.threads = threads;
+    c.split_k = std::max(1, cfg.split_k);
+    c.steps_per_stage = cfg.bk / 2.0;
+    c.lds_bytes = 2.0 * (cfg.bm * (cfg.bk + 4) + cfg.bk * (cfg.bn + 4)) * 4;
+    c.loop_eff = 0.84;
+    c.wg_overhead_cycles = 3000;
+    c.kernel_fixed_us = 6.0;
+    c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 1 : ((cfg.wm * cfg.wn == 64 * 64) ? 2 : 4);
+    model(s, c, r);
+    if (cfg.split_k > 1) {   // C accumulates in place: no fill and no bias pass around the kernel
+        r->fixed_us = c.kernel_fixed_us;
+        r->predicted_us = std::max(r->mfma_us, r->mem_us) + r->fixed_us;
+    }
+}
+
+static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+
+bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *best_rep)
+{
+    bool have = false;
+    polydl_model_report rep;
+    const int cpad = (q.C + 1) & ~1;
+    for (int i = 0; i < kNumPatchVariants; ++i) {
+        const PatchVariant &v = kPatchVariants[i];
+        for (int cb = 2; cb <= cpad && cb <= 64; cb += 2) {
+            if (cpad % cb != 0) continue;
+            if (v.conv(q, cb, 1, 0, nullptr, true) != hipSuccess) continue;
+            const int nstages = (q.C + cb - 1) / cb;
+            for (int sk : kSplits) {
+                if (sk > nstages) break;
+                polydl_tile_cfg c = {v.bm, v.bn, 0, v.wm, v.wn, sk, 0, 0, 1, cb};
+                model_conv(q, c, v.threads, &rep);
+                if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
+            }
+        }
+    }
+    const long Kg = (long)q.C * q.R * q.S;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        const long stages = (Kg + v.bk - 1) / v.bk;
+        for (int sk : kSplits) {
+            if (sk > stages || sk > 8) break;
+            polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0};
+            model_conv(q, c, v.threads, &rep);
+            if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
+        }
+    }
+    return have;
+}
+
+bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *best_rep)
+{
+    bool have = false;
+    polydl_model_report rep;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        const long stages = ((long)q.K + v.bk - 1) / v.bk;
+        for (int sk : kSplits) {
+            if (sk > stages) break;
+            for (int raster = 0; raster < 2; ++raster) {
+                polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, raster, 0, 0};
+                model_sgemm(q, c, v.threads, &rep);
+                if (raster == 1) rep.predicted_us *= 0.999;   // ties go to the XCD-aware order
+                if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
+            }
+        }
+    }
+    return have;
+}
+
+}  // namespace polydl
