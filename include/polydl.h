@@ -151,6 +151,8 @@ int polydl_num_variants(int kind);
 int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg);
 
 const char *polydl_status_string(int status);
+/* hipError_t of the most recent launch the runtime refused (POLYDL_ERR_LAUNCH), 0 if none. */
+int polydl_last_hip_error(void);
 
 #ifdef __cplusplus
 }

@@ -9,6 +9,11 @@ if not os.path.exists(LIB_PATH):
     raise ImportError("libpolydl.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
                       "(or python paper_2006_02230_amd/build.py) first; there is no fallback path")
 
+# PyTorch ships its own copy of the HIP runtime (same soname as the system one) and owns the
+# device memory and streams handed to this library, so it must be the copy this library binds to:
+# load torch first, then the dynamic linker resolves libamdhip64 to the one already in the process.
+import torch  # noqa: E402,F401
+
 lib = ctypes.CDLL(LIB_PATH)
 
 ACT = {None: 0, "none": 0, "relu": 1, "relu6": 2, 0: 0, 1: 1, 2: 2, False: 0, True: 1}
@@ -17,7 +22,11 @@ ACT = {None: 0, "none": 0, "relu": 1, "relu6": 2, 0: 0, 1: 1, 2: 2, False: 0, Tr
 class PolydlError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
-        super().__init__("%s: %s (%d)" % (where, status_string(status), status))
+        extra = ""
+        if status == -4:
+            lib.polydl_last_hip_error.restype = ctypes.c_int
+            extra = ", hipError_t %d" % lib.polydl_last_hip_error()
+        super().__init__("%s: %s (%d%s)" % (where, status_string(status), status, extra))
 
 
 class TileCfg(ctypes.Structure):

@@ -1,6 +1,8 @@
 // The C ABI: argument checks, variant choice, launch.  No data is touched on the host.
 #include <hip/hip_runtime.h>
 #include <atomic>
+#include <array>
+#include <map>
 #include <mutex>
 #include "internal.hpp"
 #include "variants.hpp"
@@ -22,9 +24,18 @@ const PatchVariant kPatchVariants[] = {POLYDL_PATCH_FAMILY(POLYDL_PATCH_ROW)};
 const int kNumPatchVariants = (int)(sizeof(kPatchVariants) / sizeof(kPatchVariants[0]));
 
 static std::mutex g_mu;
+static std::atomic<int> g_last_hip_error{0};
+static int launch_failed(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return POLYDL_ERR_LAUNCH;
+}
 static bool g_have_override = false;
 static polydl_tile_cfg g_override;
 static polydl_tile_cfg g_last = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+// picks already made, keyed by the problem's dimensions (the ranking depends on nothing else)
+static std::map<std::array<int, 9>, polydl_tile_cfg> g_conv_plans;
+static std::map<std::array<int, 3>, polydl_tile_cfg> g_sgemm_plans;
 
 static const Variant *find_variant(const polydl_tile_cfg &c)
 {
@@ -103,9 +114,16 @@ static int sgemm_impl(int M, int N, int K, const float *A, const float *B, float
         std::lock_guard<std::mutex> lk(g_mu);
         cfg = g_override;
         if (!g_have_override) {
-            polydl_model_report rep;
-            SgemmProblem pq{M, N, K, A, B, C};
-            if (!pick_sgemm(pq, &cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+            const std::array<int, 3> key = {M, N, K};
+            auto it = g_sgemm_plans.find(key);
+            if (it != g_sgemm_plans.end()) {
+                cfg = it->second;
+            } else {
+                polydl_model_report rep;
+                SgemmProblem pq{M, N, K, A, B, C};
+                if (!pick_sgemm(pq, &cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+                g_sgemm_plans[key] = cfg;
+            }
         }
     }
     const Variant *v = find_variant(cfg);
@@ -117,7 +135,7 @@ static int sgemm_impl(int M, int N, int K, const float *A, const float *B, float
     if (tiles >= 0x7FFFFFFFull || cfg.split_k > 65535) return POLYDL_ERR_UNSUPPORTED;
     SgemmProblem q{M, N, K, A, B, C};
     hipError_t e = v->sgemm(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
-    if (e != hipSuccess) return POLYDL_ERR_LAUNCH;
+    if (e != hipSuccess) return launch_failed(e);
     std::lock_guard<std::mutex> lk(g_mu);
     g_last = cfg;
     return POLYDL_OK;
@@ -143,8 +161,16 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         cfg = g_override;
     }
     if (!forced) {
-        polydl_model_report rep;
-        if (!pick_conv(q, &cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+        const std::array<int, 9> key = {N, C, H, W, K, R, S, stride, pad};
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = g_conv_plans.find(key);
+        if (it != g_conv_plans.end()) {
+            cfg = it->second;
+        } else {
+            polydl_model_report rep;
+            if (!pick_conv(q, &cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
+            g_conv_plans[key] = cfg;
+        }
     }
     if (cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
     if (cfg.algo == 1) {
@@ -154,7 +180,8 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         if (cfg.cb < 2 || (cfg.cb & 1)) return POLYDL_ERR_UNSUPPORTED;
         const int sk = cfg.split_k < 1 ? 1 : cfg.split_k;
         if (pv->conv(q, cfg.cb, sk, cfg.raster, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
-        if (pv->conv(q, cfg.cb, sk, cfg.raster, (hipStream_t)stream, false) != hipSuccess) return POLYDL_ERR_LAUNCH;
+        hipError_t pe = pv->conv(q, cfg.cb, sk, cfg.raster, (hipStream_t)stream, false);
+        if (pe != hipSuccess) return launch_failed(pe);
         std::lock_guard<std::mutex> lk(g_mu);
         g_last = cfg;
         return POLYDL_OK;
@@ -165,7 +192,7 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     const int64_t span = (v->bn / (P * Q) + 2) * CHW * 4;
     if (span >= 0x7FFFFFF0ll || (int64_t)v->bm * Kg * 4 >= 0x7FFFFFF0ll) return POLYDL_ERR_UNSUPPORTED;
     hipError_t e = v->conv(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
-    if (e != hipSuccess) return POLYDL_ERR_LAUNCH;
+    if (e != hipSuccess) return launch_failed(e);
     std::lock_guard<std::mutex> lk(g_mu);
     g_last = cfg;
     return POLYDL_OK;
@@ -347,6 +374,8 @@ int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg)
     else cfg_of_patch(kPatchVariants[index - kNumVariants], 0, 0, cfg);
     return POLYDL_OK;
 }
+
+int polydl_last_hip_error(void) { return g_last_hip_error.load(); }
 
 const char *polydl_status_string(int status)
 {

@@ -208,6 +208,7 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     a.split_k = (stages + stages_per - 1) / stages_per;
     a.raster = raster;
     a.act = q.act;
+    clear_stale_hip_error();
     const size_t nout = (size_t)q.N * q.K * a.PQ;
     if (a.split_k > 1 && launch_fill_zero(q.out, nout, stream) != hipSuccess) return hipGetLastError();
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);

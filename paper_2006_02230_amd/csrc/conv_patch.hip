@@ -406,6 +406,7 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     a.split_k = (a.nstages + a.stages_per_split - 1) / a.stages_per_split;
     if (a.split_k > 65535) return hipErrorInvalidConfiguration;
     if (dry) return hipSuccess;
+    clear_stale_hip_error();
     const size_t nout = (size_t)q.N * q.K * a.PQ;
     if (a.split_k > 1 && launch_fill_zero(q.out, nout, stream) != hipSuccess) return hipGetLastError();
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);

@@ -56,6 +56,11 @@ hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
 hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st);
 hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n, int act, hipStream_t st);
 
+// hipGetLastError() reports the last error of any HIP call of this thread, including benign ones
+// left by the caller (an event query that was not ready, say).  Launchers clear that state first
+// so that what they return is about their own launch.
+inline void clear_stale_hip_error() { (void)hipGetLastError(); }
+
 // picker.cpp
 void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem);
 double reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight);

@@ -110,6 +110,7 @@ __global__ void bias_act_kernel(float *y, const float *bias, int K, int PQ, size
 
 hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st)
 {
+    clear_stale_hip_error();
     unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, y, n);
     return hipGetLastError();
@@ -117,6 +118,7 @@ hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st)
 
 hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n, int act, hipStream_t st)
 {
+    clear_stale_hip_error();
     unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
     hipLaunchKernelGGL(bias_act_kernel, dim3(blocks), dim3(256), 0, st, y, bias, K, PQ, n, act);
     return hipGetLastError();
@@ -124,6 +126,7 @@ hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n,
 
 hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int b, bool to_blocked, hipStream_t st)
 {
+    clear_stale_hip_error();
     int Cb = (C + b - 1) / b;
     dim3 grid((unsigned)((HW + 255) / 256), (unsigned)Cb, (unsigned)N);
     size_t lds = (size_t)b * 257 * 4;
@@ -134,6 +137,7 @@ hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int 
 
 hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st)
 {
+    clear_stale_hip_error();
     int Kb = (K + bk - 1) / bk, Cb = (C + bc - 1) / bc;
     size_t total = (size_t)Kb * Cb * RS * bc * bk;
     hipLaunchKernelGGL(kcrsck_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, wt, dst, K, C, RS,
@@ -143,6 +147,7 @@ hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int 
 
 hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t total, hipStream_t st)
 {
+    clear_stale_hip_error();
     unsigned blocks = (unsigned)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
     hipLaunchKernelGGL(bias_add_kernel, dim3(blocks), dim3(256), 0, st, y, bias, K, PQ, total);
     return hipGetLastError();
@@ -150,6 +155,7 @@ hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t to
 
 hipError_t launch_act(float *y, size_t total, int act, hipStream_t st)
 {
+    clear_stale_hip_error();
     size_t work = (total + 3) / 4;
     unsigned blocks = (unsigned)((work + 255) / 256 < 8192 ? (work + 255) / 256 : 8192);
     hipLaunchKernelGGL(act_kernel, dim3(blocks), dim3(256), 0, st, y, total, act);

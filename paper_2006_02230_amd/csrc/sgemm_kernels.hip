@@ -96,6 +96,7 @@ static hipError_t sgemm_launch(const SgemmProblem &q, int split_k, int raster, h
     split_k = stages > 0 ? (stages + stages_per - 1) / stages_per : 1;
     a.split_k = split_k;
     a.raster = raster;
+    clear_stale_hip_error();
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k), block(T::NT);
     const bool avec = (q.K % 4 == 0) && ((uintptr_t)q.A % 16 == 0);
     const bool bvec = (q.N % 4 == 0) && ((uintptr_t)q.B % 16 == 0);
