@@ -19,7 +19,8 @@ const Variant kVariants[] = {POLYDL_TILE_FAMILY(POLYDL_VARIANT_ROW)};
 const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 #define POLYDL_PATCH_ROW(BM, BN, BK, WM, WN) \
-    {BM, BN, WM, WN, (BM / WM) * (BN / WN) * 64, conv_patch_launch_##BM##x##BN##_##WM##x##WN},
+    {BM, BN, WM, WN, (BM / WM) * (BN / WN) * 64, conv_patch_launch_##BM##x##BN##_##WM##x##WN,   \
+     conv_patch_class_##BM##x##BN##_##WM##x##WN},
 const PatchVariant kPatchVariants[] = {POLYDL_PATCH_FAMILY(POLYDL_PATCH_ROW)};
 const int kNumPatchVariants = (int)(sizeof(kPatchVariants) / sizeof(kPatchVariants[0]));
 
@@ -296,7 +297,9 @@ int polydl_model_conv2d(int N, int C, int H, int W, int K, int R, int S, int str
                                       : (cfg->algo == 0 && find_variant(*cfg) != nullptr);
     if (!known || !conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
     ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
-    model_conv(q, *cfg, threads_of(*cfg), report);
+    int rc = 0;
+    if (cfg->algo == 1) rc = find_patch_variant(*cfg)->reg_class(q, cfg->cb < 2 ? 2 : cfg->cb);
+    model_conv(q, *cfg, threads_of(*cfg), rc, report);
     return POLYDL_OK;
 }
 

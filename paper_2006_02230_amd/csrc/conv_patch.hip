@@ -427,8 +427,23 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb, int sk, int r,    \
                                                            hipStream_t st, bool dry)                     \
     {                                                                                                    \
+        /* the instantiation with fewer per-thread passes needs fewer registers: more waves per SIMD */ \
+        if (conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, true) == hipSuccess)        \
+            return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, dry);                \
         return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, sk, r, st, dry);                   \
     }
 POLYDL_PATCH_FAMILY(POLYDL_DEFINE_CONV_PATCH)
+
+// 1 if the problem runs in the instantiation with few per-thread passes (fewer registers, more
+// waves per SIMD), 0 if it needs the large one, -1 if neither holds it.
+#define POLYDL_DEFINE_PATCH_CLASS(BM, BN, BK, WM, WN)                                                   \
+    int conv_patch_class_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb)                         \
+    {                                                                                                    \
+        if (conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, 1, 0, nullptr, true) == hipSuccess)   \
+            return 1;                                                                                    \
+        return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, 1, 0, nullptr, true) == hipSuccess \
+                   ? 0 : -1;                                                                             \
+    }
+POLYDL_PATCH_FAMILY(POLYDL_DEFINE_PATCH_CLASS)
 
 }  // namespace polydl

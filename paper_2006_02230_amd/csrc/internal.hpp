@@ -34,6 +34,7 @@ struct PatchVariant {
     int bm, bn, wm, wn;
     int threads;
     hipError_t (*conv)(const ConvProblem &, int cb, int split_k, int raster, hipStream_t, bool dry);
+    int (*reg_class)(const ConvProblem &, int cb);   // 1 small-register instantiation, 0 large, -1 none
 };
 
 extern const Variant kVariants[];
@@ -47,7 +48,8 @@ extern const int kNumPatchVariants;
     hipError_t conv_launch_##BM##x##BN##x##BK##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t);
 
 #define POLYDL_DECLARE_PATCH_LAUNCHER(BM, BN, BK, WM, WN) \
-    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, int, hipStream_t, bool);
+    hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, int, hipStream_t, bool); \
+    int conv_patch_class_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int);
 
 hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int b, bool to_blocked, hipStream_t st);
 hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st);
@@ -64,7 +66,7 @@ inline void clear_stale_hip_error() { (void)hipGetLastError(); }
 // picker.cpp
 void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem);
 double reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight);
-void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r);
+void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, int reg_class, polydl_model_report *r);
 void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r);
 bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
 bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);

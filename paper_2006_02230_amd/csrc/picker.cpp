@@ -123,7 +123,7 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
     if (resident < 2) eff *= 0.72;
     else if (resident * mb * nb < 4) eff *= 0.85;   // two small waves leave gaps a third would fill
     // setup plus an epilogue that grows with the accumulators a lane has to store
-    const double overhead = c.wg_overhead_cycles * (0.5 + 0.5 * mb * nb / 2.0);
+    const double overhead = c.wg_overhead_cycles * (0.3 + 0.7 * mb * nb / 2.0);
     const double wave_cycles = steps * mb * nb * 64.0 / eff + overhead;
     const double mfma_us = waves_on_busiest_simd * wave_cycles / kClockHz * 1e6;
     // ---- working sets (bytes) and where algorithm 2 places them -------------------------------
@@ -204,7 +204,7 @@ static Shape conv_shape(const ConvProblem &q, int algo, int bn, int cb)
     return s;
 }
 
-void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r)
+void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, int reg_class, polydl_model_report *r)
 {
     const double RS = (double)q.R * q.S;
     Cand c;
@@ -218,7 +218,15 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, p
         c.loop_eff = 0.74;
         c.wg_overhead_cycles = 9000;
         c.kernel_fixed_us = 14.0;
+        // the small-register instantiation holds 5 waves per SIMD with a 32x32 wave tile, 3 with
+        // 64x32 in the 128x64 tile; everything else 2
         c.max_waves_per_simd = 2;
+        if (reg_class == 1 && cfg.wm * cfg.wn == 32 * 32) {
+            c.max_waves_per_simd = 5;      // enough waves to cover each other's loads and stores
+            c.loop_eff = 0.92;
+            c.wg_overhead_cycles = 4000;
+        }
+        else if (reg_class == 1 && cfg.bm == 128 && cfg.bn == 64) c.max_waves_per_simd = 3;
     } else {
         c.steps_per_stage = cfg.bk / 2.0;
         c.lds_bytes = 2.0 * (cfg.bm * (cfg.bk + 4) + cfg.bk * (cfg.bn + 4)) * 4;
@@ -267,12 +275,13 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
         const PatchVariant &v = kPatchVariants[i];
         for (int cb = 2; cb <= cpad && cb <= 64; cb += 2) {
             if (cpad % cb != 0) continue;
-            if (v.conv(q, cb, 1, 0, nullptr, true) != hipSuccess) continue;
+            const int rc = v.reg_class(q, cb);
+            if (rc < 0) continue;
             const int nstages = (q.C + cb - 1) / cb;
             for (int sk : kSplits) {
                 if (sk > nstages) break;
                 polydl_tile_cfg c = {v.bm, v.bn, 0, v.wm, v.wn, sk, 0, 0, 1, cb};
-                model_conv(q, c, v.threads, &rep);
+                model_conv(q, c, v.threads, rc, &rep);
                 if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
             }
         }
@@ -284,7 +293,7 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
         for (int sk : kSplits) {
             if (sk > stages || sk > 8) break;
             polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0};
-            model_conv(q, c, v.threads, &rep);
+            model_conv(q, c, v.threads, 0, &rep);
             if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
         }
     }
