@@ -96,6 +96,30 @@ int polydl_nchw_to_nchwc(int N, int C, int H, int W, int b, const float *in, flo
 int polydl_nchwc_to_nchw(int N, int C, int H, int W, int b, const float *in, float *out, void *stream);
 int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const float *wt, float *out, void *stream);
 
+/* ---- bfloat16 inputs, float32 accumulation and output -------------------------------------------
+ * The same convolution with `in` and `wt` given as bfloat16 bit patterns (uint16_t; the paper is
+ * fp32 only, this is the reduced-precision configuration of the workload list).  Products of two
+ * bfloat16 values are exact in float32, sums are float32 on the matrix cores
+ * (v_mfma_f32_32x32x16_bf16), bias and out are float32.
+ *
+ * The kernel consumes the blocked layouts with a channel block of eight (16 bytes = one matrix-
+ * core operand): in8c = [N][ceil(C/8)][H][W][8], wt8c = [K][ceil(C/8)][R][S][8] (that is KCRSck with
+ * bc = 8, bk = 1), channels beyond C zero.  polydl_nchw_to_nchwc_bf16 / polydl_kcrs_to_kcrsck_bf16
+ * produce them (bit-exact permutations).  polydl_conv2d_fwd_bf16_blocked takes blocked tensors
+ * (16-byte aligned); polydl_conv2d_fwd_bf16 takes NCHW / KCRS bfloat16 and blocks them into a
+ * caller-provided workspace of at least polydl_conv2d_bf16_workspace_bytes() bytes (256-byte
+ * aligned device memory, contents undefined afterwards) before running the same kernel. */
+int polydl_nchw_to_nchwc_bf16(int N, int C, int H, int W, int b, const uint16_t *in, uint16_t *out, void *stream);
+int polydl_kcrs_to_kcrsck_bf16(int K, int C, int R, int S, int bc, int bk, const uint16_t *wt, uint16_t *out,
+                               void *stream);
+int polydl_conv2d_fwd_bf16_blocked(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                   const uint16_t *in8c, const uint16_t *wt8c, const float *bias, float *out,
+                                   int act /* polydl_act */, void *stream);
+size_t polydl_conv2d_bf16_workspace_bytes(int N, int C, int H, int W, int K, int R, int S);
+int polydl_conv2d_fwd_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           const uint16_t *in, const uint16_t *wt, const float *bias, float *out, int act,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- the element-wise operators as separate kernels (section "Operator Fusion": what the fused
  * epilogue of polydl_conv2d_fwd replaces; kept for the fused-versus-unfused comparison) ---------
  * polydl_bias_add:   y[n][k][p][q] += bias[k], in place on an NKPQ tensor.

@@ -79,6 +79,15 @@ lib.polydl_pick_conv2d.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), ctypes.PO
 lib.polydl_pick_sgemm.argtypes = [_i] * 3 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ModelReport)]
 for _f in (lib.polydl_model_conv2d, lib.polydl_model_sgemm, lib.polydl_pick_conv2d, lib.polydl_pick_sgemm):
     _f.restype = _i
+lib.polydl_nchw_to_nchwc_bf16.argtypes = [_i] * 5 + [_p, _p, _p]
+lib.polydl_kcrs_to_kcrsck_bf16.argtypes = [_i] * 6 + [_p, _p, _p]
+lib.polydl_conv2d_fwd_bf16_blocked.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
+lib.polydl_conv2d_bf16_workspace_bytes.argtypes = [_i] * 7
+lib.polydl_conv2d_bf16_workspace_bytes.restype = ctypes.c_size_t
+lib.polydl_conv2d_fwd_bf16.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p, ctypes.c_size_t, _p]
+for _f in (lib.polydl_nchw_to_nchwc_bf16, lib.polydl_kcrs_to_kcrsck_bf16, lib.polydl_conv2d_fwd_bf16_blocked,
+           lib.polydl_conv2d_fwd_bf16):
+    _f.restype = _i
 lib.polydl_set_tile_override.argtypes = [ctypes.POINTER(TileCfg)]
 lib.polydl_get_last_tile.argtypes = [ctypes.POINTER(TileCfg)]
 lib.polydl_num_variants.argtypes = [_i]
@@ -113,6 +122,68 @@ def _dev(t, name):
     if not (t.is_cuda and t.is_contiguous() and t.dtype.is_floating_point and t.element_size() == 4):
         raise TypeError("%s must be a contiguous float32 tensor in device memory" % name)
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _dev16(t, name):
+    """Device pointer of a contiguous 2-byte-element tensor holding bfloat16 bit patterns."""
+    if not (t.is_cuda and t.is_contiguous() and t.element_size() == 2):
+        raise TypeError("%s must be a contiguous 16-bit tensor in device memory" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def nchw_to_nchwc_bf16(x, b=8, stream=None):
+    """polydl_nchw_to_nchwc_bf16 on a 16-bit NCHW tensor: returns [N][ceil(C/b)][H][W][b]."""
+    import torch
+    N, C, H, W = x.shape
+    out = torch.empty((N, -(-C // b), H, W, b), dtype=x.dtype, device=x.device)
+    _check(lib.polydl_nchw_to_nchwc_bf16(N, C, H, W, b, _dev16(x, "x"), _dev16(out, "out"), _stream_ptr(stream)),
+           "polydl_nchw_to_nchwc_bf16")
+    return out
+
+
+def kcrs_to_kcrsck_bf16(w, bc=8, bk=1, stream=None):
+    """polydl_kcrs_to_kcrsck_bf16: returns [ceil(K/bk)][ceil(C/bc)][R][S][bc][bk] (16-bit elements)."""
+    import torch
+    K, C, R, S = w.shape
+    out = torch.empty((-(-K // bk), -(-C // bc), R, S, bc, bk), dtype=w.dtype, device=w.device)
+    _check(lib.polydl_kcrs_to_kcrsck_bf16(K, C, R, S, bc, bk, _dev16(w, "w"), _dev16(out, "out"),
+                                          _stream_ptr(stream)), "polydl_kcrs_to_kcrsck_bf16")
+    return out
+
+
+def conv2d_fwd_bf16_blocked(x8c, w8c, C, bias=None, out=None, stride=1, pad=0, act=None, stream=None):
+    """polydl_conv2d_fwd_bf16_blocked: x8c [N][C/8][H][W][8], w8c [K][C/8][R][S][8][1] bf16 bits."""
+    import torch
+    N, _, H, W, _ = x8c.shape
+    K, _, R, S = w8c.shape[:4]
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    if out is None:
+        out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.float32, device=x8c.device)
+    st = lib.polydl_conv2d_fwd_bf16_blocked(N, C, H, W, K, R, S, stride, pad, _dev16(x8c, "x8c"),
+                                            _dev16(w8c, "w8c"), _dev(bias, "bias"), _dev(out, "out"), ACT[act],
+                                            _stream_ptr(stream))
+    _check(st, "polydl_conv2d_fwd_bf16_blocked")
+    return out
+
+
+def conv2d_fwd_bf16(x, w, bias=None, out=None, stride=1, pad=0, act=None, workspace=None, stream=None):
+    """polydl_conv2d_fwd_bf16 on 16-bit NCHW / KCRS tensors; allocates the workspace when not given."""
+    import torch
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    need = lib.polydl_conv2d_bf16_workspace_bytes(N, C, H, W, K, R, S)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.float32, device=x.device)
+    st = lib.polydl_conv2d_fwd_bf16(N, C, H, W, K, R, S, stride, pad, _dev16(x, "x"), _dev16(w, "w"),
+                                    _dev(bias, "bias"), _dev(out, "out"), ACT[act],
+                                    ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
+    _check(st, "polydl_conv2d_fwd_bf16")
+    return out
 
 
 def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None):

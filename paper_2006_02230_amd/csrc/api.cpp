@@ -1,6 +1,7 @@
 // The C ABI: argument checks, variant choice, launch.  No data is touched on the host.
 #include <hip/hip_runtime.h>
 #include <atomic>
+#include <algorithm>
 #include <array>
 #include <map>
 #include <mutex>
@@ -11,6 +12,7 @@ namespace polydl {
 
 POLYDL_TILE_FAMILY(POLYDL_DECLARE_LAUNCHERS)
 POLYDL_PATCH_FAMILY(POLYDL_DECLARE_PATCH_LAUNCHER)
+POLYDL_PATCH_BF16_FAMILY(POLYDL_DECLARE_PATCH_BF16_LAUNCHER)
 
 #define POLYDL_VARIANT_ROW(BM, BN, BK, WM, WN)                                                     \
     {BM, BN, BK, WM, WN, (BM / WM) * (BN / WN) * 64, 2 * (BM * (BK + 4) + BK * (BN + 4)) * 4,      \
@@ -23,6 +25,11 @@ const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
      conv_patch_class_##BM##x##BN##_##WM##x##WN},
 const PatchVariant kPatchVariants[] = {POLYDL_PATCH_FAMILY(POLYDL_PATCH_ROW)};
 const int kNumPatchVariants = (int)(sizeof(kPatchVariants) / sizeof(kPatchVariants[0]));
+
+#define POLYDL_PATCH_BF16_ROW(BM, BN, BK, WM, WN) \
+    {BM, BN, WM, WN, (BM / WM) * (BN / WN) * 64, conv_patch_bf16_launch_##BM##x##BN##_##WM##x##WN, nullptr},
+const PatchVariant kPatchBf16Variants[] = {POLYDL_PATCH_BF16_FAMILY(POLYDL_PATCH_BF16_ROW)};
+const int kNumPatchBf16Variants = (int)(sizeof(kPatchBf16Variants) / sizeof(kPatchBf16Variants[0]));
 
 static std::mutex g_mu;
 static std::atomic<int> g_last_hip_error{0};
@@ -230,7 +237,7 @@ int polydl_nchw_to_nchwc(int N, int C, int H, int W, int b, const float *in, flo
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!in || !out) return POLYDL_ERR_NULL_POINTER;
     if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_nchwc(in, out, N, C, H * W, b, true, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    return launch_nchwc(in, out, N, C, H * W, b, true, 4, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
 }
 
 int polydl_nchwc_to_nchw(int N, int C, int H, int W, int b, const float *in, float *out, void *stream)
@@ -238,7 +245,7 @@ int polydl_nchwc_to_nchw(int N, int C, int H, int W, int b, const float *in, flo
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!in || !out) return POLYDL_ERR_NULL_POINTER;
     if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_nchwc(in, out, N, C, H * W, b, false, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    return launch_nchwc(in, out, N, C, H * W, b, false, 4, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
 }
 
 int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const float *wt, float *out, void *stream)
@@ -247,7 +254,125 @@ int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const floa
     if (!wt || !out) return POLYDL_ERR_NULL_POINTER;
     const int64_t total = (int64_t)((K + bk - 1) / bk) * bk * ((C + bc - 1) / bc) * bc * R * S;
     if (total >= (1ll << 39) || (int64_t)R * S >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_kcrsck(wt, out, K, C, R * S, bc, bk, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    return launch_kcrsck(wt, out, K, C, R * S, bc, bk, 4, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+int polydl_nchw_to_nchwc_bf16(int N, int C, int H, int W, int b, const uint16_t *in, uint16_t *out, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!in || !out) return POLYDL_ERR_NULL_POINTER;
+    if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
+    return launch_nchwc(in, out, N, C, H * W, b, true, 2, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+int polydl_kcrs_to_kcrsck_bf16(int K, int C, int R, int S, int bc, int bk, const uint16_t *wt, uint16_t *out,
+                               void *stream)
+{
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0 || bc <= 0 || bk <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!wt || !out) return POLYDL_ERR_NULL_POINTER;
+    const int64_t total = (int64_t)((K + bk - 1) / bk) * bk * ((C + bc - 1) / bc) * bc * R * S;
+    if (total >= (1ll << 39) || (int64_t)R * S >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
+    return launch_kcrsck(wt, out, K, C, R * S, bc, bk, 2, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+}
+
+// bf16 candidates are ranked with the fp32 patch model scaled by the instruction's rate: good
+// enough to choose tile and split, since the same load-balance and overhead terms dominate
+static bool pick_bf16(const ConvProblem &qb, polydl_tile_cfg *out)
+{
+    const int cunits = qb.C;
+    bool have = false;
+    double best = 0;
+    for (int i = 0; i < kNumPatchBf16Variants; ++i) {
+        const PatchVariant &v = kPatchBf16Variants[i];
+        for (int cb = 2; cb <= ((cunits + 1) & ~1) && cb <= 32; cb += 2) {
+            if (v.conv(qb, cb, 1, 0, nullptr, true) != hipSuccess) continue;
+            const int nstages = (cunits + cb - 1) / cb;
+            const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+            for (int sk : splits) {
+                if (sk > nstages) break;
+                polydl_tile_cfg c = {v.bm, v.bn, 0, v.wm, v.wn, sk, 1, 0, 1, cb};
+                polydl_model_report rep;
+                model_conv(qb, c, v.threads, v.wm * v.wn == 32 * 32 ? 1 : 0, &rep);
+                // one bf16 step does 8x the work of an fp32 step in half the cycles
+                double t = std::max(rep.mfma_us / 2.0, rep.mem_us) + rep.fixed_us;
+                if (!have || t < best) { best = t; *out = c; have = true; }
+            }
+        }
+    }
+    return have;
+}
+
+int polydl_conv2d_fwd_bf16_blocked(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                   const uint16_t *in8c, const uint16_t *wt8c, const float *bias, float *out,
+                                   int act, void *stream)
+{
+    int64_t P, Q;
+    if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
+    if (!in8c || !wt8c || !out) return POLYDL_ERR_NULL_POINTER;
+    if (act != POLYDL_ACT_NONE && act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6) return POLYDL_ERR_UNSUPPORTED;
+    if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
+    if (((uintptr_t)in8c & 15) || ((uintptr_t)wt8c & 15)) return POLYDL_ERR_UNSUPPORTED;   // 16-byte units
+    const int cunits = (C + 7) / 8;
+    ConvProblem q{N, cunits, H, W, K, R, S, stride, pad, (int)P, (int)Q, in8c, wt8c, bias, out, act};
+    polydl_tile_cfg cfg;
+    bool forced;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        forced = g_have_override;
+        cfg = g_override;
+    }
+    if (forced) {
+        if (cfg.algo != 1) return POLYDL_ERR_UNSUPPORTED;
+    } else if (!pick_bf16(q, &cfg)) {
+        return POLYDL_ERR_UNSUPPORTED;
+    }
+    const PatchVariant *pv = nullptr;
+    for (int i = 0; i < kNumPatchBf16Variants; ++i) {
+        const PatchVariant &v = kPatchBf16Variants[i];
+        if (v.bm == cfg.bm && v.bn == cfg.bn && v.wm == cfg.wm && v.wn == cfg.wn) pv = &v;
+    }
+    if (!pv) return POLYDL_ERR_UNSUPPORTED;
+    if (cfg.cb == 0) {
+        for (int cb = 2; cb <= ((cunits + 1) & ~1) && cb <= 32; cb += 2)
+            if (pv->conv(q, cb, 1, 0, nullptr, true) == hipSuccess) cfg.cb = cb;
+    }
+    if (cfg.cb < 2 || (cfg.cb & 1)) return POLYDL_ERR_UNSUPPORTED;
+    const int sk = cfg.split_k < 1 ? 1 : cfg.split_k;
+    if (pv->conv(q, cfg.cb, sk, cfg.raster, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
+    hipError_t e = pv->conv(q, cfg.cb, sk, cfg.raster, (hipStream_t)stream, false);
+    if (e != hipSuccess) return launch_failed(e);
+    cfg.layout = 1;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_last = cfg;
+    return POLYDL_OK;
+}
+
+size_t polydl_conv2d_bf16_workspace_bytes(int N, int C, int H, int W, int K, int R, int S)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0) return 0;
+    const size_t cu = ((size_t)C + 7) / 8;
+    const size_t in_b = ((size_t)N * cu * H * W * 16 + 255) / 256 * 256;
+    return in_b + (size_t)K * cu * R * S * 16;
+}
+
+int polydl_conv2d_fwd_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           const uint16_t *in, const uint16_t *wt, const float *bias, float *out, int act,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    int64_t P, Q;
+    if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
+    if (!in || !wt || !out || !workspace) return POLYDL_ERR_NULL_POINTER;
+    if (workspace_bytes < polydl_conv2d_bf16_workspace_bytes(N, C, H, W, K, R, S) || ((uintptr_t)workspace & 255))
+        return POLYDL_ERR_UNSUPPORTED;
+    const size_t cu = ((size_t)C + 7) / 8;
+    uint16_t *in8c = static_cast<uint16_t *>(workspace);
+    uint16_t *wt8c = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) +
+                                                  ((size_t)N * cu * H * W * 16 + 255) / 256 * 256);
+    int st = polydl_nchw_to_nchwc_bf16(N, C, H, W, 8, in, in8c, stream);
+    if (st != POLYDL_OK) return st;
+    st = polydl_kcrs_to_kcrsck_bf16(K, C, R, S, 8, 1, wt, wt8c, stream);
+    if (st != POLYDL_OK) return st;
+    return polydl_conv2d_fwd_bf16_blocked(N, C, H, W, K, R, S, stride, pad, in8c, wt8c, bias, out, act, stream);
 }
 
 int polydl_bias_add(int N, int K, int P, int Q, float *y, const float *bias, void *stream)

@@ -187,7 +187,8 @@ template <class T>
 static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hipStream_t stream)
 {
     ConvKArgs a;
-    a.in = q.in; a.wt = q.wt; a.bias = q.bias; a.out = q.out;
+    a.in = static_cast<const float *>(q.in); a.wt = static_cast<const float *>(q.wt);
+    a.bias = q.bias; a.out = q.out;
     a.C = q.C; a.H = q.H; a.W = q.W; a.K = q.K; a.R = q.R; a.S = q.S;
     a.stride = q.stride; a.pad = q.pad; a.P = q.P; a.Q = q.Q;
     a.PQ = q.P * q.Q; a.RS = q.R * q.S; a.HW = q.H * q.W; a.CHW = q.C * q.H * q.W;

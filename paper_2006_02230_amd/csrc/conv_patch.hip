@@ -22,8 +22,42 @@
 
 namespace polydl {
 
+// The reduction element the kernel moves and multiplies.
+// ElemF32:   one float; an MFMA step (v_mfma_f32_32x32x2_f32) consumes one tap of a channel pair.
+// ElemBF16x8: eight consecutive bfloat16 channels (16 bytes, the NCHW8c / KCRS8c unit); an MFMA
+//            step (v_mfma_f32_32x32x16_bf16, fp32 accumulate) consumes one tap of a pair of units.
+// "Channel" below means one such unit.
+struct ElemF32 {
+    static constexpr int BYTES = 4;
+    typedef float unit_t;
+    typedef float frag_t;
+    static __device__ __forceinline__ frag_t read(const unit_t *p) { return *p; }
+    static __device__ __forceinline__ v16f mfma(frag_t a, frag_t b, v16f c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+};
+struct ElemBF16x8 {
+    static constexpr int BYTES = 16;
+    typedef v4f unit_t;
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __bf16 frag_t __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ frag_t read(const unit_t *p) { return __builtin_bit_cast(frag_t, *p); }
+    static __device__ __forceinline__ v16f mfma(frag_t a, frag_t b, v16f c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+#else
+    // the host pass only needs the kernel's signature; bfloat16 vectors do not exist there
+    typedef v4f frag_t;
+    static frag_t read(const unit_t *p) { return *p; }
+    static v16f mfma(frag_t, frag_t, v16f c) { return c; }
+#endif
+};
+
 struct ConvPatchKArgs {
-    const float *in, *wt, *bias;
+    const void *in, *wt;
+    const float *bias;
     float *out;
     int C, H, W, K, R, S, stride, pad, P, Q;
     int PQ, RS, HW, CHW, Kg, Ng;
@@ -42,6 +76,9 @@ struct ConvPatchKArgs {
     uint64_t in_bytes, wt_bytes;
     int tiles_m, tiles_n, raster, act;
     int split_k, stages_per_split;   // blockIdx.y takes stages [y*stages_per_split, ...)
+    int nbuf;        // LDS stage buffers: 2, or 1 when a workgroup runs a single stage
+    int single;      // 1: the whole reduction is ONE unit (CB == 1); the upper half-wave, which
+                     // would carry the pair's second unit, multiplies by a zero kept in LDS
 };
 
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic, uint32_t ones_if_d1)
@@ -59,41 +96,44 @@ __device__ __forceinline__ float act_apply(float v, int act)
 // One channel pair of a stage: R*S taps, each one rank-2 update of every accumulator block.
 // With the filter size known at compile time (RC, SC > 0) the taps are unrolled, so the LDS
 // reads of later taps are in flight while the matrix cores work on earlier ones.
-template <class T, int RC, int SC>
-__device__ __forceinline__ void patch_pair(const float *__restrict__ A, const float *__restrict__ B,
+template <class E, class T, int RC, int SC>
+__device__ __forceinline__ void patch_pair(const typename E::unit_t *__restrict__ A,
+                                           const typename E::unit_t *__restrict__ B,
                                            const int (&a_base)[T::MB], const int (&b_base)[T::NB],
-                                           int ka, int kb, int R, int S, int Wp, v16f (&acc)[T::MB][T::NB])
+                                           int ka, int kb, int R, int S, int Wp, v16f (&acc)[T::MB][T::NB],
+                                           int bmul = 1)
 {
     constexpr int MB = T::MB, NB = T::NB;
+    // bmul is 1, or per lane 0 where the lane's pixel operand must stay on one (zero) LDS unit;
+    // only the 16-byte element path pays for the multiply
+    auto boff = [&](int o) { return E::BYTES == 16 ? o * bmul : o; };
     if constexpr (RC > 0) {
 #pragma unroll
         for (int r = 0; r < RC; ++r)
 #pragma unroll
             for (int s = 0; s < SC; ++s) {
-                float fa[MB], fb[NB];
+                typename E::frag_t fa[MB], fb[NB];
 #pragma unroll
-                for (int bi = 0; bi < MB; ++bi) fa[bi] = A[a_base[bi] + ka + r * SC + s];
+                for (int bi = 0; bi < MB; ++bi) fa[bi] = E::read(A + a_base[bi] + ka + r * SC + s);
 #pragma unroll
-                for (int bj = 0; bj < NB; ++bj) fb[bj] = B[b_base[bj] + kb + r * Wp + s];
+                for (int bj = 0; bj < NB; ++bj) fb[bj] = E::read(B + b_base[bj] + boff(kb + r * Wp + s));
 #pragma unroll
                 for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-                    for (int bj = 0; bj < NB; ++bj)
-                        acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
+                    for (int bj = 0; bj < NB; ++bj) acc[bi][bj] = E::mfma(fa[bi], fb[bj], acc[bi][bj]);
             }
     } else {
         for (int r = 0; r < R; ++r) {
             for (int s = 0; s < S; ++s) {
-                float fa[MB], fb[NB];
+                typename E::frag_t fa[MB], fb[NB];
 #pragma unroll
-                for (int bi = 0; bi < MB; ++bi) fa[bi] = A[a_base[bi] + ka];
+                for (int bi = 0; bi < MB; ++bi) fa[bi] = E::read(A + a_base[bi] + ka);
 #pragma unroll
-                for (int bj = 0; bj < NB; ++bj) fb[bj] = B[b_base[bj] + kb + s];
+                for (int bj = 0; bj < NB; ++bj) fb[bj] = E::read(B + b_base[bj] + boff(kb + s));
 #pragma unroll
                 for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-                    for (int bj = 0; bj < NB; ++bj)
-                        acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
+                    for (int bj = 0; bj < NB; ++bj) acc[bi][bj] = E::mfma(fa[bi], fb[bj], acc[bi][bj]);
                 ++ka;
             }
             kb += Wp;
@@ -110,10 +150,28 @@ __device__ __forceinline__ void patch_pair(const float *__restrict__ A, const fl
 // RC, SC: filter size when known at compile time, 0 for any size.
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
-template <class T, int MAXA, int MAXP, int RC, int SC>
+// One direct-to-LDS buffer load of BYTES (4 or 16) per lane.  Device pass only: the 16-byte form
+// exists on gfx950 alone and the host pass has no such target to check it against.
+template <int BYTES, class U>
+__device__ __forceinline__ void lds_dma(__amdgpu_buffer_rsrc_t rsrc, U *lds_dst, uint32_t byte_off)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    // the size operand must be a literal, not a template-dependent value
+    if constexpr (BYTES == 16)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)lds_dst, 16, (int)byte_off, 0, 0, 0);
+    else
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)lds_dst, 4, (int)byte_off, 0, 0, 0);
+#else
+    (void)rsrc; (void)lds_dst; (void)byte_off;
+#endif
+}
+
+template <class E, class T, int MAXA, int MAXP, int RC, int SC>
 __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 {
-    extern __shared__ __attribute__((aligned(16))) float lds[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    typedef typename E::unit_t unit_t;
+    unit_t *lds = reinterpret_cast<unit_t *>(lds_raw);
     constexpr int NT = T::NT, MB = T::MB, NB = T::NB;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -141,9 +199,9 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const uint32_t magic_chs = chs > 1 ? 0xFFFFFFFFu / (uint32_t)chs + 1u : 0u;
     const uint32_t one_chs = chs > 1 ? 0u : 0xFFFFFFFFu;
 
-    const int a_stage = p.a_stage;                 // floats: BM rows of pitch LDA, rounded up to NT
-    float *As = lds;                               // [2][a_stage]
-    float *Bs = lds + 2 * a_stage;                 // [2][b_stage]
+    const int a_stage = p.a_stage;                 // units: BM rows of pitch LDA, rounded up to NT
+    unit_t *As = lds;                              // [2][a_stage]
+    unit_t *Bs = lds + p.nbuf * a_stage;           // [nbuf][b_stage], then one zero unit
     const int a_elems = T::BM * p.LDA;
 
     // ---- per-thread patch elements: LDS dword e <-> one input element or a zero -------------
@@ -165,7 +223,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         }
         int ih = ihb + rr * p.irs, iw = col * p.ics - p.pad;
         bool ok = ((int)e < patch_elems) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-        p_goff[i] = ok ? (uint32_t)(((ii * p.C + (int)c_l) * p.HW + ih * p.W + iw) * 4) : kOobOffset;
+        p_goff[i] = ok ? (uint32_t)(((ii * p.C + (int)c_l) * p.HW + ih * p.W + iw) * E::BYTES) : kOobOffset;
     }
 
     // ---- per-thread filter elements: LDS dword e = m*LDA + kk <-> wt[m0+m][k0+kk] ------------
@@ -176,14 +234,20 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         uint32_t m = fdiv(e, p.magic_lda, 0u);
         int kk = (int)(e - m * (uint32_t)p.LDA);
         bool ok = (int)e < a_elems && m0 + (int)m < p.K && kk < p.D;
-        a_goff[i] = ok ? (uint32_t)(((int)m * p.Kg + kk) * 4) : kOobOffset;
+        a_goff[i] = ok ? (uint32_t)(((int)m * p.Kg + kk) * E::BYTES) : kOobOffset;
     }
 
     // ---- per-lane operand bases ---------------------------------------------------------------
     // filter operand: row wm0 + 32*bi + lane%32, column offset (lane/32)*RS selects the odd channel
     int a_base[MB];
 #pragma unroll
-    for (int bi = 0; bi < MB; ++bi) a_base[bi] = (wm0 + 32 * bi + li) * p.LDA + lh * p.RS;
+    for (int bi = 0; bi < MB; ++bi) a_base[bi] = (wm0 + 32 * bi + li) * p.LDA + (p.single ? 0 : lh * p.RS);
+    const int zero_unit = p.nbuf * p.b_stage;      // relative to Bs
+    const int bmul = (p.single && lh) ? 0 : 1;
+    if (tid == 0) {
+        unit_t z = {};
+        Bs[zero_unit] = z;                          // visible after the first barrier below
+    }
     // pixel operand: the lane's NB blocks are NB adjacent pixels (so the epilogue stores them as
     // one vector); patch position of tap (0,0), channel parity lane/32
     int b_base[NB];
@@ -204,7 +268,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             px_img[bj] = img;
             px_pq[bj] = pq;
         }
-        b_base[bj] = base + lh * chs;
+        b_base[bj] = (p.single && lh) ? zero_unit : base + lh * chs;
     }
 
     v16f acc[MB][NB];
@@ -220,9 +284,9 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         const int k0 = c0 * p.RS;
         const int krem = p.Kg - k0;     // reduction elements that exist from k0 on
         const int crem = p.C - c0;      // channels that exist from c0 on
-        const uint64_t a_skip = ((uint64_t)m0 * p.Kg + k0) * 4;
+        const uint64_t a_skip = ((uint64_t)m0 * p.Kg + k0) * E::BYTES;
         __amdgpu_buffer_rsrc_t ra = make_rsrc(reinterpret_cast<const char *>(p.wt) + a_skip, p.wt_bytes - a_skip);
-        float *A = As + buf * a_stage + wave * 64;
+        unit_t *A = As + buf * a_stage + wave * 64;
 #pragma unroll
         for (int i = 0; i < MAXA; ++i)
             if (i * NT < a_elems) {
@@ -233,11 +297,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
                     int kk = (int)(e - m * (uint32_t)p.LDA);
                     off = kk < krem ? off : kOobOffset;
                 }
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(A + i * NT), 4, (int)off, 0, 0, 0);
+                lds_dma<E::BYTES>(ra, A + i * NT, off);
             }
-        const uint64_t b_skip = ((uint64_t)img_a * p.C + c0) * p.HW * 4;
+        const uint64_t b_skip = ((uint64_t)img_a * p.C + c0) * p.HW * E::BYTES;
         __amdgpu_buffer_rsrc_t rb = make_rsrc(reinterpret_cast<const char *>(p.in) + b_skip, p.in_bytes - b_skip);
-        float *B = Bs + buf * p.b_stage + wave * 64;
+        unit_t *B = Bs + buf * p.b_stage + wave * 64;
 #pragma unroll
         for (int i = 0; i < MAXP; ++i)
             if (i * NT < patch_elems) {
@@ -246,11 +310,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
                     uint32_t c_l = fdiv((uint32_t)(tid + i * NT), magic_chs, one_chs);
                     off = (int)c_l < crem ? off : kOobOffset;
                 }
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr_t)(B + i * NT), 4, (int)off, 0, 0, 0);
+                lds_dma<E::BYTES>(rb, B + i * NT, off);
             }
     };
 
-    const int npairs = p.CB >> 1;
+    const int npairs = (p.CB + 1) >> 1;
 
     const int t_begin = blockIdx.y * p.stages_per_split;
     const int t_end = min(p.nstages, t_begin + p.stages_per_split);
@@ -262,21 +326,21 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         // buffer buf^1 was last read in stage t-1, which every wave has left (barrier below)
         if (t + 1 < t_end) load_stage(t + 1, buf ^ 1);
 
-        const float *A = As + buf * a_stage;
-        const float *B = Bs + buf * p.b_stage;
+        const unit_t *A = As + buf * a_stage;
+        const unit_t *B = Bs + buf * p.b_stage;
         if constexpr (RC == 1 && SC == 1) {
             // 1x1 filters: a pair is a single tap, so unroll over pairs instead
             int cp = 0;
             for (; cp + 4 <= npairs; cp += 4) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    patch_pair<T, 1, 1>(A, B, a_base, b_base, (cp + u) * 2, (cp + u) * 2 * chs, 1, 1, p.Wp, acc);
+                    patch_pair<E, T, 1, 1>(A, B, a_base, b_base, (cp + u) * 2, (cp + u) * 2 * chs, 1, 1, p.Wp, acc, bmul);
             }
             for (; cp < npairs; ++cp)
-                patch_pair<T, 1, 1>(A, B, a_base, b_base, cp * 2, cp * 2 * chs, 1, 1, p.Wp, acc);
+                patch_pair<E, T, 1, 1>(A, B, a_base, b_base, cp * 2, cp * 2 * chs, 1, 1, p.Wp, acc, bmul);
         } else {
             for (int cp = 0; cp < npairs; ++cp)
-                patch_pair<T, RC, SC>(A, B, a_base, b_base, cp * 2 * p.RS, cp * 2 * chs, p.R, p.S, p.Wp, acc);
+                patch_pair<E, T, RC, SC>(A, B, a_base, b_base, cp * 2 * p.RS, cp * 2 * chs, p.R, p.S, p.Wp, acc, bmul);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
@@ -343,6 +407,9 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     }
 }
 
+// LDS one workgroup may take: the whole 160 KB of a compute unit.
+static constexpr size_t kMaxLdsBytes = 160 * 1024;
+
 // Input rows a run of bn consecutive output pixels can need at most (all images it touches).
 static int patch_rows_bound(const ConvProblem &q, int bn)
 {
@@ -359,7 +426,9 @@ static int patch_rows_bound(const ConvProblem &q, int bn)
     return (int)bound;
 }
 
-template <class T, int MAXA, int MAXP>
+// q.C counts reduction units of E (channels for fp32, blocks of eight channels for bf16) and
+// q.in / q.wt point at tensors made of such units.
+template <class E, class T, int MAXA, int MAXP>
 static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, int raster, hipStream_t stream,
                                     bool dry)
 {
@@ -373,10 +442,13 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     a.Wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
     a.prs = q.R == 1 ? 1 : q.stride; a.irs = q.R == 1 ? q.stride : 1;
     a.pcs = q.S == 1 ? 1 : q.stride; a.ics = q.S == 1 ? q.stride : 1;
+    // a reduction of one 16-byte unit runs unpaired instead of staging a second unit of zeros
+    a.single = (E::BYTES == 16 && q.C == 1) ? 1 : 0;
+    if (a.single) cb = 1;
     a.CB = cb;
     a.nstages = (q.C + cb - 1) / cb;
     a.D = cb * a.RS;
-    a.LDA = a.D + 1;   // D is even (cb is), so the pitch is odd and at least 3
+    a.LDA = (a.D + 1) | 1;   // odd pitch (D is even unless single), at least 3
     a.rows_full = (q.P - 1) * a.prs + q.R;
     const int rows_alloc = patch_rows_bound(q, T::BN);
     a.a_stage = (T::BM * a.LDA + T::NT - 1) / T::NT * T::NT;
@@ -384,8 +456,8 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     a.magic_Wp = div_magic((uint32_t)a.Wp); a.one_Wp = a.Wp == 1 ? 0xFFFFFFFFu : 0u;
     a.magic_rf = div_magic((uint32_t)a.rows_full); a.one_rf = a.rows_full == 1 ? 0xFFFFFFFFu : 0u;
     a.magic_lda = div_magic((uint32_t)a.LDA);
-    a.in_bytes = (uint64_t)q.N * a.CHW * 4;
-    a.wt_bytes = (uint64_t)q.K * a.Kg * 4;
+    a.in_bytes = (uint64_t)q.N * a.CHW * E::BYTES;
+    a.wt_bytes = (uint64_t)q.K * a.Kg * E::BYTES;
     a.tiles_m = (q.K + T::BM - 1) / T::BM;
     a.tiles_n = (a.Ng + T::BN - 1) / T::BN;
     a.raster = raster;
@@ -393,31 +465,36 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     // what one thread may hold, and the LDS a workgroup may take
     if ((long)a.a_stage > (long)MAXA * T::NT) return hipErrorInvalidConfiguration;
     if ((long)a.b_stage > (long)MAXP * T::NT) return hipErrorInvalidConfiguration;
-    const size_t lds_bytes = (size_t)2 * ((size_t)a.a_stage + a.b_stage) * 4;
-    if (lds_bytes > 64 * 1024) return hipErrorInvalidConfiguration;
-    // 31-bit byte offsets: filter rows of one tile, and the images one pixel run touches
-    const long PQl = a.PQ;
-    const long imgs = (T::BN - 1 + PQl - 1) / PQl + 1;
-    if ((long)T::BM * a.Kg * 4 >= 0x7FFFFFF0l || (imgs * q.C + cb) * (long)a.HW * 4 >= 0x7FFFFFF0l)
-        return hipErrorInvalidConfiguration;
     if (split_k < 1) split_k = 1;
     if (split_k > a.nstages) split_k = a.nstages;
     a.stages_per_split = (a.nstages + split_k - 1) / split_k;
     a.split_k = (a.nstages + a.stages_per_split - 1) / a.stages_per_split;
     if (a.split_k > 65535) return hipErrorInvalidConfiguration;
+    a.nbuf = a.stages_per_split > 1 ? 2 : 1;
+    // the stage buffers and the zero unit behind them (kept a whole 64-unit row for alignment)
+    const size_t lds_bytes = ((size_t)a.nbuf * ((size_t)a.a_stage + a.b_stage) + 64) * E::BYTES;
+    if (lds_bytes > kMaxLdsBytes) return hipErrorInvalidConfiguration;
+    // 31-bit byte offsets: filter rows of one tile, and the images one pixel run touches
+    const long PQl = a.PQ;
+    const long imgs = (T::BN - 1 + PQl - 1) / PQl + 1;
+    if ((long)T::BM * a.Kg * E::BYTES >= 0x7FFFFFF0l || (imgs * q.C + cb) * (long)a.HW * E::BYTES >= 0x7FFFFFF0l)
+        return hipErrorInvalidConfiguration;
     if (dry) return hipSuccess;
     clear_stale_hip_error();
     const size_t nout = (size_t)q.N * q.K * a.PQ;
     if (a.split_k > 1 && launch_fill_zero(q.out, nout, stream) != hipSuccess) return hipGetLastError();
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
-    if (q.R == 1 && q.S == 1)
-        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 1, 1>), grid, block, lds_bytes, stream, a);
-    else if (q.R == 3 && q.S == 3)
-        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 3, 3>), grid, block, lds_bytes, stream, a);
-    else if (q.R == 7 && q.S == 7)
-        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 7, 7>), grid, block, lds_bytes, stream, a);
-    else
-        hipLaunchKernelGGL((conv_patch_kernel<T, MAXA, MAXP, 0, 0>), grid, block, lds_bytes, stream, a);
+    void (*kern)(ConvPatchKArgs) = conv_patch_kernel<E, T, MAXA, MAXP, 0, 0>;
+    if (q.R == 1 && q.S == 1) kern = conv_patch_kernel<E, T, MAXA, MAXP, 1, 1>;
+    else if (q.R == 3 && q.S == 3) kern = conv_patch_kernel<E, T, MAXA, MAXP, 3, 3>;
+    else if (q.R == 7 && q.S == 7) kern = conv_patch_kernel<E, T, MAXA, MAXP, 7, 7>;
+    if (lds_bytes > 64 * 1024) {
+        // more than the default per-workgroup LDS window has to be asked for, per kernel
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a);
     if (a.split_k > 1 && (q.bias || q.act != POLYDL_ACT_NONE))
         return launch_bias_act(q.out, q.bias, q.K, a.PQ, nout, q.act, stream);
     return hipGetLastError();
@@ -428,20 +505,29 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
                                                            hipStream_t st, bool dry)                     \
     {                                                                                                    \
         /* the instantiation with fewer per-thread passes needs fewer registers: more waves per SIMD */ \
-        if (conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, true) == hipSuccess)        \
-            return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, dry);                \
-        return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, sk, r, st, dry);                   \
+        if (conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, true) == hipSuccess)        \
+            return conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, dry);                \
+        return conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, sk, r, st, dry);                   \
     }
 POLYDL_PATCH_FAMILY(POLYDL_DEFINE_CONV_PATCH)
+
+// bfloat16 (units of eight channels) launchers: same kernel, 16-byte elements
+#define POLYDL_DEFINE_CONV_PATCH_BF16(BM, BN, BK, WM, WN)                                                \
+    hipError_t conv_patch_bf16_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb, int sk,      \
+                                                                int r, hipStream_t st, bool dry)         \
+    {                                                                                                    \
+        return conv_patch_launch<ElemBF16x8, Tile<BM, BN, 8, WM, WN>, 16, 16>(q, cb, sk, r, st, dry);        \
+    }
+POLYDL_PATCH_BF16_FAMILY(POLYDL_DEFINE_CONV_PATCH_BF16)
 
 // 1 if the problem runs in the instantiation with few per-thread passes (fewer registers, more
 // waves per SIMD), 0 if it needs the large one, -1 if neither holds it.
 #define POLYDL_DEFINE_PATCH_CLASS(BM, BN, BK, WM, WN)                                                   \
     int conv_patch_class_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb)                         \
     {                                                                                                    \
-        if (conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, 1, 0, nullptr, true) == hipSuccess)   \
+        if (conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, 1, 0, nullptr, true) == hipSuccess)   \
             return 1;                                                                                    \
-        return conv_patch_launch<Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, 1, 0, nullptr, true) == hipSuccess \
+        return conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, 1, 0, nullptr, true) == hipSuccess \
                    ? 0 : -1;                                                                             \
     }
 POLYDL_PATCH_FAMILY(POLYDL_DEFINE_PATCH_CLASS)

@@ -14,7 +14,8 @@ struct SgemmProblem {
 
 struct ConvProblem {
     int N, C, H, W, K, R, S, stride, pad, P, Q;
-    const float *in, *wt, *bias;
+    const void *in, *wt;   // float tensors, or tensors of eight-bfloat16 units for the bf16 kernels
+    const float *bias;
     float *out;
     int act;
 };
@@ -40,6 +41,8 @@ struct PatchVariant {
 extern const Variant kVariants[];
 extern const int kNumVariants;
 extern const PatchVariant kPatchVariants[];
+extern const PatchVariant kPatchBf16Variants[];
+extern const int kNumPatchBf16Variants;
 extern const int kNumPatchVariants;
 
 // filled in by the kernel files
@@ -47,12 +50,17 @@ extern const int kNumPatchVariants;
     hipError_t sgemm_launch_##BM##x##BN##x##BK##_##WM##x##WN(const SgemmProblem &, int, int, hipStream_t);     \
     hipError_t conv_launch_##BM##x##BN##x##BK##_##WM##x##WN(const ConvProblem &, int, int, hipStream_t);
 
+#define POLYDL_DECLARE_PATCH_BF16_LAUNCHER(BM, BN, BK, WM, WN) \
+    hipError_t conv_patch_bf16_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, int, hipStream_t, bool);
+
 #define POLYDL_DECLARE_PATCH_LAUNCHER(BM, BN, BK, WM, WN) \
     hipError_t conv_patch_launch_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int, int, int, hipStream_t, bool); \
     int conv_patch_class_##BM##x##BN##_##WM##x##WN(const ConvProblem &, int);
 
-hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int b, bool to_blocked, hipStream_t st);
-hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st);
+hipError_t launch_nchwc(const void *src, void *dst, int N, int C, int HW, int b, bool to_blocked, int elem_bytes,
+                        hipStream_t st);
+hipError_t launch_kcrsck(const void *wt, void *dst, int K, int C, int RS, int bc, int bk, int elem_bytes,
+                         hipStream_t st);
 hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t total, hipStream_t st);
 hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
 hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st);

@@ -13,26 +13,27 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 // NCHW -> NCHWc.  One workgroup moves b channels x 256 pixels of one image: rows are read along
 // the pixels (contiguous in NCHW), transposed in LDS, and written along (pixel, channel) which
 // is contiguous in NCHWc.  Channels beyond C are written as zeros.
-template <bool TO_BLOCKED>
-__global__ __launch_bounds__(256) void nchwc_kernel(const float *__restrict__ src, float *__restrict__ dst,
+template <class V, bool TO_BLOCKED>
+__global__ __launch_bounds__(256) void nchwc_kernel(const V *__restrict__ src, V *__restrict__ dst,
                                                     int C, int HW, int b, int Cb)
 {
-    extern __shared__ float tile[];   // [b][257]
+    extern __shared__ __attribute__((aligned(16))) unsigned char tile_raw[];
+    V *tile = reinterpret_cast<V *>(tile_raw);   // [b][257]
     const int t = threadIdx.x;
     const int hw0 = blockIdx.x * 256, cb = blockIdx.y, n = blockIdx.z;
     const int npix = min(256, HW - hw0);
     if (TO_BLOCKED) {
         for (int ci = 0; ci < b; ++ci) {
             int c = cb * b + ci;
-            float v = 0.f;
+            V v = 0;
             if (c < C && t < npix) v = src[((size_t)n * C + c) * HW + hw0 + t];
             tile[ci * 257 + t] = v;
         }
         __syncthreads();
-        float *o = dst + (((size_t)n * Cb + cb) * HW + hw0) * b;
+        V *o = dst + (((size_t)n * Cb + cb) * HW + hw0) * b;
         for (int e = t; e < npix * b; e += 256) o[e] = tile[(e % b) * 257 + e / b];
     } else {
-        const float *i = src + (((size_t)n * Cb + cb) * HW + hw0) * b;
+        const V *i = src + (((size_t)n * Cb + cb) * HW + hw0) * b;
         for (int e = t; e < npix * b; e += 256) tile[(e % b) * 257 + e / b] = i[e];
         __syncthreads();
         for (int ci = 0; ci < b; ++ci) {
@@ -44,7 +45,8 @@ __global__ __launch_bounds__(256) void nchwc_kernel(const float *__restrict__ sr
 
 // KCRS -> KCRSck: one thread per element of the blocked tensor (weights are small and packed
 // once per tensor).  Elements whose channel indices fall beyond K or C are zeros.
-__global__ void kcrsck_kernel(const float *__restrict__ wt, float *__restrict__ dst, int K, int C, int RS,
+template <class V>
+__global__ void kcrsck_kernel(const V *__restrict__ wt, V *__restrict__ dst, int K, int C, int RS,
                               int bc, int bk, int Cb, size_t total)
 {
     size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -58,7 +60,7 @@ __global__ void kcrsck_kernel(const float *__restrict__ wt, float *__restrict__ 
     int cblk = (int)(r3 % Cb);
     int kblk = (int)(r3 / Cb);
     int k = kblk * bk + ki, c = cblk * bc + ci;
-    dst[o] = (k < K && c < C) ? wt[((size_t)k * C + c) * RS + rs] : 0.f;
+    dst[o] = (k < K && c < C) ? wt[((size_t)k * C + c) * RS + rs] : (V)0;
 }
 
 // y[n][k][pq] += bias[k], in place.
@@ -124,24 +126,41 @@ hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n,
     return hipGetLastError();
 }
 
-hipError_t launch_nchwc(const float *src, float *dst, int N, int C, int HW, int b, bool to_blocked, hipStream_t st)
+// elem_bytes: 4 (float) or 2 (bfloat16 bit patterns; a permutation does not look at the values)
+hipError_t launch_nchwc(const void *src, void *dst, int N, int C, int HW, int b, bool to_blocked, int elem_bytes,
+                        hipStream_t st)
 {
     clear_stale_hip_error();
     int Cb = (C + b - 1) / b;
     dim3 grid((unsigned)((HW + 255) / 256), (unsigned)Cb, (unsigned)N);
-    size_t lds = (size_t)b * 257 * 4;
-    if (to_blocked) hipLaunchKernelGGL(nchwc_kernel<true>, grid, dim3(256), lds, st, src, dst, C, HW, b, Cb);
-    else hipLaunchKernelGGL(nchwc_kernel<false>, grid, dim3(256), lds, st, src, dst, C, HW, b, Cb);
+    size_t lds = (size_t)b * 257 * elem_bytes;
+    if (elem_bytes == 4) {
+        const float *s = static_cast<const float *>(src);
+        float *d = static_cast<float *>(dst);
+        if (to_blocked) hipLaunchKernelGGL((nchwc_kernel<float, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+        else hipLaunchKernelGGL((nchwc_kernel<float, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+    } else {
+        const uint16_t *s = static_cast<const uint16_t *>(src);
+        uint16_t *d = static_cast<uint16_t *>(dst);
+        if (to_blocked) hipLaunchKernelGGL((nchwc_kernel<uint16_t, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+        else hipLaunchKernelGGL((nchwc_kernel<uint16_t, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_kcrsck(const float *wt, float *dst, int K, int C, int RS, int bc, int bk, hipStream_t st)
+hipError_t launch_kcrsck(const void *wt, void *dst, int K, int C, int RS, int bc, int bk, int elem_bytes,
+                         hipStream_t st)
 {
     clear_stale_hip_error();
     int Kb = (K + bk - 1) / bk, Cb = (C + bc - 1) / bc;
     size_t total = (size_t)Kb * Cb * RS * bc * bk;
-    hipLaunchKernelGGL(kcrsck_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, wt, dst, K, C, RS,
-                       bc, bk, Cb, total);
+    dim3 grid((unsigned)((total + 255) / 256));
+    if (elem_bytes == 4)
+        hipLaunchKernelGGL(kcrsck_kernel<float>, grid, dim3(256), 0, st, static_cast<const float *>(wt),
+                           static_cast<float *>(dst), K, C, RS, bc, bk, Cb, total);
+    else
+        hipLaunchKernelGGL(kcrsck_kernel<uint16_t>, grid, dim3(256), 0, st, static_cast<const uint16_t *>(wt),
+                           static_cast<uint16_t *>(dst), K, C, RS, bc, bk, Cb, total);
     return hipGetLastError();
 }
 

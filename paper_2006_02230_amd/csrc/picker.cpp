@@ -214,7 +214,10 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         const int cb = std::max(2, cfg.cb);
         const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
         c.steps_per_stage = cb / 2.0 * RS;
-        c.lds_bytes = 2.0 * (cfg.bm * (cb * RS + 1) + cb * conv_patch_rows(q, cfg.bn) * wp) * 4;
+        // two stage buffers, one when a workgroup's share of the reduction is a single stage
+        const int nstages = (q.C + cb - 1) / cb;
+        const int per_split = (nstages + c.split_k - 1) / c.split_k;
+        c.lds_bytes = (per_split > 1 ? 2.0 : 1.0) * (cfg.bm * (cb * RS + 1) + cb * conv_patch_rows(q, cfg.bn) * wp) * 4;
         c.loop_eff = 0.74;
         c.wg_overhead_cycles = 9000;
         c.kernel_fixed_us = 14.0;

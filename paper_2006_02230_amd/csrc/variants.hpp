@@ -21,3 +21,10 @@
     X(64, 256, 0, 64, 64)      \
     X(128, 64, 0, 64, 32)      \
     X(128, 128, 0, 64, 64)
+
+// Tiles of the bfloat16 row-patch kernel (eight-channel units, v_mfma_f32_32x32x16_bf16).
+#define POLYDL_PATCH_BF16_FAMILY(X) \
+    X(64, 64, 0, 32, 32)            \
+    X(64, 128, 0, 64, 32)           \
+    X(128, 64, 0, 64, 32)           \
+    X(128, 128, 0, 64, 64)
