@@ -18,7 +18,25 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
+
+# HBM-side bytes of one pass over the suite (all kernels of the eight layers, batch 32), from the L2
+# fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
+# reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
+# with: their digest is kept beside them and the bench line reports null when it no longer matches.
+HBM_TRAFFIC = {"csrc_sha256": "", "batch": 32, "fetch_bytes": 0.0, "write_bytes": 0.0}
+
+
+def csrc_digest():
+    import hashlib
+    d = os.path.join(ROOT, "paper_2006_02230_amd", "csrc")
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".hpp", ".cpp", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()
 
 
 def conv_flops(s, P, Q):
@@ -55,6 +73,11 @@ def main():
     ap.add_argument("--sweep-out", default="", help="with --sweep: write every candidate's time to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-sgemm", action="store_true")
+    ap.add_argument("--no-bf16", action="store_true", help="skip the bfloat16 rows (same suite at batch 64)")
+    ap.add_argument("--no-fusion", action="store_true", help="skip the fused-versus-separate epilogue row")
+    ap.add_argument("--copy-probe", action="store_true", help="first run three plain 256 MiB device copies "
+                    "(an elementwise kernel of known traffic that calibrates the HBM byte counters)")
+    ap.add_argument("--no-layer-rows", action="store_true", help="skip the per-layer timing loops (counter runs)")
     ap.add_argument("--layers", default="", help="comma list of suite layers to run (default: all eight); "
                     "a subset is for profiling one kernel and changes the workload the line reports")
     ap.add_argument("--tile", default="", help="force a variant bm,bn,bk,wm,wn[,split_k[,layout[,raster]]] (profiling)")
@@ -71,6 +94,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+
+    if args.copy_probe:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     suite = synth.RESNET50_SUITE(args.batch)
     chosen = [int(t) for t in args.layers.split(",") if t != ""] or list(range(len(suite)))
@@ -112,13 +143,14 @@ def main():
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = wall_ms / args.steps
     total_flops = sum(L["flops"] for L in layers)
+    total_bytes = sum(L["bytes"] for L in layers)
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
     # per-layer kernel time: back-to-back launches of one layer between two events on the launch stream
     rows = []
     sweep_dump = []
     kern_ms_sum = 0.0
-    for L in layers:
+    for L in ([] if args.no_layer_rows else layers):
         i = L["index"]
         reps = 30
         ms = time_calls(torch, lambda L=L: run_layer(L), reps)
@@ -158,6 +190,8 @@ def main():
                             sweep_seconds=round(t_sweep, 3))
             sweep_dump.append(dict(layer=i, shape=list(shape), picked=pcfg.as_dict(), picked_us=round(ms * 1e3, 2),
                                    candidates=cands))
+    if args.no_layer_rows:
+        kern_ms_sum = e0.elapsed_time(e1) / args.steps
     achieved = total_flops / (kern_ms_sum * 1e-3) / 1e12
 
     sg = []
@@ -172,24 +206,87 @@ def main():
                            frac_mfma=round(tf / FP32_MFMA_PEAK_TFLOPS, 4), tile=P.get_last_tile().as_dict()))
             del dA, dB, dC
 
+    # the same suite with bfloat16 inputs (fp32 accumulate and output) at batch 64: operands already in
+    # the 8-channel blocked layouts, as a network that stays in that layout between layers holds them
+    bf = None
+    if not args.no_bf16 and len(chosen) == 8 and forced is None:
+        bf_rows, bf_ms, bf_flops, tr_ms = [], 0.0, 0.0, 0.0
+        for i, s in enumerate(synth.RESNET50_SUITE(64)):
+            x, w, b = synth.conv_inputs(s, seed=300 + i, dist="normal", bias=True)
+            Pq, Qq = synth.out_hw(s)
+            xb = torch.from_numpy(synth.to_bf16_bits(x).view(np.int16)).cuda()
+            wb = torch.from_numpy(synth.to_bf16_bits(w).view(np.int16)).cuda()
+            db = torch.from_numpy(b).cuda()
+            t_tr = time_calls(torch, lambda: (P.nchw_to_nchwc_bf16(xb, 8), P.kcrs_to_kcrsck_bf16(wb, 8, 1)), 5)
+            x8, w8 = P.nchw_to_nchwc_bf16(xb, 8), P.kcrs_to_kcrsck_bf16(wb, 8, 1)
+            out = torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda")
+            fn = lambda: P.conv2d_fwd_bf16_blocked(x8, w8, s.C, db, out=out, stride=s.stride, pad=s.pad, act="relu")
+            fn()
+            ms = time_calls(torch, fn, 20)
+            fl = conv_flops(s, Pq, Qq)
+            bf_rows.append(dict(layer=i, us=round(ms * 1e3, 2), tflops=round(fl / (ms * 1e-3) / 1e12, 2),
+                                layout_us=round(t_tr * 1e3, 2), tile=P.get_last_tile().as_dict()))
+            bf_ms += ms
+            tr_ms += t_tr
+            bf_flops += fl
+            del xb, wb, x8, w8, out
+        tf = bf_flops / (bf_ms * 1e-3) / 1e12
+        bf = dict(workload="configs[4]: the same eight layers, bf16 inputs in NCHW8c / KCRS8c, fp32 accumulate "
+                           "and output, N=64, bias+ReLU fused",
+                  tflops=round(tf, 2), frac_of_bf16_mfma_peak=round(tf / BF16_MFMA_PEAK_TFLOPS, 4),
+                  us_per_pass=round(bf_ms * 1e3, 1), layout_transform_us_per_pass=round(tr_ms * 1e3, 1),
+                  tflops_with_layout_transforms=round(bf_flops / ((bf_ms + tr_ms) * 1e-3) / 1e12, 2),
+                  layers=bf_rows)
+
+    # convolution + bias + ReLU as one kernel against the same three operators as three kernels
+    fusion = None
+    if not args.no_fusion and forced is None:
+        s = synth.CONFIG4
+        x, w, b = synth.conv_inputs(s, seed=400, dist="normal", bias=True)
+        Pq, Qq = synth.out_hw(s)
+        dx, dw, db = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
+        out = torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda")
+        fused = lambda: P.conv2d_fwd(dx, dw, db, out=out, stride=s.stride, pad=s.pad, act="relu")
+
+        def separate():
+            P.conv2d_fwd(dx, dw, None, out=out, stride=s.stride, pad=s.pad, act=None)
+            P.bias_add(out, db)
+            P.activation(out, "relu")
+        fused(); separate()
+        t_f, t_s = time_calls(torch, fused, 50), time_calls(torch, separate, 50)
+        t_c = time_calls(torch, lambda: P.conv2d_fwd(dx, dw, None, out=out, stride=s.stride, pad=s.pad, act=None), 50)
+        ob = 4.0 * s.N * s.K * Pq * Qq
+        fusion = dict(workload="configs[3]: conv+bias+ReLU, N=%d C=K=%d %dx%d 3x3" % (s.N, s.C, s.H, s.W),
+                      fused_us=round(t_f * 1e3, 2), separate_us=round(t_s * 1e3, 2), conv_only_us=round(t_c * 1e3, 2),
+                      speedup=round(t_s / t_f, 3),
+                      output_bytes=ob, algorithmic_bytes_saved=4 * ob,
+                      note="the two extra kernels each read and write the whole output once: four passes "
+                           "over it that the fused epilogue never makes")
+        del dx, dw, out
+
     cpu = None
     if not args.no_cpu:
         import oracle
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        done_flops, t_cpu, desc = 0.0, 0.0, []
-        for i, L in enumerate(layers):
-            s = L["shape"]
-            x, w, b = L["host"]
-            nsub = max(1, min(s.N, int(round(s.N * 2.0e9 / L["flops"]))))  # about 2 GFLOP per layer
-            t = time.perf_counter()
-            oracle.conv2d_fwd(x[:nsub], w, bias=b, stride=s.stride, pad=s.pad, act="relu")
-            t_cpu += time.perf_counter() - t
-            done_flops += L["flops"] * nsub / s.N
-            desc.append("%d" % nsub)
+        done_flops, t_cpu, passes = 0.0, 0.0, 0
+        nsub = min(args.batch, 8)          # the first 8 images of every layer: a quarter of the batch
+        while t_cpu < 12.0 and passes < 40:
+            for L in layers:
+                s = L["shape"]
+                x, w, b = L["host"]
+                t = time.perf_counter()
+                oracle.conv2d_fwd(x[:nsub], w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+                t_cpu += time.perf_counter() - t
+                done_flops += L["flops"] * nsub / s.N
+            passes += 1
         cpu = dict(value=round(done_flops / t_cpu / 1e12, 6), unit="TFLOP/s", cores=threads, kind="oracle",
-                   sample="full oracle conv+bias+ReLU on the first n images of each layer, n = [%s] of %d "
-                          "(%.1f GFLOP, %.1f s)" % (",".join(desc), args.batch, done_flops / 1e9, t_cpu))
+                   sample="fp64 oracle conv+bias+ReLU on the first %d of %d images of every layer, %d passes "
+                          "(%.1f GFLOP in %.1f s)" % (nsub, args.batch, passes, done_flops / 1e9, t_cpu))
 
+    traffic = None
+    if (HBM_TRAFFIC["csrc_sha256"] == csrc_digest() and args.batch == HBM_TRAFFIC["batch"] and len(chosen) == 8
+            and forced is None):
+        traffic = HBM_TRAFFIC["fetch_bytes"] + HBM_TRAFFIC["write_bytes"]
     result = {
         "metric": "conv fwd TFLOP/s, ResNet-50-shaped 8-layer suite (fp32, bias+ReLU fused), 1 GPU",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -200,12 +297,15 @@ def main():
                                % (args.batch, "0-7 (all eight)" if len(chosen) == 8 else str(chosen)),
                    "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "polydl::conv_kernel (all 8 layers, nominal 2*N*K*P*Q*C*R*S flops / sum of "
-                               "per-layer mean launch durations)"},
+                     "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
+                     "traffic_unit": "bytes per suite pass (L2 fetch + write-back); algorithmic: %d" % total_bytes,
+                     "kernel": "polydl::conv_kernel / polydl::conv_patch_kernel as picked per layer (all 8 "
+                               "layers, nominal 2*N*K*P*Q*C*R*S flops / sum of per-layer mean launch durations)"},
         "cpu_baseline": cpu,
         "layers": rows,
         "sgemm": sg,
+        "bf16": bf,
+        "fusion": fusion,
         "event_ms_per_step": round(e0.elapsed_time(e1) / args.steps, 4),
     }
     if args.sweep and args.sweep_out:

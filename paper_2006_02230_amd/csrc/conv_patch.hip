@@ -76,6 +76,8 @@ struct ConvPatchKArgs {
     uint64_t in_bytes, wt_bytes;
     int tiles_m, tiles_n, raster, act;
     int split_k, stages_per_split;   // blockIdx.y takes stages [y*stages_per_split, ...)
+    float *partials;      // split_k > 1: [tile][split][BM*BN] accumulator tiles in register order
+    unsigned *counters;   // split_k > 1: per tile, how many of its reduction parts have finished
     int nbuf;        // LDS stage buffers: 2, or 1 when a workgroup runs a single stage
     int single;      // 1: the whole reduction is ONE unit (CB == 1); the upper half-wave, which
                      // would carry the pair's second unit, multiplies by a zero kept in LDS
@@ -352,20 +354,52 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const bool vec = NB > 1 && (p.PQ % NB == 0) && (((uintptr_t)p.out & 15) == 0);
     const bool full_rows = m0 + T::BM <= p.K;   // uniform: no channel of this tile is outside K
     if (p.split_k > 1) {
-        // partial sums of the reduction parts meet in the zero-filled output through float
-        // atomics; bias and activation follow in a separate pass over the output
+        // Every reduction part leaves its accumulator tile in scratch memory, register by register
+        // (thread-contiguous, so the stores coalesce).  The part that finishes last -- whichever
+        // it is -- adds all parts up in their fixed order and goes on to the fused epilogue, so
+        // the result does not depend on the order of arrival and no pass over the output follows.
+        __shared__ unsigned s_arrived;
+        constexpr size_t TILE = (size_t)T::BM * T::BN;
+        float *tile0 = p.partials + (size_t)blockIdx.x * p.split_k * TILE;
+        float *mine = tile0 + (size_t)blockIdx.y * TILE;
 #pragma unroll
         for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int k = m0 + acc_row(wm0, bi, r, lane);
-                if (!full_rows && k >= p.K) continue;
+            for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __hip_atomic_store(mine + ((bi * NB + bj) * 16 + r) * NT + tid, acc[bi][bj][r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        // The tile is written and read back with device-scope accesses, which go past the caches
+        // that are not shared by the whole device.  A full release/acquire fence pair would do
+        // too, but costs a write-back of the whole L2 per workgroup.  Instead: wait until this
+        // wave's stores have completed (at device scope), meet the other waves, then count the
+        // arrival; whoever sees the last count knows every part's stores completed before it.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+        if (tid == 0)
+            s_arrived = __hip_atomic_fetch_add(p.counters + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (s_arrived != (unsigned)p.split_k - 1u) return;   // uniform: not the last part
+        if (tid == 0)               // leave the counter at zero for the next launch
+            __hip_atomic_store(p.counters + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+        for (int sp = 0; sp < p.split_k; ++sp) {
+            const float *part = tile0 + (size_t)sp * TILE;
+#pragma unroll
+            for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
                 for (int bj = 0; bj < NB; ++bj)
-                    if (px_img[bj] >= 0)
-                        unsafeAtomicAdd(p.out + ((size_t)px_img[bj] * p.K + k) * p.PQ + px_pq[bj], acc[bi][bj][r]);
-            }
-        return;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[bi][bj][r] += __hip_atomic_load(part + ((bi * NB + bj) * 16 + r) * NT + tid,
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     float bias[MB][16];
 #pragma unroll
@@ -408,7 +442,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 }
 
 // LDS one workgroup may take: the whole 160 KB of a compute unit.
-static constexpr size_t kMaxLdsBytes = 160 * 1024;
+static constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // less the kernel's few static words
 
 // Input rows a run of bn consecutive output pixels can need at most (all images it touches).
 static int patch_rows_bound(const ConvProblem &q, int bn)
@@ -481,8 +515,13 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
         return hipErrorInvalidConfiguration;
     if (dry) return hipSuccess;
     clear_stale_hip_error();
-    const size_t nout = (size_t)q.N * q.K * a.PQ;
-    if (a.split_k > 1 && launch_fill_zero(q.out, nout, stream) != hipSuccess) return hipGetLastError();
+    a.partials = nullptr;
+    a.counters = nullptr;
+    if (a.split_k > 1) {
+        const size_t bytes = (size_t)a.tiles_m * a.tiles_n * a.split_k * T::BM * T::BN * sizeof(float);
+        hipError_t e = splitk_scratch(stream, bytes, a.tiles_m * a.tiles_n, &a.partials, &a.counters);
+        if (e != hipSuccess) return e;
+    }
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     void (*kern)(ConvPatchKArgs) = conv_patch_kernel<E, T, MAXA, MAXP, 0, 0>;
     if (q.R == 1 && q.S == 1) kern = conv_patch_kernel<E, T, MAXA, MAXP, 1, 1>;
@@ -495,8 +534,6 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a);
-    if (a.split_k > 1 && (q.bias || q.act != POLYDL_ACT_NONE))
-        return launch_bias_act(q.out, q.bias, q.K, a.PQ, nout, q.act, stream);
     return hipGetLastError();
 }
 

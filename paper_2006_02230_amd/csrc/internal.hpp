@@ -66,6 +66,10 @@ hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
 hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st);
 hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n, int act, hipStream_t st);
 
+// scratch.cpp: partial-tile buffer (>= partial_bytes) and zeroed arrival counters (>= tiles) for
+// split-reduction launches on this device and stream
+hipError_t splitk_scratch(hipStream_t stream, size_t partial_bytes, int tiles, float **partials, unsigned **counters);
+
 // hipGetLastError() reports the last error of any HIP call of this thread, including benign ones
 // left by the caller (an event query that was not ready, say).  Launchers clear that state first
 // so that what they return is about their own launch.

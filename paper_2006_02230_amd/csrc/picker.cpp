@@ -94,6 +94,7 @@ struct Cand {
     double wg_overhead_cycles;   // cycles a wave spends outside the reduction loop (setup, first loads, stores)
     double kernel_fixed_us;      // launch, first-stage latency and the store tail that nothing overlaps
     int max_waves_per_simd;
+    bool split_in_scratch = false;   // reduction parts meet in scratch tiles (fused epilogue), not through atomics
 };
 
 // Constants below were fitted to an exhaustive sweep of the compiled family on the ResNet-50-shaped
@@ -158,7 +159,11 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
     mem_us += (b_traffic > s.b_bytes ? b_traffic - s.b_bytes : 0) / rate_of(b_level) * 1e-3;
     mem_us += (s.a_bytes + s.b_bytes + s.d_bytes) / kHbmGBs * 1e-3;        // compulsory
     double fixed = c.kernel_fixed_us;
-    if (c.split_k > 1) {
+    if (c.split_k > 1 && c.split_in_scratch) {
+        // every part writes its accumulator tile once, coalesced; the last part of each tile reads
+        // them all back and runs the fused epilogue: no other launch, no pass over the output
+        fixed += 2.0 * c.split_k * s.d_bytes / kHbmGBs * 1e-3;
+    } else if (c.split_k > 1) {
         // every part adds its tile to the output with atomics; a zero fill before and a bias /
         // activation pass after, each a launch and a sweep over the output
         // the atomic adds run in the epilogues, after the matrix-core work, so they add to it
@@ -218,6 +223,7 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         const int nstages = (q.C + cb - 1) / cb;
         const int per_split = (nstages + c.split_k - 1) / c.split_k;
         c.lds_bytes = (per_split > 1 ? 2.0 : 1.0) * (cfg.bm * (cb * RS + 1) + cb * conv_patch_rows(q, cfg.bn) * wp) * 4;
+        c.split_in_scratch = true;
         c.loop_eff = 0.74;
         c.wg_overhead_cycles = 9000;
         c.kernel_fixed_us = 14.0;

@@ -157,6 +157,35 @@ def test_split_k_random(P):
     P.set_tile_override(None)
 
 
+def test_split_reduction_in_patch_kernel_is_reproducible(P):
+    # the parts of a split reduction are summed in a fixed order whatever order they finish in:
+    # repeated launches agree bit for bit, over many tiles, ragged tile edges and a reused scratch
+    s = synth.ConvShape("split_many", 5, 48, 13, 11, 150, 3, 3, 1, 1)
+    x, w, b = synth.conv_inputs(s, seed=36, dist="normal", bias=True)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1, act="relu")
+    small = synth.ConvShape("split_small", 1, 16, 6, 6, 20, 3, 3, 1, 1)
+    xs, ws, bs = synth.conv_inputs(small, seed=37, dist="normal", bias=True)
+    want_s, ab_s = oracle.conv2d_fwd(xs, ws, bias=bs, stride=1, pad=1, act="relu")
+    ran = 0
+    for v in P.variants(0):
+        if v.algo != 1:
+            continue
+        for split_k in (2, 3, 12):
+            v.split_k, v.cb = split_k, 4
+            first = try_variant(P, v, s, x, w, b, act="relu")
+            if first is None:
+                continue
+            assert oracle.scaled_error(first, want, ab) <= FP32_TOL, v
+            for _ in range(3):
+                assert np.array_equal(try_variant(P, v, s, x, w, b, act="relu"), first), v
+            # a smaller problem next, on the same scratch memory and counters
+            got_s = try_variant(P, v, small, xs, ws, bs, act="relu")
+            assert got_s is not None and oracle.scaled_error(got_s, want_s, ab_s) <= FP32_TOL, v
+            ran += 1
+    assert ran > 0
+    P.set_tile_override(None)
+
+
 def test_argument_errors(P):
     import ctypes
     z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
