@@ -10,7 +10,11 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpolydl.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # matrix-core results stay in ordinary vector registers: without this the compiler keeps
+         # the accumulators in the accumulation registers inside the reduction loop and copies all
+         # of them out and back in every stage
+         "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include"]

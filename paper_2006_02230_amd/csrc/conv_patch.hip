@@ -289,31 +289,36 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         const uint64_t a_skip = ((uint64_t)m0 * p.Kg + k0) * E::BYTES;
         __amdgpu_buffer_rsrc_t ra = make_rsrc(reinterpret_cast<const char *>(p.wt) + a_skip, p.wt_bytes - a_skip);
         unit_t *A = As + buf * a_stage + wave * 64;
+        if (krem >= p.D) {
 #pragma unroll
-        for (int i = 0; i < MAXA; ++i)
-            if (i * NT < a_elems) {
-                uint32_t off = a_goff[i];
-                if (krem < p.D) {       // last stage of a channel count that is no multiple of CB
+            for (int i = 0; i < MAXA; ++i)
+                if (i * NT < a_elems) lds_dma<E::BYTES>(ra, A + i * NT, a_goff[i]);
+        } else {
+            // last stage of a channel count that is no multiple of CB: columns past the end are zero
+#pragma unroll
+            for (int i = 0; i < MAXA; ++i)
+                if (i * NT < a_elems) {
                     uint32_t e = (uint32_t)(tid + i * NT);
                     uint32_t m = fdiv(e, p.magic_lda, 0u);
                     int kk = (int)(e - m * (uint32_t)p.LDA);
-                    off = kk < krem ? off : kOobOffset;
+                    lds_dma<E::BYTES>(ra, A + i * NT, kk < krem ? a_goff[i] : kOobOffset);
                 }
-                lds_dma<E::BYTES>(ra, A + i * NT, off);
-            }
+        }
         const uint64_t b_skip = ((uint64_t)img_a * p.C + c0) * p.HW * E::BYTES;
         __amdgpu_buffer_rsrc_t rb = make_rsrc(reinterpret_cast<const char *>(p.in) + b_skip, p.in_bytes - b_skip);
         unit_t *B = Bs + buf * p.b_stage + wave * 64;
+        if (crem >= p.CB) {
 #pragma unroll
-        for (int i = 0; i < MAXP; ++i)
-            if (i * NT < patch_elems) {
-                uint32_t off = p_goff[i];
-                if (crem < p.CB) {
+            for (int i = 0; i < MAXP; ++i)
+                if (i * NT < patch_elems) lds_dma<E::BYTES>(rb, B + i * NT, p_goff[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < MAXP; ++i)
+                if (i * NT < patch_elems) {
                     uint32_t c_l = fdiv((uint32_t)(tid + i * NT), magic_chs, one_chs);
-                    off = (int)c_l < crem ? off : kOobOffset;
+                    lds_dma<E::BYTES>(rb, B + i * NT, (int)c_l < crem ? p_goff[i] : kOobOffset);
                 }
-                lds_dma<E::BYTES>(rb, B + i * NT, off);
-            }
+        }
     };
 
     const int npairs = (p.CB + 1) >> 1;
