@@ -51,6 +51,8 @@ def conv_bytes(s, P, Q):
 def time_calls(torch, fn, reps, batches=3):
     """Median over batches of the mean time (ms) of reps back-to-back calls between two events."""
     out = []
+    for _ in range(max(2, reps // 4)):   # clocks and caches as in steady state
+        fn()
     for _ in range(batches):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
