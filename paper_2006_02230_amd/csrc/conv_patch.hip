@@ -583,6 +583,8 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
                                                            hipStream_t st, bool dry)                     \
     {                                                                                                    \
         /* the instantiation with fewer per-thread passes needs fewer registers: more waves per SIMD */ \
+        if (conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 6, 4>(q, cb, sk, r, st, true) == hipSuccess)         \
+            return conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 6, 4>(q, cb, sk, r, st, dry);                 \
         if (conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, true) == hipSuccess)        \
             return conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, sk, r, st, dry);                \
         return conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, sk, r, st, dry);                   \
@@ -598,11 +600,13 @@ POLYDL_PATCH_FAMILY(POLYDL_DEFINE_CONV_PATCH)
     }
 POLYDL_PATCH_BF16_FAMILY(POLYDL_DEFINE_CONV_PATCH_BF16)
 
-// 1 if the problem runs in the instantiation with few per-thread passes (fewer registers, more
-// waves per SIMD), 0 if it needs the large one, -1 if neither holds it.
+// 2 or 1 if the problem runs in an instantiation with few per-thread passes (fewer registers,
+// more waves per SIMD; 2 is the smallest), 0 if it needs the large one, -1 if none holds it.
 #define POLYDL_DEFINE_PATCH_CLASS(BM, BN, BK, WM, WN)                                                   \
     int conv_patch_class_##BM##x##BN##_##WM##x##WN(const ConvProblem &q, int cb)                         \
     {                                                                                                    \
+        if (conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 6, 4>(q, cb, 1, 0, nullptr, true) == hipSuccess)    \
+            return 2;                                                                                    \
         if (conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 12, 8>(q, cb, 1, 0, nullptr, true) == hipSuccess)   \
             return 1;                                                                                    \
         return conv_patch_launch<ElemF32, Tile<BM, BN, 8, WM, WN>, 40, 32>(q, cb, 1, 0, nullptr, true) == hipSuccess \

@@ -35,7 +35,7 @@ struct PatchVariant {
     int bm, bn, wm, wn;
     int threads;
     hipError_t (*conv)(const ConvProblem &, int cb, int split_k, int raster, hipStream_t, bool dry);
-    int (*reg_class)(const ConvProblem &, int cb);   // 1 small-register instantiation, 0 large, -1 none
+    int (*reg_class)(const ConvProblem &, int cb);   // 2, 1: small-register instantiations, 0 large, -1 none
 };
 
 extern const Variant kVariants[];

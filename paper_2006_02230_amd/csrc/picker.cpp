@@ -230,12 +230,12 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         // the small-register instantiation holds 5 waves per SIMD with a 32x32 wave tile, 3 with
         // 64x32 in the 128x64 tile; everything else 2
         c.max_waves_per_simd = 2;
-        if (reg_class == 1 && cfg.wm * cfg.wn == 32 * 32) {
+        if (reg_class >= 1 && cfg.wm * cfg.wn == 32 * 32) {
             c.max_waves_per_simd = 5;      // enough waves to cover each other's loads and stores
             c.loop_eff = 0.92;
             c.wg_overhead_cycles = 4000;
         }
-        else if (reg_class == 1 && cfg.bm == 128 && cfg.bn == 64) c.max_waves_per_simd = 3;
+        else if (reg_class >= 1 && cfg.bm == 128 && cfg.bn == 64) c.max_waves_per_simd = 3;
     } else {
         c.steps_per_stage = cfg.bk / 2.0;
         c.lds_bytes = 2.0 * (cfg.bm * (cfg.bk + 4) + cfg.bk * (cfg.bn + 4)) * 4;
