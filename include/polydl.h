@@ -52,8 +52,6 @@ typedef struct polydl_tile_cfg {
     int bm, bn, bk;   /* workgroup tile: bm x bn outputs, bk reduction elements per stage      */
     int wm, wn;       /* wave tile (multiples of 32); the workgroup has (bm/wm)*(bn/wn) waves  */
     int split_k;      /* >= 1: the reduction is cut into this many parts (one workgroup each);  */
-                      /* 0 (algo 1 only): whole tiles while they fill rounds of the workgroups the  */
-                      /* device holds at once, the tiles left over cut to fill one more round     */
     int layout;       /* 0: read NCHW / KCRS directly; 1: via blocked NCHWc / KCRSck copies    */
     int raster;       /* 0: workgroups walk M fastest; 1: chunked per XCD, grouped for L2 reuse */
     int algo;         /* convolution only.  0: im2col columns gathered element by element from

@@ -315,7 +315,6 @@ def conv_candidates(shape):
                 if cpad % cb:
                     continue
                 stages = -(-C // cb)
-                out.append(TileCfg(v.bm, v.bn, 0, v.wm, v.wn, 0, 0, 0, 1, cb))   # leftover tiles cut to fill a round
                 for sk in splits:
                     if sk > stages:
                         break

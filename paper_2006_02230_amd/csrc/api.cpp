@@ -186,7 +186,7 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         if (!pv) return POLYDL_ERR_UNSUPPORTED;
         if (cfg.cb == 0) cfg.cb = choose_cb(*pv, q);
         if (cfg.cb < 2 || (cfg.cb & 1)) return POLYDL_ERR_UNSUPPORTED;
-        const int sk = cfg.split_k < 0 ? 1 : cfg.split_k;   // 0: even division over a resident grid
+        const int sk = cfg.split_k < 1 ? 1 : cfg.split_k;
         if (pv->conv(q, cfg.cb, sk, cfg.raster, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
         hipError_t pe = pv->conv(q, cfg.cb, sk, cfg.raster, (hipStream_t)stream, false);
         if (pe != hipSuccess) return launch_failed(pe);
@@ -337,7 +337,7 @@ int polydl_conv2d_fwd_bf16_blocked(int N, int C, int H, int W, int K, int R, int
             if (pv->conv(q, cb, 1, 0, nullptr, true) == hipSuccess) cfg.cb = cb;
     }
     if (cfg.cb < 2 || (cfg.cb & 1)) return POLYDL_ERR_UNSUPPORTED;
-    const int sk = cfg.split_k < 0 ? 1 : cfg.split_k;
+    const int sk = cfg.split_k < 1 ? 1 : cfg.split_k;
     if (pv->conv(q, cfg.cb, sk, cfg.raster, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
     hipError_t e = pv->conv(q, cfg.cb, sk, cfg.raster, (hipStream_t)stream, false);
     if (e != hipSuccess) return launch_failed(e);
@@ -472,7 +472,7 @@ int polydl_set_tile_override(const polydl_tile_cfg *cfg)
     }
     const bool known = cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
                                       : (cfg->algo == 0 && find_variant(*cfg) != nullptr);
-    if (!known || cfg->split_k < (cfg->algo == 1 ? 0 : 1) || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
+    if (!known || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
         cfg->raster > 1 || cfg->cb < 0 || (cfg->cb & 1))
         return POLYDL_ERR_UNSUPPORTED;
     g_override = *cfg;

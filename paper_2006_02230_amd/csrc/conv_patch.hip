@@ -75,10 +75,9 @@ struct ConvPatchKArgs {
     uint32_t magic_Wp, one_Wp, magic_rf, one_rf, magic_lda;
     uint64_t in_bytes, wt_bytes;
     int tiles_m, tiles_n, raster, act;
-    // Workgroup b < T_full runs the whole reduction of tile b.  The tiles from T_full on are cut
-    // into split_k parts of stages_per_split stages each: workgroup T_full + t*split_k + y takes
-    // part y of tile T_full + t.  (T_full = 0: every tile is cut.)
-    int split_k, stages_per_split, T_full;
+    // split_k > 1: every tile's reduction is cut into split_k parts of stages_per_split stages;
+    // workgroup t*split_k + y takes part y of tile t
+    int split_k, stages_per_split;
     float *partials;      // split_k > 1: [tile][split][BM*BN] accumulator tiles in register order
     unsigned *counters;   // split_k > 1: per tile, how many of its reduction parts have finished
     int nbuf;        // LDS stage buffers: 2, or 1 when a workgroup runs a single stage
@@ -181,13 +180,13 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, lh = lane >> 5;
-    int tile = blockIdx.x, part = 0, cut_tile = 0;
-    if (tile >= p.T_full && p.split_k > 1) {
-        cut_tile = (tile - p.T_full) / p.split_k;
-        part = tile - p.T_full - cut_tile * p.split_k;
-        tile = p.T_full + cut_tile;
+    const bool cut = p.split_k > 1;   // uniform
+    int tile = blockIdx.x, part = 0;
+    if (cut) {
+        tile = blockIdx.x / p.split_k;
+        part = blockIdx.x - tile * p.split_k;
     }
-    const bool cut = blockIdx.x >= p.T_full && p.split_k > 1;   // uniform
+    const int cut_tile = tile;
     int tm, tn;
     tile_coords(tile, p.raster, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
@@ -514,35 +513,14 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     // what one thread may hold, and the LDS a workgroup may take
     if ((long)a.a_stage > (long)MAXA * T::NT) return hipErrorInvalidConfiguration;
     if ((long)a.b_stage > (long)MAXP * T::NT) return hipErrorInvalidConfiguration;
-    // split_k == 0: whole tiles for as many full rounds of the resident workgroups as there are,
-    // and the tiles left over cut into about as many parts as fill one more round
     const int tiles = a.tiles_m * a.tiles_n;
-    a.T_full = 0;
-    if (split_k == 0) {
-        // resident workgroups, from an estimate of the kernel's registers (accumulators, offset
-        // tables, operands) and its LDS need with two stage buffers: 512 registers per SIMD lane,
-        // at most 8 waves per SIMD, 4 SIMDs and 160 KB of LDS per compute unit, 256 compute units
-        const int regs = (16 * T::MB * T::NB + MAXA + MAXP + 40 + 7) & ~7;
-        const int waves_per_simd = 512 / regs > 8 ? 8 : 512 / regs;
-        const int by_regs = waves_per_simd * 4 / (T::NT / 64);
-        const size_t lds2 = ((size_t)2 * ((size_t)a.a_stage + a.b_stage) + 64) * E::BYTES;
-        const int by_lds = (int)(kMaxLdsBytes / ((lds2 + 1023) & ~(size_t)1023));
-        const int per_cu = by_regs < by_lds ? by_regs : by_lds;
-        const long G = 256L * (per_cu < 1 ? 1 : per_cu);
-        a.T_full = (int)(tiles / G * G);
-        const long left = tiles - a.T_full;
-        split_k = left > 0 ? (int)((G + left / 2) / left) : 1;
-        if (split_k > 16) split_k = 16;
-        if (split_k <= 1) { split_k = 1; a.T_full = 0; }
-    }
     if (split_k < 1) split_k = 1;
     if (split_k > a.nstages) split_k = a.nstages;
     a.stages_per_split = (a.nstages + split_k - 1) / split_k;
     a.split_k = (a.nstages + a.stages_per_split - 1) / a.stages_per_split;
     if (a.split_k > 65535) return hipErrorInvalidConfiguration;
-    if (a.split_k <= 1) a.T_full = 0;
     // one stage buffer is enough when no workgroup runs more than one stage
-    a.nbuf = (a.T_full > 0 ? a.nstages : a.stages_per_split) > 1 ? 2 : 1;
+    a.nbuf = a.stages_per_split > 1 ? 2 : 1;
     // the stage buffers and the zero unit behind them (kept a whole 64-unit row for alignment)
     const size_t lds_bytes = ((size_t)a.nbuf * ((size_t)a.a_stage + a.b_stage) + 64) * E::BYTES;
     if (lds_bytes > kMaxLdsBytes) return hipErrorInvalidConfiguration;
@@ -555,7 +533,7 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     clear_stale_hip_error();
     a.partials = nullptr;
     a.counters = nullptr;
-    const int cut_tiles = a.split_k > 1 ? tiles - a.T_full : 0;
+    const int cut_tiles = a.split_k > 1 ? tiles : 0;
     if (cut_tiles > 0) {
         const size_t bytes = (size_t)cut_tiles * a.split_k * T::BM * T::BN * sizeof(float);
         hipError_t e = splitk_scratch(stream, bytes, cut_tiles, &a.partials, &a.counters);

@@ -95,6 +95,16 @@ struct Cand {
     double kernel_fixed_us;      // launch, first-stage latency and the store tail that nothing overlaps
     int max_waves_per_simd;
     bool split_in_scratch = false;   // reduction parts meet in scratch tiles (fused epilogue), not through atomics
+    // Convolution kernels are timed round by round (see model()): workgroups that are resident
+    // together start, load and store in step, so each round pays its own latency.
+    bool rounds = false;
+    int regs = 128;              // vector registers the compiler reports for the instantiation
+    double eff_sat = 0.65;       // matrix-core share of a stage once enough workgroups share a SIMD
+    double t_lat_us = 0.8;       // a stage is never shorter than one global-to-LDS round trip
+    double t_round_us = 8.0;     // per round: setup, first loads, epilogue of the last workgroup
+    double gather_elems = 0;     // B elements a thread gathers per stage (im2col addressing in the ALUs)
+    double gather_cycles = 0;    // cycles of that addressing per element
+    double split_c0 = 0, split_c1 = 0;   // split reduction: microseconds, and microseconds per MB of parts
 };
 
 // Constants below were fitted to an exhaustive sweep of the compiled family on the ResNet-50-shaped
@@ -126,7 +136,26 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
     // setup plus an epilogue that grows with the accumulators a lane has to store
     const double overhead = c.wg_overhead_cycles * (0.3 + 0.7 * mb * nb / 2.0);
     const double wave_cycles = steps * mb * nb * 64.0 / eff + overhead;
-    const double mfma_us = waves_on_busiest_simd * wave_cycles / kClockHz * 1e6;
+    double mfma_us = waves_on_busiest_simd * wave_cycles / kClockHz * 1e6;
+    if (c.rounds) {
+        // Resident workgroups per CU, from registers (512 per SIMD lane, at most 8 waves per SIMD)
+        // and LDS (160 KB).  The grid runs in rounds of that many workgroups per CU; within a
+        // round the workgroups of a CU share its matrix cores stage by stage, and a round ends
+        // with the epilogue of its workgroups before the next one's first loads are issued.
+        const int waves_per_simd = std::min(8, 512 / ((c.regs + 7) / 8 * 8));
+        const double by_regs = std::floor(waves_per_simd * kSimdsPerCU / waves_per_wg);
+        const double by_lds = std::floor(160.0 * 1024 / c.lds_bytes);
+        const double occ = std::max(1.0, std::min(by_regs, by_lds));
+        const double per_cu = wgs / kCUs;
+        const double full_rounds = std::floor(per_cu / occ);
+        const double rest = per_cu - full_rounds * occ;
+        const double stages = std::ceil(steps / c.steps_per_stage);
+        const double simd_share = std::ceil(waves_per_wg / kSimdsPerCU);
+        const double t_stage = c.steps_per_stage * mb * nb * 64.0 * simd_share / kClockHz * 1e6 / c.eff_sat +
+                               c.gather_elems * c.gather_cycles / kClockHz * 1e6;
+        auto round_us = [&](double n) { return c.t_round_us + stages * std::max(n * t_stage, c.t_lat_us); };
+        mfma_us = full_rounds * round_us(occ) + (rest > 1e-9 ? round_us(std::ceil(rest - 1e-9)) : 0.0);
+    }
     // ---- working sets (bytes) and where algorithm 2 places them -------------------------------
     const double ws_acc = (double)c.wm * c.wn * 4;                         // accumulators over the reduction
     const double ws_stage = c.lds_bytes;                                   // staged operands, shared by the waves
@@ -159,7 +188,11 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
     mem_us += (b_traffic > s.b_bytes ? b_traffic - s.b_bytes : 0) / rate_of(b_level) * 1e-3;
     mem_us += (s.a_bytes + s.b_bytes + s.d_bytes) / kHbmGBs * 1e-3;        // compulsory
     double fixed = c.kernel_fixed_us;
-    if (c.split_k > 1 && c.split_in_scratch) {
+    if (c.rounds) {
+        // nothing streams the tensors faster than this, with the first and last touches exposed
+        mem_us = std::max(mem_us, (s.a_bytes + s.b_bytes + s.d_bytes) / 4000.0 * 1e-3 + 3.0);
+        if (c.split_k > 1) fixed += c.split_c0 + c.split_c1 * c.split_k * s.d_bytes * 1e-6;
+    } else if (c.split_k > 1 && c.split_in_scratch) {
         // every part writes its accumulator tile once, coalesced; the last part of each tile reads
         // them all back and runs the fused epilogue: no other launch, no pass over the output
         fixed += 2.0 * c.split_k * s.d_bytes / kHbmGBs * 1e-3;
@@ -236,6 +269,16 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
             c.wg_overhead_cycles = 4000;
         }
         else if (reg_class >= 1 && cfg.bm == 128 && cfg.bn == 64) c.max_waves_per_simd = 3;
+        // fitted on the sweep, by wave tile
+        const int mbn = (cfg.wm / 32) * 10 + cfg.wn / 32;
+        const int rc = reg_class < 0 ? 0 : reg_class;
+        c.rounds = true;
+        c.kernel_fixed_us = 5.0;
+        if (mbn == 11)      { static const int R[3] = {190, 80, 60};   c.regs = R[rc]; c.eff_sat = 0.65; c.t_lat_us = 0.8; c.t_round_us = 10; }
+        else if (mbn == 21) { static const int R[3] = {190, 121, 106}; c.regs = R[rc]; c.eff_sat = 0.65; c.t_lat_us = 0.8; c.t_round_us = 12; }
+        else                { static const int R[3] = {210, 155, 140}; c.regs = R[rc]; c.eff_sat = 0.65; c.t_lat_us = 0.8; c.t_round_us = 18; }
+        if (cfg.bm == 128 && cfg.bn == 64) { static const int R[3] = {190, 100, 89}; c.regs = R[rc]; }
+        c.split_c0 = 0; c.split_c1 = 0.1;
     } else {
         c.steps_per_stage = cfg.bk / 2.0;
         c.lds_bytes = 2.0 * (cfg.bm * (cfg.bk + 4) + cfg.bk * (cfg.bn + 4)) * 4;
@@ -243,6 +286,20 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         c.wg_overhead_cycles = 5000;
         c.kernel_fixed_us = 10.0;
         c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 1 : ((cfg.wm * cfg.wn == 64 * 64) ? 2 : 4);
+        const int mbn = (cfg.wm / 32) * 10 + cfg.wn / 32;
+        const bool contiguous = q.R == 1 && q.S == 1 && q.stride == 1;   // im2col columns are input rows
+        c.rounds = true;
+        c.kernel_fixed_us = 5.0;
+        c.gather_elems = (double)cfg.bk * cfg.bn / threads;
+        switch (mbn) {
+        case 11: c.regs = 70;  c.eff_sat = 0.70; c.t_lat_us = 0.6; c.t_round_us = 6;  c.gather_cycles = 40; c.split_c0 = 0;  c.split_c1 = 0.2;  break;
+        case 12: c.regs = 110; c.eff_sat = 0.65; c.t_lat_us = 1.0; c.t_round_us = 6;  c.gather_cycles = 20; c.split_c0 = 10; c.split_c1 = 0.45; break;
+        case 21: c.regs = 95;  c.eff_sat = 0.70; c.t_lat_us = 0.8; c.t_round_us = 8;  c.gather_cycles = 0;  c.split_c0 = 6;  c.split_c1 = 0.3;  break;
+        case 22: c.regs = cfg.bk == 16 ? 150 : 115; c.eff_sat = 0.60; c.t_lat_us = 0.8; c.t_round_us = 6; c.gather_cycles = 0; c.split_c0 = 15; c.split_c1 = 0.6; break;
+        case 24: c.regs = 215; c.eff_sat = 0.65; c.t_lat_us = 0.4; c.t_round_us = 10; c.gather_cycles = 20;  c.split_c0 = 15; c.split_c1 = 1.0; break;
+        default: c.regs = 240; c.eff_sat = 0.90; c.t_lat_us = 0.4; c.t_round_us = 16; c.gather_cycles = 160; c.split_c0 = 15; c.split_c1 = 1.0; break;
+        }
+        if (contiguous) c.gather_cycles *= 0.3;
     }
     Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
     model(s, c, r);

@@ -186,36 +186,6 @@ def test_split_reduction_in_patch_kernel_is_reproducible(P):
     P.set_tile_override(None)
 
 
-EVEN_SHAPES = SMALL[:8] + [
-    synth.ConvShape("even_many", 5, 48, 13, 11, 150, 3, 3, 1, 1),
-    synth.ConvShape("even_big", 72, 16, 28, 28, 32, 3, 3, 1, 1),     # more tiles than resident workgroups
-    synth.ConvShape("even_1x1", 9, 96, 14, 14, 80, 1, 1, 1, 0),
-]
-
-
-@pytest.mark.parametrize("s", EVEN_SHAPES, ids=lambda s: s.name)
-def test_leftover_tiles_cut_to_fill_a_round(P, s):
-    # split_k = 0: whole tiles for the full rounds of resident workgroups, the tiles left over cut into
-    # parts that are summed in a fixed order, so repeated launches agree bit for bit
-    x, w, b = synth.conv_inputs(s, seed=38, dist="normal", bias=True)
-    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
-    ran = 0
-    for v in P.variants(0):
-        if v.algo != 1:
-            continue
-        for cb in (2, 4):
-            v.split_k, v.cb = 0, cb
-            first = try_variant(P, v, s, x, w, b, act="relu")
-            if first is None:
-                continue
-            assert first.shape == want.shape
-            assert oracle.scaled_error(first, want, ab) <= FP32_TOL, (v, cb)
-            assert np.array_equal(try_variant(P, v, s, x, w, b, act="relu"), first), (v, cb)
-            ran += 1
-    assert ran > 0
-    P.set_tile_override(None)
-
-
 def test_argument_errors(P):
     import ctypes
     z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
