@@ -254,9 +254,15 @@ def main():
             P.conv2d_fwd(dx, dw, None, out=out, stride=s.stride, pad=s.pad, act=None)
             P.bias_add(out, db)
             P.activation(out, "relu")
-        fused(); separate()
-        t_f, t_s = time_calls(torch, fused, 50), time_calls(torch, separate, 50)
-        t_c = time_calls(torch, lambda: P.conv2d_fwd(dx, dw, None, out=out, stride=s.stride, pad=s.pad, act=None), 50)
+        conv_only = lambda: P.conv2d_fwd(dx, dw, None, out=out, stride=s.stride, pad=s.pad, act=None)
+        fused(); separate(); conv_only()
+        # the three are timed in turn, several times over, so that a drift of the clocks hits all alike
+        samples = {"f": [], "s": [], "c": []}
+        for _ in range(5):
+            samples["f"].append(time_calls(torch, fused, 20, batches=1))
+            samples["s"].append(time_calls(torch, separate, 20, batches=1))
+            samples["c"].append(time_calls(torch, conv_only, 20, batches=1))
+        t_f, t_s, t_c = (sorted(samples[k])[2] for k in ("f", "s", "c"))
         ob = 4.0 * s.N * s.K * Pq * Qq
         fusion = dict(workload="configs[3]: conv+bias+ReLU, N=%d C=K=%d %dx%d 3x3" % (s.N, s.C, s.H, s.W),
                       fused_us=round(t_f * 1e3, 2), separate_us=round(t_s * 1e3, 2), conv_only_us=round(t_c * 1e3, 2),

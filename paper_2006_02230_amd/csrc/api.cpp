@@ -275,8 +275,7 @@ int polydl_kcrs_to_kcrsck_bf16(int K, int C, int R, int S, int bc, int bk, const
     return launch_kcrsck(wt, out, K, C, R * S, bc, bk, 2, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
 }
 
-// bf16 candidates are ranked with the fp32 patch model scaled by the instruction's rate: good
-// enough to choose tile and split, since the same load-balance and overhead terms dominate
+// bf16 candidates are ranked with the round-by-round time model at the bf16 instruction's rate
 static bool pick_bf16(const ConvProblem &qb, polydl_tile_cfg *out)
 {
     const int cunits = qb.C;
@@ -291,10 +290,7 @@ static bool pick_bf16(const ConvProblem &qb, polydl_tile_cfg *out)
             for (int sk : splits) {
                 if (sk > nstages) break;
                 polydl_tile_cfg c = {v.bm, v.bn, 0, v.wm, v.wn, sk, 1, 0, 1, cb};
-                polydl_model_report rep;
-                model_conv(qb, c, v.threads, v.wm * v.wn == 32 * 32 ? 1 : 0, &rep);
-                // one bf16 step does 8x the work of an fp32 step in half the cycles
-                double t = std::max(rep.mfma_us / 2.0, rep.mem_us) + rep.fixed_us;
+                const double t = model_conv_bf16(qb, c, v.threads);
                 if (!have || t < best) { best = t; *out = c; have = true; }
             }
         }

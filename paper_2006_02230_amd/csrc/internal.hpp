@@ -80,6 +80,7 @@ void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, dou
 double reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight);
 void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, int reg_class, polydl_model_report *r);
 void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r);
+double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads);   // predicted microseconds
 bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
 bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
 

@@ -305,6 +305,41 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
     model(s, c, r);
 }
 
+// bfloat16 patch kernel; q.C counts units of eight channels.  Same round-by-round timing as the
+// fp32 kernels with the bf16 instruction's rate (a 32x32x16 step takes 32 cycles).  The stage
+// efficiency is low because every step needs two 16-byte operand reads per lane from LDS, which
+// the LDS cannot deliver at the matrix cores' pace; constants fitted to a sweep of the family on
+// the ResNet-50-shaped suite at batch 64.
+double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads)
+{
+    const double RS = (double)q.R * q.S;
+    const int cb = q.C == 1 ? 1 : std::max(2, cfg.cb);
+    const double mb = cfg.wm / 32.0, nb = cfg.wn / 32.0, waves_per_wg = threads / 64.0;
+    const double Ng = (double)q.N * q.P * q.Q;
+    const double tiles = std::ceil((double)q.K / cfg.bm) * std::ceil(Ng / cfg.bn);
+    const double nstages = std::ceil((double)q.C / cb);
+    const double per_split = std::ceil(nstages / std::max(1, cfg.split_k));
+    const double parts = std::ceil(nstages / per_split);
+    const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
+    const double stage_units = cfg.bm * (cb * RS + 1) + cb * conv_patch_rows(q, cfg.bn) * wp;
+    const double lds_bytes = (per_split > 1 ? 2.0 : 1.0) * stage_units * 16;
+    const int waves_per_simd = mb * nb == 1 ? 6 : (mb * nb == 2 ? 4 : 2);
+    const double occ = std::max(1.0, std::min(std::floor(waves_per_simd * kSimdsPerCU / waves_per_wg),
+                                              std::floor(160.0 * 1024 / lds_bytes)));
+    const double eff = 0.3, t_round = 6.0 * (1.0 + 0.5 * (mb * nb - 1) / 3.0), t_lat = 0.8;
+    const double t_stage = std::ceil(cb / 2.0) * RS * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
+                           kClockHz * 1e6 / eff;
+    const double per_cu = tiles * parts / kCUs;
+    const double full_rounds = std::floor(per_cu / occ), rest = per_cu - full_rounds * occ;
+    auto round_us = [&](double n) { return t_round + per_split * std::max(n * t_stage, t_lat); };
+    double t = full_rounds * round_us(occ) + (rest > 1e-9 ? round_us(std::ceil(rest - 1e-9)) : 0.0);
+    const double d_bytes = (double)q.N * q.K * q.P * q.Q * 4;
+    const double mem_bytes = (double)q.N * q.C * 8 * q.H * q.W * 2 + (double)q.K * q.C * 8 * RS * 2 + d_bytes;
+    t = 5.0 + std::max(t, mem_bytes / 4000.0 * 1e-3 + 3.0);
+    if (parts > 1) t += 0.2 * parts * d_bytes * 1e-6;
+    return t;
+}
+
 void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r)
 {
     Shape s;
