@@ -207,6 +207,17 @@ def main():
             sg.append(dict(n=n, us=round(ms * 1e3, 2), tflops=round(tf, 2),
                            frac_mfma=round(tf / FP32_MFMA_PEAK_TFLOPS, 4), tile=P.get_last_tile().as_dict()))
             del dA, dB, dC
+        # the (M, N, K) of the paper's GEMM-size table; values do not matter for the timing
+        for (M, N, K) in synth.PAPER_GEMM_SIZES:
+            dA = torch.rand((M, K), dtype=torch.float32, device="cuda") - 0.5
+            dB = torch.rand((K, N), dtype=torch.float32, device="cuda") - 0.5
+            dC = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+            P.sgemm(dA, dB, dC)
+            ms = time_calls(torch, lambda: P.sgemm(dA, dB, dC), 10)
+            tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+            sg.append(dict(mnk=[M, N, K], us=round(ms * 1e3, 2), tflops=round(tf, 2),
+                           frac_mfma=round(tf / FP32_MFMA_PEAK_TFLOPS, 4), tile=P.get_last_tile().as_dict()))
+            del dA, dB, dC
 
     # the same suite with bfloat16 inputs (fp32 accumulate and output) at batch 64: operands already in
     # the 8-channel blocked layouts, as a network that stays in that layout between layers holds them

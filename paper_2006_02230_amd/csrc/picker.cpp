@@ -408,7 +408,9 @@ bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_repor
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         const long stages = ((long)q.K + v.bk - 1) / v.bk;
-        for (int sk : kSplits) {
+        // long, skinny reductions (few output tiles) want many parts
+        static const int kSgemmSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128};
+        for (int sk : kSgemmSplits) {
             if (sk > stages) break;
             for (int raster = 0; raster < 2; ++raster) {
                 polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, raster, 0, 0};

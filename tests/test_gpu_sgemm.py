@@ -108,6 +108,24 @@ def test_square_sampled_compare(P, n):
     assert np.max(np.abs(got.astype(np.float64).sum(axis=1) - rs) / scale) <= FP32_TOL
 
 
+@pytest.mark.parametrize("M,N,K", synth.PAPER_GEMM_SIZES, ids=lambda v: str(v))
+def test_paper_gemm_sizes_sampled(P, M, N, K):
+    # the (M, N, K) of the paper's GEMM-size table (section "GEMM"), in the picker's own
+    # configuration; operands are drawn in row chunks (one stream each) to bound host memory
+    from synth import rng
+    seed = (M * 31 + N) * 31 + K
+    A = np.empty((M, K), np.float32)
+    rows = max(1, (1 << 24) // K)
+    for c, i0 in enumerate(range(0, M, rows)):
+        A[i0:i0 + rows] = rng.uniform_pm1(seed, 100 + c, (min(rows, M - i0), K))
+    B = rng.uniform_pm1(seed, 1, (K, N))
+    C0 = rng.uniform_pm1(seed, 2, (M, N))
+    got = run_sgemm(P, A, B, C0)
+    idx = sample_indices(M * N, 4000, seed=seed)
+    want, ab = oracle.gemm(A, B, C0, at=idx)
+    assert oracle.scaled_error(got.ravel()[idx], want, ab) <= FP32_TOL
+
+
 def test_argument_errors(P):
     import ctypes
     z = ctypes.c_void_p(0)
