@@ -283,6 +283,43 @@ def main():
                            "over it that the fused epilogue never makes")
         del dx, dw, out
 
+    # batch normalisation + ReLU in one pass against the two operators as two kernels, on the
+    # output tensors of the suite layers (memory bound: one read and one write per element)
+    bn = None
+    if not args.no_fusion and forced is None and len(chosen) == 8:
+        bn_rows, t_fused, t_sep, nbytes = [], 0.0, 0.0, 0.0
+        for L in layers:
+            y = L["out"]
+            K = y.shape[1]
+            g, be = torch.rand(K, device="cuda") + 0.5, torch.rand(K, device="cuda") - 0.5
+            mu, va = torch.rand(K, device="cuda") - 0.5, torch.rand(K, device="cuda") + 0.5
+            dst = torch.empty_like(y)
+            fused = lambda: P.bnorm_fwd(y, g, be, mu, va, 1e-5, out=dst, act="relu")
+
+            def separate():
+                P.bnorm_fwd(y, g, be, mu, va, 1e-5, out=dst, act=None)
+                P.activation(dst, "relu")
+            tf_, ts_ = [], []
+            for _ in range(3):
+                tf_.append(time_calls(torch, fused, 20, batches=1))
+                ts_.append(time_calls(torch, separate, 20, batches=1))
+            f_ms, s_ms = sorted(tf_)[1], sorted(ts_)[1]
+            b = 8.0 * y.numel()
+            bn_rows.append(dict(layer=L["index"], elements=y.numel(), fused_us=round(f_ms * 1e3, 2),
+                                separate_us=round(s_ms * 1e3, 2), fused_gbs=round(b / (f_ms * 1e-3) / 1e9, 1),
+                                frac_hbm=round(b / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)))
+            t_fused += f_ms
+            t_sep += s_ms
+            nbytes += b
+            del dst
+        bn = dict(workload="bnorm + ReLU on the eight NKPQ output tensors of the suite (N=%d), out of place" % args.batch,
+                  fused_us=round(t_fused * 1e3, 1), separate_us=round(t_sep * 1e3, 1),
+                  speedup=round(t_sep / t_fused, 3), fused_gbs=round(nbytes / (t_fused * 1e-3) / 1e9, 1),
+                  roofline={"bound": "hbm", "achieved": round(nbytes / (t_fused * 1e-3) / 1e9, 1),
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": round(nbytes / (t_fused * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+                  layers=bn_rows)
+
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -325,6 +362,7 @@ def main():
         "sgemm": sg,
         "bf16": bf,
         "fusion": fusion,
+        "bnorm_relu": bn,
         "event_ms_per_step": round(e0.elapsed_time(e1) / args.steps, 4),
     }
     if args.sweep and args.sweep_out:

@@ -126,6 +126,18 @@ int polydl_conv2d_fwd_bf16(int N, int C, int H, int W, int K, int R, int S, int 
  * polydl_activation: y = max(y,0) (POLYDL_ACT_RELU) or min(max(y,0),6) (POLYDL_ACT_RELU6), in
  *   place on `count` floats. */
 int polydl_bias_add(int N, int K, int P, int Q, float *y, const float *bias, void *stream);
+
+/* ---- batch normalisation followed by an activation, one pass (section "Experimental Evaluation",
+ * operator-fusion experiments: the bnorm + ReLU sequence fused by the fusion algorithm) ----------
+ * Inference form on an NKPQ fp32 tensor in device memory, per channel k:
+ *   y = act(gamma[k] * (x - mean[k]) / sqrt(var[k] + eps) + beta[k])
+ * gamma, beta, mean, var: K floats each (device); eps >= 0; y may be x (in place) or a disjoint
+ * tensor of the same shape; act as in polydl_act (POLYDL_ACT_NONE gives the unfused first half,
+ * polydl_activation the second).  Nothing is retained.  N*K*P*Q must be below 2^31.
+ * Errors: BAD_DIMENSION, NULL_POINTER, UNSUPPORTED (act, eps, size), LAUNCH. */
+int polydl_bnorm_fwd(int N, int K, int P, int Q, const float *x, const float *gamma, const float *beta,
+                     const float *mean, const float *var, float eps, float *y, int act /* polydl_act */,
+                     void *stream);
 int polydl_activation(int64_t count, float *y, int act, void *stream);
 
 /* ---- the reuse model (sections "Working set size computation" and "Poly-ranking algorithm") ------

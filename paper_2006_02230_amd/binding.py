@@ -64,6 +64,8 @@ lib.polydl_nchwc_to_nchw.argtypes = [_i] * 5 + [_p, _p, _p]
 lib.polydl_kcrs_to_kcrsck.argtypes = [_i] * 6 + [_p, _p, _p]
 lib.polydl_bias_add.argtypes = [_i] * 4 + [_p, _p, _p]
 lib.polydl_activation.argtypes = [ctypes.c_int64, _p, _i, _p]
+lib.polydl_bnorm_fwd.argtypes = [_i] * 4 + [_p] * 5 + [ctypes.c_float, _p, _i, _p]
+lib.polydl_bnorm_fwd.restype = _i
 for _f in (lib.polydl_nchw_to_nchwc, lib.polydl_nchwc_to_nchw, lib.polydl_kcrs_to_kcrsck,
            lib.polydl_bias_add, lib.polydl_activation):
     _f.restype = _i
@@ -249,6 +251,18 @@ def bias_add(y, bias, stream=None):
     N, K, P, Q = y.shape
     _check(lib.polydl_bias_add(N, K, P, Q, _dev(y, "y"), _dev(bias, "bias"), _stream_ptr(stream)), "polydl_bias_add")
     return y
+
+
+def bnorm_fwd(x, gamma, beta, mean, var, eps=1e-5, out=None, act=None, stream=None):
+    """polydl_bnorm_fwd on an NKPQ tensor; out defaults to a new tensor (pass out=x for in place)."""
+    import torch
+    N, K, P, Q = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    st = lib.polydl_bnorm_fwd(N, K, P, Q, _dev(x, "x"), _dev(gamma, "gamma"), _dev(beta, "beta"), _dev(mean, "mean"),
+                              _dev(var, "var"), ctypes.c_float(eps), _dev(out, "out"), ACT[act], _stream_ptr(stream))
+    _check(st, "polydl_bnorm_fwd")
+    return out
 
 
 def activation(y, act="relu", stream=None):

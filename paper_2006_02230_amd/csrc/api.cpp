@@ -380,6 +380,19 @@ int polydl_bias_add(int N, int K, int P, int Q, float *y, const float *bias, voi
                ? POLYDL_OK : POLYDL_ERR_LAUNCH;
 }
 
+int polydl_bnorm_fwd(int N, int K, int P, int Q, const float *x, const float *gamma, const float *beta,
+                     const float *mean, const float *var, float eps, float *y, int act, void *stream)
+{
+    if (N <= 0 || K <= 0 || P <= 0 || Q <= 0) return POLYDL_ERR_BAD_DIMENSION;
+    if (!x || !y || !gamma || !beta || !mean || !var) return POLYDL_ERR_NULL_POINTER;
+    if (act < POLYDL_ACT_NONE || act > POLYDL_ACT_RELU6 || !(eps >= 0.f)) return POLYDL_ERR_UNSUPPORTED;
+    // element indices are 31-bit in the kernel
+    if ((int64_t)N * K * P * Q >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
+    hipError_t e = launch_bnorm_act(x, y, gamma, beta, mean, var, eps, K, P * Q, (size_t)N * K * P * Q, act,
+                                    (hipStream_t)stream);
+    return e == hipSuccess ? POLYDL_OK : launch_failed(e);
+}
+
 int polydl_activation(int64_t count, float *y, int act, void *stream)
 {
     if (count <= 0) return POLYDL_ERR_BAD_DIMENSION;

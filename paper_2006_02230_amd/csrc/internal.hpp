@@ -63,6 +63,8 @@ hipError_t launch_kcrsck(const void *wt, void *dst, int K, int C, int RS, int bc
                          hipStream_t st);
 hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t total, hipStream_t st);
 hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
+hipError_t launch_bnorm_act(const float *x, float *y, const float *gamma, const float *beta, const float *mean,
+                            const float *var, float eps, int K, int PQ, size_t total, int act, hipStream_t st);
 hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st);
 hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n, int act, hipStream_t st);
 

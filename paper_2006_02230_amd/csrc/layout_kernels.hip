@@ -92,6 +92,62 @@ __global__ void act_kernel(float *__restrict__ y, size_t total, int act)
     }
 }
 
+// Inference batch normalisation with an optional activation in the same pass:
+// y = act(gamma[k] * (x - mean[k]) / sqrt(var[k] + eps) + beta[k]) on an NKPQ tensor (y may be x).
+// One thread handles four consecutive elements of one (n, k) plane when planes are a multiple of
+// four floats and both tensors are 16-byte aligned, else one element.  Bound by HBM: one read and
+// one write per element (the two integer divisions per thread are far below the ALU rate).
+template <int V>
+__global__ void bnorm_act_kernel(const float *__restrict__ x, float *__restrict__ y, const float *__restrict__ gamma,
+                                 const float *__restrict__ beta, const float *__restrict__ mean,
+                                 const float *__restrict__ var, float eps, uint32_t K, uint32_t PQ, uint32_t units,
+                                 int act)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t step = gridDim.x * blockDim.x;
+    for (; i < units; i += step) {
+        const uint32_t e = i * V;
+        const uint32_t k = (e / PQ) % K;
+        const float inv = 1.0f / sqrtf(var[k] + eps);
+        const float g = gamma[k], m = mean[k], b = beta[k];
+        float v[V];
+        if constexpr (V == 4) {
+            f4 t = *reinterpret_cast<const f4 *>(x + e);
+            for (int c = 0; c < 4; ++c) v[c] = t[c];
+        } else {
+            v[0] = x[e];
+        }
+        for (int c = 0; c < V; ++c) {
+            float r = g * ((v[c] - m) * inv) + b;
+            if (act != POLYDL_ACT_NONE) r = fmaxf(r, 0.f);
+            if (act == POLYDL_ACT_RELU6) r = fminf(r, 6.f);
+            v[c] = r;
+        }
+        if constexpr (V == 4) {
+            f4 t = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<f4 *>(y + e) = t;
+        } else {
+            y[e] = v[0];
+        }
+    }
+}
+
+hipError_t launch_bnorm_act(const float *x, float *y, const float *gamma, const float *beta, const float *mean,
+                            const float *var, float eps, int K, int PQ, size_t total, int act, hipStream_t st)
+{
+    clear_stale_hip_error();
+    const bool vec = PQ % 4 == 0 && (((uintptr_t)x | (uintptr_t)y) & 15) == 0;
+    const uint32_t units = (uint32_t)(vec ? total / 4 : total);
+    const unsigned blocks = (unsigned)((units + 255) / 256 < 16384 ? (units + 255) / 256 : 16384);
+    if (vec)
+        hipLaunchKernelGGL((bnorm_act_kernel<4>), dim3(blocks), dim3(256), 0, st, x, y, gamma, beta, mean, var, eps,
+                           (uint32_t)K, (uint32_t)PQ, units, act);
+    else
+        hipLaunchKernelGGL((bnorm_act_kernel<1>), dim3(blocks), dim3(256), 0, st, x, y, gamma, beta, mean, var, eps,
+                           (uint32_t)K, (uint32_t)PQ, units, act);
+    return hipGetLastError();
+}
+
 // Zero fill before a split reduction and the bias + activation pass after it (kernels rather than
 // memset nodes, so a captured graph replays them faithfully).
 __global__ void fill_zero_kernel(float *p, size_t n)
