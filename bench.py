@@ -86,7 +86,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on one GPU; --gpus %d is not supported "
-                 "(the path has no multi-GPU part, see DESIGN.md)" % args.gpus)
+                 "(the path has no multi-GPU part: it would shard over the batch with no exchange step)" % args.gpus)
 
     import numpy as np
     import torch
