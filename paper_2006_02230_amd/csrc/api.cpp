@@ -283,7 +283,8 @@ static bool pick_bf16(const ConvProblem &qb, polydl_tile_cfg *out)
     double best = 0;
     for (int i = 0; i < kNumPatchBf16Variants; ++i) {
         const PatchVariant &v = kPatchBf16Variants[i];
-        for (int cb = 2; cb <= ((cunits + 1) & ~1) && cb <= 32; cb += 2) {
+        // deepest stages first: on equal predictions fewer, longer stages win (fewer barriers)
+        for (int cb = std::min(32, (cunits + 1) & ~1); cb >= 2; cb -= 2) {
             if (v.conv(qb, cb, 1, 0, nullptr, true) != hipSuccess) continue;
             const int nstages = (cunits + cb - 1) / cb;
             const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16};
@@ -291,7 +292,7 @@ static bool pick_bf16(const ConvProblem &qb, polydl_tile_cfg *out)
                 if (sk > nstages) break;
                 polydl_tile_cfg c = {v.bm, v.bn, 0, v.wm, v.wn, sk, 1, 0, 1, cb};
                 const double t = model_conv_bf16(qb, c, v.threads);
-                if (!have || t < best) { best = t; *out = c; have = true; }
+                if (!have || t < best * 0.999) { best = t; *out = c; have = true; }
             }
         }
     }

@@ -326,9 +326,14 @@ double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int thr
     const int waves_per_simd = mb * nb == 1 ? 6 : (mb * nb == 2 ? 4 : 2);
     const double occ = std::max(1.0, std::min(std::floor(waves_per_simd * kSimdsPerCU / waves_per_wg),
                                               std::floor(160.0 * 1024 / lds_bytes)));
-    const double eff = 0.3, t_round = 6.0 * (1.0 + 0.5 * (mb * nb - 1) / 3.0), t_lat = 0.8;
-    const double t_stage = std::ceil(cb / 2.0) * RS * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
-                           kClockHz * 1e6 / eff;
+    // per wave tile: stage efficiency, per-round latency, stage latency floor, bytes per microsecond a
+    // CU stages into LDS, split cost per MB of parts
+    double eff = 0.3, t_round = 6.0, t_lat = 0.8, rate = 60000.0, c1 = 0.1;
+    if (mb * nb == 2) { eff = 0.4; t_round = 8.0; c1 = 0.2; }
+    else if (mb * nb == 4) { t_lat = 0.4; rate = 31000.0; c1 = 0.4; }
+    const double t_stage = std::max(std::ceil(cb / 2.0) * RS * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
+                                        kClockHz * 1e6 / eff,
+                                    (cfg.bm * cb * RS + cb * conv_patch_rows(q, cfg.bn) * wp) * 16.0 / rate);
     const double per_cu = tiles * parts / kCUs;
     const double full_rounds = std::floor(per_cu / occ), rest = per_cu - full_rounds * occ;
     auto round_us = [&](double n) { return t_round + per_split * std::max(n * t_stage, t_lat); };
@@ -336,7 +341,7 @@ double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int thr
     const double d_bytes = (double)q.N * q.K * q.P * q.Q * 4;
     const double mem_bytes = (double)q.N * q.C * 8 * q.H * q.W * 2 + (double)q.K * q.C * 8 * RS * 2 + d_bytes;
     t = 5.0 + std::max(t, mem_bytes / 4000.0 * 1e-3 + 3.0);
-    if (parts > 1) t += 0.2 * parts * d_bytes * 1e-6;
+    if (parts > 1) t += c1 * parts * d_bytes * 1e-6;
     return t;
 }
 
