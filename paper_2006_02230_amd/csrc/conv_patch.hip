@@ -66,8 +66,14 @@ struct ConvPatchKArgs {
                      // (1, stride) when R == 1 so that rows no tap reads are not staged
     int pcs, ics;    // the same for columns: (stride, 1), or (1, stride) when S == 1
     int CB;          // input channels per stage (even)
-    int nstages;     // ceil(C / CB)
-    int D;           // CB*R*S: reduction elements per stage
+    // Filter rows per stage.  Rp = R: a stage holds all R*S taps of its CB channels.  Rp = 1 (large
+    // filters): a stage holds ONE filter row of its CB channels -- S taps per channel, and of the
+    // input only the rows that filter row reads (one per output row) -- so that the LDS need of a
+    // stage does not grow with R; the R filter rows of a channel block are consecutive stages.
+    int Rp, nr;      // nr = R / Rp stages per channel block
+    int RSp;         // Rp*S: taps of one channel in a stage
+    int nstages;     // ceil(C / CB) * nr
+    int D;           // CB*Rp*S: reduction elements per stage
     int LDA;         // LDS pitch of a filter row: D + 1 (odd, so a column read has no bank conflict)
     int rows_full;   // patch rows one whole image contributes: (P-1)*prs + R
     int a_stage;     // floats reserved per LDS filter stage (BM*LDA rounded up to the workgroup size)
@@ -170,7 +176,8 @@ __device__ __forceinline__ void lds_dma(__amdgpu_buffer_rsrc_t rsrc, U *lds_dst,
 #endif
 }
 
-template <class E, class T, int MAXA, int MAXP, int RC, int SC>
+// ROWS: one filter row per stage (p.nr > 1); RC, SC then describe that row (RC = 1).
+template <class E, class T, int MAXA, int MAXP, int RC, int SC, bool ROWS = false>
 __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -198,11 +205,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const int img_b = nlast / p.PQ, p_b = (nlast - img_b * p.PQ) / p.Q;
     int nrows0, total_rows;
     if (img_a == img_b) {
-        nrows0 = (p_b - p_a) * p.prs + p.R;
+        nrows0 = (p_b - p_a) * p.prs + p.Rp;
         total_rows = nrows0;
     } else {
-        nrows0 = (p.P - 1 - p_a) * p.prs + p.R;
-        total_rows = nrows0 + (img_b - img_a - 1) * p.rows_full + p_b * p.prs + p.R;
+        nrows0 = (p.P - 1 - p_a) * p.prs + p.Rp;
+        total_rows = nrows0 + (img_b - img_a - 1) * p.rows_full + p_b * p.prs + p.Rp;
     }
     const int ihb0 = p_a * p.stride - p.pad;       // first input row held for the first image
     const int chs = total_rows * p.Wp;             // patch floats per channel
@@ -216,7 +223,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const int a_elems = T::BM * p.LDA;
 
     // ---- per-thread patch elements: LDS dword e <-> one input element or a zero -------------
+    // ROWS: the input row of an element moves down by one per filter-row stage, so whether it lies
+    // inside the image is decided per stage from p_row (its row for filter row 0; far below zero
+    // for an element that is never valid); p_goff then holds the signed offset for filter row 0.
     uint32_t p_goff[MAXP];
+    int p_row[ROWS ? MAXP : 1];
 #pragma unroll
     for (int i = 0; i < MAXP; ++i) {
         uint32_t e = (uint32_t)(tid + i * NT);
@@ -233,8 +244,14 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             ihb = -p.pad;
         }
         int ih = ihb + rr * p.irs, iw = col * p.ics - p.pad;
-        bool ok = ((int)e < patch_elems) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-        p_goff[i] = ok ? (uint32_t)(((ii * p.C + (int)c_l) * p.HW + ih * p.W + iw) * E::BYTES) : kOobOffset;
+        if constexpr (ROWS) {
+            const bool okc = ((int)e < patch_elems) && iw >= 0 && iw < p.W;
+            p_row[i] = okc ? ih : -0x40000000;
+            p_goff[i] = (uint32_t)(((ii * p.C + (int)c_l) * p.HW + ih * p.W + iw) * E::BYTES);
+        } else {
+            bool ok = ((int)e < patch_elems) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            p_goff[i] = ok ? (uint32_t)(((ii * p.C + (int)c_l) * p.HW + ih * p.W + iw) * E::BYTES) : kOobOffset;
+        }
     }
 
     // ---- per-thread filter elements: LDS dword e = m*LDA + kk <-> wt[m0+m][k0+kk] ------------
@@ -245,14 +262,19 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         uint32_t m = fdiv(e, p.magic_lda, 0u);
         int kk = (int)(e - m * (uint32_t)p.LDA);
         bool ok = (int)e < a_elems && m0 + (int)m < p.K && kk < p.D;
-        a_goff[i] = ok ? (uint32_t)(((int)m * p.Kg + kk) * E::BYTES) : kOobOffset;
+        int col = kk;
+        if constexpr (ROWS) {   // stage column kk = (channel, s) -> KCRS column channel*R*S + s (+ r*S per stage)
+            const int c_l = kk / p.S;
+            col = c_l * p.RS + (kk - c_l * p.S);
+        }
+        a_goff[i] = ok ? (uint32_t)(((int)m * p.Kg + col) * E::BYTES) : kOobOffset;
     }
 
     // ---- per-lane operand bases ---------------------------------------------------------------
     // filter operand: row wm0 + 32*bi + lane%32, column offset (lane/32)*RS selects the odd channel
     int a_base[MB];
 #pragma unroll
-    for (int bi = 0; bi < MB; ++bi) a_base[bi] = (wm0 + 32 * bi + li) * p.LDA + (p.single ? 0 : lh * p.RS);
+    for (int bi = 0; bi < MB; ++bi) a_base[bi] = (wm0 + 32 * bi + li) * p.LDA + (p.single ? 0 : lh * p.RSp);
     const int zero_unit = p.nbuf * p.b_stage;      // relative to Bs
     const int bmul = (p.single && lh) ? 0 : 1;
     if (tid == 0) {
@@ -291,10 +313,12 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
 
     auto load_stage = [&](int t, int buf) {
-        const int c0 = t * p.CB;
-        const int k0 = c0 * p.RS;
-        const int krem = p.Kg - k0;     // reduction elements that exist from k0 on
+        const int cblk = ROWS ? t / p.nr : t;
+        const int frow = ROWS ? t - cblk * p.nr : 0;     // filter row of this stage
+        const int c0 = cblk * p.CB;
+        const int k0 = c0 * p.RS + frow * p.S;
         const int crem = p.C - c0;      // channels that exist from c0 on
+        const int krem = crem * p.RSp;  // stage columns that exist
         const uint64_t a_skip = ((uint64_t)m0 * p.Kg + k0) * E::BYTES;
         __amdgpu_buffer_rsrc_t ra = make_rsrc(reinterpret_cast<const char *>(p.wt) + a_skip, p.wt_bytes - a_skip);
         unit_t *A = As + buf * a_stage + wave * 64;
@@ -316,7 +340,18 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         const uint64_t b_skip = ((uint64_t)img_a * p.C + c0) * p.HW * E::BYTES;
         __amdgpu_buffer_rsrc_t rb = make_rsrc(reinterpret_cast<const char *>(p.in) + b_skip, p.in_bytes - b_skip);
         unit_t *B = Bs + buf * p.b_stage + wave * 64;
-        if (crem >= p.CB) {
+        if constexpr (ROWS) {
+            const int shift = frow * p.W * E::BYTES;
+            const uint32_t magic_c = chs > 1 ? 0xFFFFFFFFu / (uint32_t)chs + 1u : 0u;
+            const uint32_t one_c = chs > 1 ? 0u : 0xFFFFFFFFu;
+#pragma unroll
+            for (int i = 0; i < MAXP; ++i)
+                if (i * NT < patch_elems) {
+                    bool ok = (uint32_t)(p_row[i] + frow) < (uint32_t)p.H;
+                    if (crem < p.CB) ok = ok && (int)fdiv((uint32_t)(tid + i * NT), magic_c, one_c) < crem;
+                    lds_dma<E::BYTES>(rb, B + i * NT, ok ? p_goff[i] + (uint32_t)shift : kOobOffset);
+                }
+        } else if (crem >= p.CB) {
 #pragma unroll
             for (int i = 0; i < MAXP; ++i)
                 if (i * NT < patch_elems) lds_dma<E::BYTES>(rb, B + i * NT, p_goff[i]);
@@ -356,7 +391,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
                 patch_pair<E, T, 1, 1>(A, B, a_base, b_base, cp * 2, cp * 2 * chs, 1, 1, p.Wp, acc, bmul);
         } else {
             for (int cp = 0; cp < npairs; ++cp)
-                patch_pair<E, T, RC, SC>(A, B, a_base, b_base, cp * 2 * p.RS, cp * 2 * chs, p.R, p.S, p.Wp, acc, bmul);
+                patch_pair<E, T, RC, SC>(A, B, a_base, b_base, cp * 2 * p.RSp, cp * 2 * chs, p.Rp, p.S, p.Wp, acc, bmul);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
@@ -459,7 +494,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 static constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // less the kernel's few static words
 
 // Input rows a run of bn consecutive output pixels can need at most (all images it touches).
-static int patch_rows_bound(const ConvProblem &q, int bn)
+static int patch_rows_bound(const ConvProblem &q, int bn, int Rp)
 {
     const long PQ = (long)q.P * q.Q, Ng = (long)q.N * PQ;
     long run = bn < Ng ? bn : Ng;
@@ -468,8 +503,8 @@ static int patch_rows_bound(const ConvProblem &q, int bn)
     long imgs = (run - 1 + PQ - 1) / PQ + 1;
     if (imgs > q.N) imgs = q.N;
     // an image with n output rows in the run holds (n-1)*prs + R patch rows
-    long prs = q.R == 1 ? 1 : q.stride;
-    long extra = q.R > prs ? q.R - prs : 0;
+    long prs = Rp == 1 ? 1 : q.stride;
+    long extra = Rp > prs ? Rp - prs : 0;
     long bound = rows_out * prs + imgs * extra;
     return (int)bound;
 }
@@ -488,17 +523,22 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     a.Kg = q.C * a.RS;
     a.Ng = q.N * a.PQ;
     a.Wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
-    a.prs = q.R == 1 ? 1 : q.stride; a.irs = q.R == 1 ? q.stride : 1;
+    // filters of five rows or more are staged one filter row at a time
+    const bool rows = q.R >= 5;
+    a.Rp = rows ? 1 : q.R;
+    a.nr = q.R / a.Rp;
+    a.RSp = a.Rp * q.S;
+    a.prs = a.Rp == 1 ? 1 : q.stride; a.irs = a.Rp == 1 ? q.stride : 1;
     a.pcs = q.S == 1 ? 1 : q.stride; a.ics = q.S == 1 ? q.stride : 1;
     // a reduction of one 16-byte unit runs unpaired instead of staging a second unit of zeros
     a.single = (E::BYTES == 16 && q.C == 1) ? 1 : 0;
     if (a.single) cb = 1;
     a.CB = cb;
-    a.nstages = (q.C + cb - 1) / cb;
-    a.D = cb * a.RS;
+    a.nstages = (q.C + cb - 1) / cb * a.nr;
+    a.D = cb * a.RSp;
     a.LDA = (a.D + 1) | 1;   // odd pitch (D is even unless single), at least 3
-    a.rows_full = (q.P - 1) * a.prs + q.R;
-    const int rows_alloc = patch_rows_bound(q, T::BN);
+    a.rows_full = (q.P - 1) * a.prs + a.Rp;
+    const int rows_alloc = patch_rows_bound(q, T::BN, a.Rp);
     a.a_stage = (T::BM * a.LDA + T::NT - 1) / T::NT * T::NT;
     a.b_stage = (cb * rows_alloc * a.Wp + T::NT - 1) / T::NT * T::NT;
     a.magic_Wp = div_magic((uint32_t)a.Wp); a.one_Wp = a.Wp == 1 ? 0xFFFFFFFFu : 0u;
@@ -545,7 +585,10 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     void (*kern)(ConvPatchKArgs) = conv_patch_kernel<E, T, MAXA, MAXP, 0, 0>;
     if (q.R == 1 && q.S == 1) kern = conv_patch_kernel<E, T, MAXA, MAXP, 1, 1>;
     else if (q.R == 3 && q.S == 3) kern = conv_patch_kernel<E, T, MAXA, MAXP, 3, 3>;
-    else if (q.R == 7 && q.S == 7) kern = conv_patch_kernel<E, T, MAXA, MAXP, 7, 7>;
+    if (rows) {
+        kern = conv_patch_kernel<E, T, MAXA, MAXP, 0, 0, true>;
+        if (q.S == 7) kern = conv_patch_kernel<E, T, MAXA, MAXP, 1, 7, true>;
+    }
     if (lds_bytes > 64 * 1024) {
         // more than the default per-workgroup LDS window has to be asked for, per kernel
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -212,14 +212,18 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
 }
 
 // ---- convolution ---------------------------------------------------------------------------------
+// filters of five rows or more are staged one filter row at a time by the patch kernel
+static int patch_rows_per_stage(const ConvProblem &q) { return q.R >= 5 ? 1 : q.R; }
+
 static double conv_patch_rows(const ConvProblem &q, int bn)
 {
+    const double Rp = patch_rows_per_stage(q);
     const double PQ = (double)q.P * q.Q, Ng = q.N * PQ;
     const double run = std::min<double>(bn, Ng);
     const double rows_out = std::min<double>(std::ceil((run - 1) / q.Q) + 1, (double)q.N * q.P);
     const double imgs = std::min<double>(std::ceil((run - 1) / PQ) + 1, q.N);
-    const double prs = q.R == 1 ? 1 : q.stride;
-    return rows_out * prs + imgs * std::max(0.0, q.R - prs);
+    const double prs = Rp == 1 ? 1 : q.stride;
+    return rows_out * prs + imgs * std::max(0.0, Rp - prs);
 }
 
 static Shape conv_shape(const ConvProblem &q, int algo, int bn, int cb)
@@ -235,7 +239,8 @@ static Shape conv_shape(const ConvProblem &q, int algo, int bn, int cb)
     s.d_bytes = (double)q.N * q.K * q.P * q.Q * 4;
     if (algo == 1) {
         const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
-        s.b_tile_bytes = q.C * conv_patch_rows(q, bn) * wp * 4;            // rows staged once per channel
+        // rows staged once per channel (once per channel and filter row when staged row by row)
+        s.b_tile_bytes = q.C * conv_patch_rows(q, bn) * wp * 4 * (q.R / patch_rows_per_stage(q));
     } else {
         s.b_tile_bytes = (double)bn * q.C * RS * 4;                        // every tap gathered again
     }
@@ -244,18 +249,18 @@ static Shape conv_shape(const ConvProblem &q, int algo, int bn, int cb)
 
 void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, int reg_class, polydl_model_report *r)
 {
-    const double RS = (double)q.R * q.S;
     Cand c;
     c.bm = cfg.bm; c.bn = cfg.bn; c.wm = cfg.wm; c.wn = cfg.wn; c.threads = threads;
     c.split_k = std::max(1, cfg.split_k);
     if (cfg.algo == 1) {
         const int cb = std::max(2, cfg.cb);
         const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
-        c.steps_per_stage = cb / 2.0 * RS;
+        const double RSp = (double)patch_rows_per_stage(q) * q.S;     // taps of a channel in one stage
+        c.steps_per_stage = cb / 2.0 * RSp;
         // two stage buffers, one when a workgroup's share of the reduction is a single stage
-        const int nstages = (q.C + cb - 1) / cb;
+        const int nstages = (q.C + cb - 1) / cb * (q.R / patch_rows_per_stage(q));
         const int per_split = (nstages + c.split_k - 1) / c.split_k;
-        c.lds_bytes = (per_split > 1 ? 2.0 : 1.0) * (cfg.bm * (cb * RS + 1) + cb * conv_patch_rows(q, cfg.bn) * wp) * 4;
+        c.lds_bytes = (per_split > 1 ? 2.0 : 1.0) * (cfg.bm * (cb * RSp + 1) + cb * conv_patch_rows(q, cfg.bn) * wp) * 4;
         c.split_in_scratch = true;
         c.loop_eff = 0.74;
         c.wg_overhead_cycles = 9000;
@@ -317,11 +322,12 @@ double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int thr
     const double mb = cfg.wm / 32.0, nb = cfg.wn / 32.0, waves_per_wg = threads / 64.0;
     const double Ng = (double)q.N * q.P * q.Q;
     const double tiles = std::ceil((double)q.K / cfg.bm) * std::ceil(Ng / cfg.bn);
-    const double nstages = std::ceil((double)q.C / cb);
+    const double RSp = (double)patch_rows_per_stage(q) * q.S;
+    const double nstages = std::ceil((double)q.C / cb) * (q.R / patch_rows_per_stage(q));
     const double per_split = std::ceil(nstages / std::max(1, cfg.split_k));
     const double parts = std::ceil(nstages / per_split);
     const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
-    const double stage_units = cfg.bm * (cb * RS + 1) + cb * conv_patch_rows(q, cfg.bn) * wp;
+    const double stage_units = cfg.bm * (cb * RSp + 1) + cb * conv_patch_rows(q, cfg.bn) * wp;
     const double lds_bytes = (per_split > 1 ? 2.0 : 1.0) * stage_units * 16;
     const int waves_per_simd = mb * nb == 1 ? 6 : (mb * nb == 2 ? 4 : 2);
     const double occ = std::max(1.0, std::min(std::floor(waves_per_simd * kSimdsPerCU / waves_per_wg),
@@ -331,9 +337,9 @@ double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int thr
     double eff = 0.3, t_round = 6.0, t_lat = 0.8, rate = 60000.0, c1 = 0.1;
     if (mb * nb == 2) { eff = 0.4; t_round = 8.0; c1 = 0.2; }
     else if (mb * nb == 4) { t_lat = 0.4; rate = 31000.0; c1 = 0.4; }
-    const double t_stage = std::max(std::ceil(cb / 2.0) * RS * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
+    const double t_stage = std::max(std::ceil(cb / 2.0) * RSp * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
                                         kClockHz * 1e6 / eff,
-                                    (cfg.bm * cb * RS + cb * conv_patch_rows(q, cfg.bn) * wp) * 16.0 / rate);
+                                    (cfg.bm * cb * RSp + cb * conv_patch_rows(q, cfg.bn) * wp) * 16.0 / rate);
     const double per_cu = tiles * parts / kCUs;
     const double full_rounds = std::floor(per_cu / occ), rest = per_cu - full_rounds * occ;
     auto round_us = [&](double n) { return t_round + per_split * std::max(n * t_stage, t_lat); };

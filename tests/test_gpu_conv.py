@@ -186,6 +186,38 @@ def test_split_reduction_in_patch_kernel_is_reproducible(P):
     P.set_tile_override(None)
 
 
+ROW_STAGED = [
+    synth.ConvShape("rows5", 3, 10, 12, 12, 40, 5, 5, 1, 2),        # channel tail, runs crossing images
+    synth.ConvShape("rows7s2", 2, 6, 32, 32, 70, 7, 7, 2, 3),       # 16x16 outputs: tiles inside one image
+    synth.ConvShape("rows5x3", 1, 7, 15, 9, 33, 5, 3, 1, 1),        # R != S, pad < (R-1)/2: rows fall off both edges
+    synth.ConvShape("rows9", 2, 4, 20, 20, 16, 9, 9, 1, 4),         # filter size without an unrolled instantiation
+]
+
+
+@pytest.mark.parametrize("s", ROW_STAGED, ids=lambda s: s.name)
+def test_filter_row_staging(P, s):
+    # filters of five rows or more: a stage of the patch kernel holds one filter row of its channels
+    x, w, b = synth.conv_inputs(s, seed=39, dist="normal", bias=True)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+    xi, wi, bi = synth.conv_inputs(s, seed=40, dist="ints", bias=True)
+    want_i, _ = oracle.conv2d_fwd(xi, wi, bias=bi, stride=s.stride, pad=s.pad)
+    ran = 0
+    for v in P.variants(0):
+        if v.algo != 1:
+            continue
+        for cb, split_k in ((2, 1), (4, 1), (2, 5), (4, 2)):
+            v.cb, v.split_k = cb, split_k
+            got = try_variant(P, v, s, x, w, b, act="relu")
+            if got is None:
+                continue
+            assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (v, cb, split_k)
+            got_i = try_variant(P, v, s, xi, wi, bi)
+            assert np.array_equal(got_i.astype(np.float64), want_i), (v, cb, split_k)
+            ran += 1
+    assert ran > 0
+    P.set_tile_override(None)
+
+
 def test_argument_errors(P):
     import ctypes
     z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
