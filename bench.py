@@ -320,6 +320,35 @@ def main():
                             "frac": round(nbytes / (t_fused * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
                   layers=bn_rows)
 
+    # the blocked-layout transforms (pure permutations, memory bound): activations NCHW -> NCHW16c
+    # and back, filters KCRS -> KCRS16c16k, on the tensors of the suite layers
+    lay = None
+    if not args.no_fusion and forced is None and len(chosen) == 8:
+        lay_rows, t_all, b_all = [], 0.0, 0.0
+        for L in layers:
+            s = L["shape"]
+            xb = P.nchw_to_nchwc(L["x"], 16)
+            xr = torch.empty_like(L["x"])
+            wb = P.kcrs_to_kcrsck(L["w"], 16, 16)
+            t_fw = time_calls(torch, lambda: P.nchw_to_nchwc(L["x"], 16, out=xb), 20, batches=3)
+            t_bw = time_calls(torch, lambda: P.nchwc_to_nchw(xb, s.C, out=xr), 20, batches=3)
+            t_w = time_calls(torch, lambda: P.kcrs_to_kcrsck(L["w"], 16, 16, out=wb), 20, batches=3)
+            # bytes moved: the source once and the (zero-padded) blocked tensor once
+            b_act = 4.0 * (L["x"].numel() + xb.numel())
+            lay_rows.append(dict(layer=L["index"], act_to_blocked_us=round(t_fw * 1e3, 2),
+                                 act_to_blocked_gbs=round(b_act / (t_fw * 1e-3) / 1e9, 1),
+                                 act_from_blocked_us=round(t_bw * 1e3, 2),
+                                 act_from_blocked_gbs=round(b_act / (t_bw * 1e-3) / 1e9, 1),
+                                 filter_pack_us=round(t_w * 1e3, 2)))
+            t_all += t_fw
+            b_all += b_act
+            del xb, xr, wb
+        lay = dict(workload="NCHW <-> NCHW16c on the suite inputs (N=%d), KCRS -> KCRS16c16k on its filters; "
+                            "back-to-back launches into preallocated tensors" % args.batch,
+                   roofline={"bound": "hbm", "achieved": round(b_all / (t_all * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(b_all / (t_all * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+                   layers=lay_rows)
+
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -363,6 +392,7 @@ def main():
         "bf16": bf,
         "fusion": fusion,
         "bnorm_relu": bn,
+        "layouts": lay,
         "event_ms_per_step": round(e0.elapsed_time(e1) / args.steps, 4),
     }
     if args.sweep and args.sweep_out:

@@ -216,31 +216,34 @@ def sgemm(A, B, C, stream=None):
     return C
 
 
-def nchw_to_nchwc(x, b, stream=None):
-    """polydl_nchw_to_nchwc: returns the [N][ceil(C/b)][H][W][b] tensor."""
+def nchw_to_nchwc(x, b, stream=None, out=None):
+    """polydl_nchw_to_nchwc: returns the [N][ceil(C/b)][H][W][b] tensor (written into out if given)."""
     import torch
     N, C, H, W = x.shape
-    out = torch.empty((N, -(-C // b), H, W, b), dtype=torch.float32, device=x.device)
+    if out is None:
+        out = torch.empty((N, -(-C // b), H, W, b), dtype=torch.float32, device=x.device)
     _check(lib.polydl_nchw_to_nchwc(N, C, H, W, b, _dev(x, "x"), _dev(out, "out"), _stream_ptr(stream)),
            "polydl_nchw_to_nchwc")
     return out
 
 
-def nchwc_to_nchw(xb, C, stream=None):
-    """polydl_nchwc_to_nchw: returns the [N][C][H][W] tensor."""
+def nchwc_to_nchw(xb, C, stream=None, out=None):
+    """polydl_nchwc_to_nchw: returns the [N][C][H][W] tensor (written into out if given)."""
     import torch
     N, Cb, H, W, b = xb.shape
-    out = torch.empty((N, C, H, W), dtype=torch.float32, device=xb.device)
+    if out is None:
+        out = torch.empty((N, C, H, W), dtype=torch.float32, device=xb.device)
     _check(lib.polydl_nchwc_to_nchw(N, C, H, W, b, _dev(xb, "xb"), _dev(out, "out"), _stream_ptr(stream)),
            "polydl_nchwc_to_nchw")
     return out
 
 
-def kcrs_to_kcrsck(w, bc, bk, stream=None):
-    """polydl_kcrs_to_kcrsck: returns the [ceil(K/bk)][ceil(C/bc)][R][S][bc][bk] tensor."""
+def kcrs_to_kcrsck(w, bc, bk, stream=None, out=None):
+    """polydl_kcrs_to_kcrsck: returns the [ceil(K/bk)][ceil(C/bc)][R][S][bc][bk] tensor (out if given)."""
     import torch
     K, C, R, S = w.shape
-    out = torch.empty((-(-K // bk), -(-C // bc), R, S, bc, bk), dtype=torch.float32, device=w.device)
+    if out is None:
+        out = torch.empty((-(-K // bk), -(-C // bc), R, S, bc, bk), dtype=torch.float32, device=w.device)
     _check(lib.polydl_kcrs_to_kcrsck(K, C, R, S, bc, bk, _dev(w, "w"), _dev(out, "out"), _stream_ptr(stream)),
            "polydl_kcrs_to_kcrsck")
     return out
