@@ -51,8 +51,12 @@ def conv_bytes(s, P, Q):
 def time_calls(torch, fn, reps, batches=3):
     """Median over batches of the mean time (ms) of reps back-to-back calls between two events."""
     out = []
-    for _ in range(max(2, reps // 4)):   # clocks and caches as in steady state
-        fn()
+    # clocks and caches as in steady state: keep the GPU busy with the same call for about 30 ms
+    t_warm = time.perf_counter()
+    while time.perf_counter() - t_warm < 0.03:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
     for _ in range(batches):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()

@@ -369,9 +369,8 @@ void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads,
     c.kernel_fixed_us = 6.0;
     c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 1 : ((cfg.wm * cfg.wn == 64 * 64) ? 2 : 4);
     model(s, c, r);
-    if (cfg.split_k > 1) {   // C accumulates in place: atomics, but no fill and no bias pass around the kernel
-        r->fixed_us = c.kernel_fixed_us +
-                      cfg.split_k * (double)q.M * q.N * 4 / (cfg.wn > 32 ? kAtomicGBs : 6.0 * kAtomicGBs) * 1e-3;
+    if (cfg.split_k > 1) {   // every part writes its tile to scratch once, the last one reads them all back
+        r->fixed_us = c.kernel_fixed_us + 2.0 * cfg.split_k * (double)q.M * q.N * 4 / kHbmGBs * 1e-3;
         r->predicted_us = std::max(r->mfma_us, r->mem_us) + r->fixed_us;
     }
 }

@@ -13,6 +13,8 @@ struct SgemmKArgs {
     int tiles_m, tiles_n;
     int split_k, k_per_split;  // k_per_split is a multiple of the stage depth
     int raster;
+    float *partials;           // split_k > 1: [tile][part][BM*BN] accumulator tiles in register order
+    unsigned *counters;        // split_k > 1: per tile, how many of its reduction parts have finished
 };
 
 // AVEC / BVEC: 4 when the operand allows 128-bit loads, else 1.  CVEC: the lane's NB adjacent
@@ -44,10 +46,52 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
 
     if (kbegin < kend) gemm_mainloop<T>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
 
-    // epilogue: C += acc.  With the reduction split over blockIdx.y the parts meet in C through
-    // float atomics (C already holds the caller's values, so no zero fill is needed).
+    // With the reduction split over blockIdx.y every part leaves its accumulator tile in scratch
+    // memory (thread-contiguous, device-scope stores); the part that arrives last adds all parts
+    // in index order and alone updates C, so the result does not depend on the order of arrival.
+    // Nothing waits on another workgroup.
+    if (p.split_k > 1) {
+        __shared__ unsigned s_arrived;
+        constexpr size_t TILE = (size_t)T::BM * T::BN;
+        constexpr int NT = T::NT;
+        float *tile0 = p.partials + (size_t)blockIdx.x * p.split_k * TILE;
+        float *mine = tile0 + (size_t)blockIdx.y * TILE;
+#pragma unroll
+        for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __hip_atomic_store(mine + ((bi * T::NB + bj) * 16 + r) * NT + tid, acc[bi][bj][r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's device-scope stores have completed
+        __syncthreads();
+        if (tid == 0)
+            s_arrived = __hip_atomic_fetch_add(p.counters + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (__builtin_amdgcn_readfirstlane(s_arrived) != (unsigned)p.split_k - 1u) return;   // not the last part
+        if (tid == 0)               // leave the counter at zero for the next launch
+            __hip_atomic_store(p.counters + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+        for (int sp = 0; sp < p.split_k; ++sp) {
+            const float *part = tile0 + (size_t)sp * TILE;
+#pragma unroll
+            for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[bi][bj][r] += __hip_atomic_load(part + ((bi * T::NB + bj) * 16 + r) * NT + tid,
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    // epilogue: C += acc
     const int col = n0 + wn0 + T::NB * (lane & 31);
-    const bool atomic = p.split_k > 1;
 #pragma unroll
     for (int bi = 0; bi < T::MB; ++bi)
 #pragma unroll
@@ -55,11 +99,7 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
             int row = m0 + acc_row(wm0, bi, r, lane);
             if (row >= p.M) continue;
             float *c = p.C + (size_t)row * p.N + col;
-            if (atomic) {
-#pragma unroll
-                for (int bj = 0; bj < T::NB; ++bj)
-                    if (col + bj < p.N) unsafeAtomicAdd(c + bj, acc[bi][bj][r]);
-            } else if (CVEC && T::NB == 4) {
+            if (CVEC && T::NB == 4) {
                 if (col < p.N) {
                     v4f v = *reinterpret_cast<v4f *>(c);
                     v.x += acc[bi][0][r]; v.y += acc[bi][1][r]; v.z += acc[bi][2][r]; v.w += acc[bi][3][r];
@@ -96,7 +136,14 @@ static hipError_t sgemm_launch(const SgemmProblem &q, int split_k, int raster, h
     split_k = stages > 0 ? (stages + stages_per - 1) / stages_per : 1;
     a.split_k = split_k;
     a.raster = raster;
+    a.partials = nullptr;
+    a.counters = nullptr;
     clear_stale_hip_error();
+    if (split_k > 1) {
+        const size_t bytes = (size_t)a.tiles_m * a.tiles_n * split_k * T::BM * T::BN * sizeof(float);
+        hipError_t e = splitk_scratch(stream, bytes, a.tiles_m * a.tiles_n, &a.partials, &a.counters);
+        if (e != hipSuccess) return e;
+    }
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k), block(T::NT);
     const bool avec = (q.K % 4 == 0) && ((uintptr_t)q.A % 16 == 0);
     const bool bvec = (q.N % 4 == 0) && ((uintptr_t)q.B % 16 == 0);

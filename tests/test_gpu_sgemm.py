@@ -126,6 +126,21 @@ def test_paper_gemm_sizes_sampled(P, M, N, K):
     assert oracle.scaled_error(got.ravel()[idx], want, ab) <= FP32_TOL
 
 
+def test_split_reduction_is_reproducible(P):
+    # the parts of a split reduction are summed in index order whatever order they finish in
+    A, B, C0 = synth.sgemm_inputs(300, 200, 1000, seed=11, c0="random")
+    want, ab = oracle.gemm(A, B, C0)
+    for v in P.variants(1):
+        for split_k in (2, 7):
+            v.split_k = split_k
+            P.set_tile_override(v)
+            first = run_sgemm(P, A, B, C0)
+            assert oracle.scaled_error(first, want, ab) <= FP32_TOL, v
+            for _ in range(2):
+                assert np.array_equal(run_sgemm(P, A, B, C0), first), v
+    P.set_tile_override(None)
+
+
 def test_argument_errors(P):
     import ctypes
     z = ctypes.c_void_p(0)
