@@ -16,7 +16,7 @@
  *   - the return value is POLYDL_OK (0) or a negative polydl_status; on an argument error
  *     nothing is enqueued and no output byte is written;
  *   - tensors are dense, contiguous float32 unless stated; input and output must not overlap;
- *   - memory of its own: a convolution (algo 1) or matrix product whose reduction is split over
+ *   - memory of its own: a convolution or matrix product whose reduction is split over
  *     several workgroups (split_k > 1) keeps partial tiles and arrival counters in a
  *     device buffer the library allocates with hipMalloc on first need, one per (device, stream),
  *     grows on demand and keeps until the process ends; growing it waits for the device.  Calls
@@ -74,9 +74,8 @@ typedef struct polydl_tile_cfg {
  *   in   N*C*H*W floats, NCHW.      wt  K*C*R*S floats, KCRS.
  *   bias K floats or NULL (= none). out N*K*P*Q floats, NKPQ, overwritten.
  *   fuse_relu: 0 = no activation, 1 = ReLU.  (polydl_conv2d_fwd_act takes any polydl_act.)
- * Accumulation is float32 on the matrix cores; the summation order is unspecified (fixed for a
- * given tile configuration of algo 1, so repeated calls agree bit for bit; algo 0 with
- * split_k > 1 adds its parts with float atomics in arrival order). */
+ * Accumulation is float32 on the matrix cores; the summation order is unspecified but fixed for
+ * a given tile configuration, so repeated calls agree bit for bit. */
 int polydl_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                       const float *in, const float *wt, const float *bias, float *out,
                       int fuse_relu, void *stream);

@@ -26,6 +26,8 @@ struct ConvKArgs {
     int tiles_m, tiles_n;
     int split_k, k_per_split;
     int raster, act;
+    float *partials;            // split_k > 1: [tile][part][BM*BN] accumulator tiles in register order
+    unsigned *counters;         // split_k > 1: per tile, how many of its reduction parts have finished
 };
 
 // ---- B operand: on-the-fly im2col gather from NCHW --------------------------------------------
@@ -136,12 +138,55 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
 
     gemm_mainloop<T>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
 
+    // With the reduction split over blockIdx.y every part leaves its accumulator tile in scratch
+    // memory (thread-contiguous, device-scope stores); the part that arrives last adds all parts
+    // in index order and runs the fused epilogue.  Nothing waits on another workgroup.
+    if (p.split_k > 1) {
+        __shared__ unsigned s_arrived;
+        constexpr size_t TILE = (size_t)T::BM * T::BN;
+        constexpr int NT = T::NT;
+        float *tile0 = p.partials + (size_t)blockIdx.x * p.split_k * TILE;
+        float *mine = tile0 + (size_t)blockIdx.y * TILE;
+#pragma unroll
+        for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __hip_atomic_store(mine + ((bi * T::NB + bj) * 16 + r) * NT + tid, acc[bi][bj][r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's device-scope stores have completed
+        __syncthreads();
+        if (tid == 0)
+            s_arrived = __hip_atomic_fetch_add(p.counters + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (__builtin_amdgcn_readfirstlane(s_arrived) != (unsigned)p.split_k - 1u) return;   // not the last part
+        if (tid == 0)               // leave the counter at zero for the next launch
+            __hip_atomic_store(p.counters + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+        for (int sp = 0; sp < p.split_k; ++sp) {
+            const float *part = tile0 + (size_t)sp * TILE;
+#pragma unroll
+            for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[bi][bj][r] += __hip_atomic_load(part + ((bi * T::NB + bj) * 16 + r) * NT + tid,
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     // epilogue.  The lane owns NB adjacent pixels starting at colg for 16*MB output channels.
     const int colg = n0 + wn0 + T::NB * (lane & 31);
     if (colg >= p.Ng) return;
     const int img = colg / p.PQ, pq = colg - img * p.PQ;
     // the NB pixels are one vector store when they lie in one image and keep the alignment
-    const bool vec = (p.PQ % T::NB == 0) && (((uintptr_t)p.out & 15) == 0) && p.split_k == 1;
+    const bool vec = (p.PQ % T::NB == 0) && (((uintptr_t)p.out & 15) == 0);
 #pragma unroll
     for (int bi = 0; bi < T::MB; ++bi)
 #pragma unroll
@@ -150,17 +195,7 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
             if (k >= p.K) continue;
             const float b = p.bias ? p.bias[k] : 0.f;
             float *o = p.out + ((size_t)img * p.K + k) * p.PQ + pq;
-            if (p.split_k > 1) {
-                // partial sums meet in a zero-filled output; bias and activation follow in a
-                // separate pass over the output
-#pragma unroll
-                for (int bj = 0; bj < T::NB; ++bj) {
-                    int cg = colg + bj;
-                    if (cg >= p.Ng) break;
-                    int im = cg / p.PQ, q = cg - im * p.PQ;
-                    unsafeAtomicAdd(p.out + ((size_t)im * p.K + k) * p.PQ + q, acc[bi][bj][r]);
-                }
-            } else if (vec) {
+            if (vec) {
                 if constexpr (T::NB == 4) {
                     v4f v = {apply_act(acc[bi][0][r] + b, p.act), apply_act(acc[bi][1][r] + b, p.act),
                              apply_act(acc[bi][2][r] + b, p.act), apply_act(acc[bi][3][r] + b, p.act)};
@@ -209,15 +244,18 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     a.split_k = (stages + stages_per - 1) / stages_per;
     a.raster = raster;
     a.act = q.act;
+    a.partials = nullptr;
+    a.counters = nullptr;
     clear_stale_hip_error();
-    const size_t nout = (size_t)q.N * q.K * a.PQ;
-    if (a.split_k > 1 && launch_fill_zero(q.out, nout, stream) != hipSuccess) return hipGetLastError();
+    if (a.split_k > 1) {
+        const size_t bytes = (size_t)a.tiles_m * a.tiles_n * a.split_k * T::BM * T::BN * sizeof(float);
+        hipError_t e = splitk_scratch(stream, bytes, a.tiles_m * a.tiles_n, &a.partials, &a.counters);
+        if (e != hipSuccess) return e;
+    }
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
     if (avec) hipLaunchKernelGGL((conv_kernel<T, 4>), grid, block, 0, stream, a);
     else hipLaunchKernelGGL((conv_kernel<T, 1>), grid, block, 0, stream, a);
-    if (a.split_k > 1 && (q.bias || q.act != POLYDL_ACT_NONE))
-        return launch_bias_act(q.out, q.bias, q.K, a.PQ, nout, q.act, stream);
     return hipGetLastError();
 }
 

@@ -65,8 +65,6 @@ hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t to
 hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
 hipError_t launch_bnorm_act(const float *x, float *y, const float *gamma, const float *beta, const float *mean,
                             const float *var, float eps, int K, int PQ, size_t total, int act, hipStream_t st);
-hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st);
-hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n, int act, hipStream_t st);
 
 // scratch.cpp: partial-tile buffer (>= partial_bytes) and zeroed arrival counters (>= tiles) for
 // split-reduction launches on this device and stream

@@ -148,40 +148,6 @@ hipError_t launch_bnorm_act(const float *x, float *y, const float *gamma, const 
     return hipGetLastError();
 }
 
-// Zero fill before a split reduction and the bias + activation pass after it (kernels rather than
-// memset nodes, so a captured graph replays them faithfully).
-__global__ void fill_zero_kernel(float *p, size_t n)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += step) p[i] = 0.f;
-}
-__global__ void bias_act_kernel(float *y, const float *bias, int K, int PQ, size_t n, int act)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += step) {
-        float v = y[i] + (bias ? bias[(i / PQ) % K] : 0.f);
-        if (act != POLYDL_ACT_NONE) v = fmaxf(v, 0.f);
-        if (act == POLYDL_ACT_RELU6) v = fminf(v, 6.f);
-        y[i] = v;
-    }
-}
-
-hipError_t launch_fill_zero(float *y, size_t n, hipStream_t st)
-{
-    clear_stale_hip_error();
-    unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, y, n);
-    return hipGetLastError();
-}
-
-hipError_t launch_bias_act(float *y, const float *bias, int K, int PQ, size_t n, int act, hipStream_t st)
-{
-    clear_stale_hip_error();
-    unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    hipLaunchKernelGGL(bias_act_kernel, dim3(blocks), dim3(256), 0, st, y, bias, K, PQ, n, act);
-    return hipGetLastError();
-}
-
 // elem_bytes: 4 (float) or 2 (bfloat16 bit patterns; a permutation does not look at the values)
 hipError_t launch_nchwc(const void *src, void *dst, int N, int C, int HW, int b, bool to_blocked, int elem_bytes,
                         hipStream_t st)

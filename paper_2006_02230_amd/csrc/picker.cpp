@@ -40,11 +40,8 @@ static const Level kLevels[4] = {
     {"mall", 256.0 * 1024 * 1024, 8000.0},  // Infinity Cache
 };
 static const double kHbmGBs = 4500.0;       // sustained mixed read/write HBM rate
-static const double kAtomicGBs = 450.0;     // float atomic adds into L2 when a lane owns adjacent columns (stride-2
-                                            // or stride-4 lanes per instruction); contiguous lanes run about 6x faster
 static const double kClockHz = 2.4e9;
 static const int kCUs = 256, kSimdsPerCU = 4, kXcds = 8;
-static const double kLaunchUs = 2.5;        // one kernel launch inside a stream
 
 void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem)
 {
@@ -94,7 +91,6 @@ struct Cand {
     double wg_overhead_cycles;   // cycles a wave spends outside the reduction loop (setup, first loads, stores)
     double kernel_fixed_us;      // launch, first-stage latency and the store tail that nothing overlaps
     int max_waves_per_simd;
-    bool split_in_scratch = false;   // reduction parts meet in scratch tiles (fused epilogue), not through atomics
     // Convolution kernels are timed round by round (see model()): workgroups that are resident
     // together start, load and store in step, so each round pays its own latency.
     bool rounds = false;
@@ -192,16 +188,10 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
         // nothing streams the tensors faster than this, with the first and last touches exposed
         mem_us = std::max(mem_us, (s.a_bytes + s.b_bytes + s.d_bytes) / 4000.0 * 1e-3 + 3.0);
         if (c.split_k > 1) fixed += c.split_c0 + c.split_c1 * c.split_k * s.d_bytes * 1e-6;
-    } else if (c.split_k > 1 && c.split_in_scratch) {
-        // every part writes its accumulator tile once, coalesced; the last part of each tile reads
-        // them all back and runs the fused epilogue: no other launch, no pass over the output
-        fixed += 2.0 * c.split_k * s.d_bytes / kHbmGBs * 1e-3;
     } else if (c.split_k > 1) {
-        // every part adds its tile to the output with atomics; a zero fill before and a bias /
-        // activation pass after, each a launch and a sweep over the output
-        // the atomic adds run in the epilogues, after the matrix-core work, so they add to it
-        fixed += c.split_k * s.d_bytes / (nb > 1 ? kAtomicGBs : 6.0 * kAtomicGBs) * 1e-3;
-        fixed += 2 * kLaunchUs + 3.0 * s.d_bytes / kHbmGBs * 1e-3;
+        // every part writes its accumulator tile once, coalesced; the last part of each tile reads
+        // them all back and runs the epilogue: no other launch, no pass over the output
+        fixed += 2.0 * c.split_k * s.d_bytes / kHbmGBs * 1e-3;
     }
     r->mfma_us = mfma_us;
     r->mem_us = mem_us;
@@ -261,7 +251,6 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         const int nstages = (q.C + cb - 1) / cb * (q.R / patch_rows_per_stage(q));
         const int per_split = (nstages + c.split_k - 1) / c.split_k;
         c.lds_bytes = (per_split > 1 ? 2.0 : 1.0) * (cfg.bm * (cb * RSp + 1) + cb * conv_patch_rows(q, cfg.bn) * wp) * 4;
-        c.split_in_scratch = true;
         c.loop_eff = 0.74;
         c.wg_overhead_cycles = 9000;
         c.kernel_fixed_us = 14.0;
@@ -297,14 +286,15 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         c.kernel_fixed_us = 5.0;
         c.gather_elems = (double)cfg.bk * cfg.bn / threads;
         switch (mbn) {
-        case 11: c.regs = 70;  c.eff_sat = 0.70; c.t_lat_us = 0.6; c.t_round_us = 6;  c.gather_cycles = 40; c.split_c0 = 0;  c.split_c1 = 0.2;  break;
-        case 12: c.regs = 110; c.eff_sat = 0.65; c.t_lat_us = 1.0; c.t_round_us = 6;  c.gather_cycles = 20; c.split_c0 = 10; c.split_c1 = 0.45; break;
-        case 21: c.regs = 95;  c.eff_sat = 0.70; c.t_lat_us = 0.8; c.t_round_us = 8;  c.gather_cycles = 0;  c.split_c0 = 6;  c.split_c1 = 0.3;  break;
-        case 22: c.regs = cfg.bk == 16 ? 150 : 115; c.eff_sat = 0.60; c.t_lat_us = 0.8; c.t_round_us = 6; c.gather_cycles = 0; c.split_c0 = 15; c.split_c1 = 0.6; break;
-        case 24: c.regs = 215; c.eff_sat = 0.65; c.t_lat_us = 0.4; c.t_round_us = 10; c.gather_cycles = 20;  c.split_c0 = 15; c.split_c1 = 1.0; break;
-        default: c.regs = 240; c.eff_sat = 0.90; c.t_lat_us = 0.4; c.t_round_us = 16; c.gather_cycles = 160; c.split_c0 = 15; c.split_c1 = 1.0; break;
+        case 11: c.regs = 70;  c.eff_sat = 0.70; c.t_lat_us = 0.6; c.t_round_us = 6;  c.gather_cycles = 40; break;
+        case 12: c.regs = 110; c.eff_sat = 0.65; c.t_lat_us = 1.0; c.t_round_us = 6;  c.gather_cycles = 20; break;
+        case 21: c.regs = 95;  c.eff_sat = 0.70; c.t_lat_us = 0.8; c.t_round_us = 8;  c.gather_cycles = 0;  break;
+        case 22: c.regs = cfg.bk == 16 ? 150 : 115; c.eff_sat = 0.60; c.t_lat_us = 0.8; c.t_round_us = 6; c.gather_cycles = 0; break;
+        case 24: c.regs = 215; c.eff_sat = 0.65; c.t_lat_us = 0.4; c.t_round_us = 10; c.gather_cycles = 20;  break;
+        default: c.regs = 240; c.eff_sat = 0.90; c.t_lat_us = 0.4; c.t_round_us = 16; c.gather_cycles = 160; break;
         }
         if (contiguous) c.gather_cycles *= 0.3;
+        c.split_c0 = 0; c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
     }
     Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
     model(s, c, r);

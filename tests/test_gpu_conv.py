@@ -151,9 +151,9 @@ def test_split_k_random(P):
         v.split_k = 4
         got = try_variant(P, v, s, x, w, b)
         assert got is not None and oracle.scaled_error(got, want, ab) <= FP32_TOL, v
-        if v.algo == 1:   # the patch kernel applies bias and activation after the split reduction
-            got = try_variant(P, v, s, x, w, b, act="relu")
-            assert oracle.scaled_error(got, want_r, ab_r) <= FP32_TOL, v
+        got = try_variant(P, v, s, x, w, b, act="relu")
+        assert oracle.scaled_error(got, want_r, ab_r) <= FP32_TOL, v
+        assert np.array_equal(try_variant(P, v, s, x, w, b, act="relu"), got), v   # fixed summation order
     P.set_tile_override(None)
 
 
