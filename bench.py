@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "b388c67db2329e542346c6a62b5856ca10180651408c11885c2918cf4a18dcc5", "batch": 32, "fetch_bytes": 685337316, "write_bytes": 358308536}
+HBM_TRAFFIC = {"csrc_sha256": "0f70b9484b2f13afb2f5bd2c9929d6ac70fba8b01d4080dc731414363bbdc156", "batch": 32, "fetch_bytes": 717657453, "write_bytes": 429605768}
 
 
 def csrc_digest():
