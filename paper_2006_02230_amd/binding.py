@@ -339,7 +339,7 @@ def conv_candidates(shape):
         else:
             stages = -(-(C * R * S) // v.bk)
             for sk in splits:
-                if sk > stages or sk > 8:
+                if sk > stages:
                     break
                 out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0))
     return out

@@ -392,7 +392,7 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
         const Variant &v = kVariants[i];
         const long stages = (Kg + v.bk - 1) / v.bk;
         for (int sk : kSplits) {
-            if (sk > stages || sk > 8) break;
+            if (sk > stages) break;
             polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0};
             model_conv(q, c, v.threads, 0, &rep);
             if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
