@@ -94,6 +94,30 @@ def test_model_monotonic_in_batch():
     assert t == sorted(t) and t[-1] > t[0]
 
 
+def test_rounds_of_resident_workgroups_show_in_the_prediction():
+    # 64x64 tiles of the patch kernel on a 64 -> 64 channel 3x3 layer: 49 tiles per image.  The model
+    # times the grid in rounds of the workgroups a CU holds at once, so the prediction grows with the
+    # batch in steps, never decreases, and a batch that just overflows a round costs visibly more
+    # than one that just fills it
+    cfg = P.TileCfg(64, 64, 0, 32, 32, 1, 0, 0, 1, 4)
+    t = [P.model_conv2d((n, 64, 56, 56, 64, 3, 3, 1, 1), cfg).predicted_us for n in range(1, 64)]
+    assert all(b >= a - 1e-9 for a, b in zip(t, t[1:]))
+    steps = [b - a for a, b in zip(t, t[1:])]
+    assert max(steps) > 4 * (t[-1] - t[0]) / len(steps)        # some step is a whole round's latency
+    # splitting the reduction over more workgroups than fit at once cannot be predicted free
+    base = P.model_conv2d((32, 256, 14, 14, 256, 3, 3, 1, 1), P.TileCfg(64, 64, 0, 32, 32, 1, 0, 0, 1, 4))
+    many = P.model_conv2d((32, 256, 14, 14, 256, 3, 3, 1, 1), P.TileCfg(64, 64, 0, 32, 32, 16, 0, 0, 1, 4))
+    assert many.fixed_us > base.fixed_us
+
+
+def test_filter_row_staging_in_the_model():
+    # a 7x7 filter is staged one filter row at a time: its LDS stage (second working set) does not
+    # hold all 49 taps of its channels
+    rep7 = P.model_conv2d((8, 16, 32, 32, 64, 7, 7, 1, 3), P.TileCfg(64, 64, 0, 32, 32, 1, 0, 0, 1, 4))
+    rep3 = P.model_conv2d((8, 16, 32, 32, 64, 3, 3, 1, 1), P.TileCfg(64, 64, 0, 32, 32, 1, 0, 0, 1, 4))
+    assert rep7.ws[1] < rep3.ws[1] * 49 / 9
+
+
 def test_sgemm_pick_valid():
     for n in synth.SGEMM_SIZES:
         cfg, rep = P.pick_sgemm(n, n, n)
