@@ -25,7 +25,10 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "0f70b9484b2f13afb2f5bd2c9929d6ac70fba8b01d4080dc731414363bbdc156", "batch": 32, "fetch_bytes": 717657453, "write_bytes": 429605768}
+HBM_TRAFFIC = {"csrc_sha256": "c4dd32ca342413b32abc01a7ac633fb51ba812896180835942c71bf6788c5ee8", "batch": 32, "fetch_bytes": 755746881, "write_bytes": 449133584}
+
+
+COLD_ROTATION_BYTES = 640 * 1000 * 1000
 
 
 def csrc_digest():
@@ -84,6 +87,7 @@ def main():
     ap.add_argument("--copy-probe", action="store_true", help="first run three plain 256 MiB device copies "
                     "(an elementwise kernel of known traffic that calibrates the HBM byte counters)")
     ap.add_argument("--no-layer-rows", action="store_true", help="skip the per-layer timing loops (counter runs)")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache per-layer timings")
     ap.add_argument("--layers", default="", help="comma list of suite layers to run (default: all eight); "
                     "a subset is for profiling one kernel and changes the workload the line reports")
     ap.add_argument("--tile", default="", help="force a variant bm,bn,bk,wm,wn[,split_k[,layout[,raster]]] (profiling)")
@@ -169,6 +173,23 @@ def main():
                          frac_roofline=round(tf / ceiling, 4), gbs=round(L["bytes"] / (ms * 1e-3) / 1e9, 1),
                          tile=tile))
         kern_ms_sum += ms
+        if not args.no_cold:
+            # the same call over a rotation of distinct operand sets larger than the 256 MB last-level
+            # cache taken twice, so that no call finds its operands or its output lines cached
+            nsets = max(2, int(-(-COLD_ROTATION_BYTES // L["bytes"])))
+            sets = [(L["x"].clone(), L["w"].clone(), L["b"].clone(), torch.empty_like(L["out"])) for _ in range(nsets)]
+            turn = [0]
+
+            def run_cold(L=L, sets=sets, turn=turn):
+                x, w, b, o = sets[turn[0] % len(sets)]
+                turn[0] += 1
+                P.conv2d_fwd(x, w, b, out=o, stride=L["shape"].stride, pad=L["shape"].pad, act="relu")
+
+            cms = time_calls(torch, run_cold, max(reps, nsets))
+            rows[-1].update(cold_us=round(cms * 1e3, 2), cold_sets=nsets,
+                            cold_gbs=round(L["bytes"] / (cms * 1e-3) / 1e9, 1),
+                            cold_frac_roofline=round(L["flops"] / (cms * 1e-3) / 1e12 / ceiling, 4))
+            del sets
         if args.sweep:
             # every candidate the picker ranks, timed; the model's prediction beside it
             shape = tuple(L["shape"])[1:]
@@ -234,8 +255,9 @@ def main():
             xb = torch.from_numpy(synth.to_bf16_bits(x).view(np.int16)).cuda()
             wb = torch.from_numpy(synth.to_bf16_bits(w).view(np.int16)).cuda()
             db = torch.from_numpy(b).cuda()
-            t_tr = time_calls(torch, lambda: (P.nchw_to_nchwc_bf16(xb, 8), P.kcrs_to_kcrsck_bf16(wb, 8, 1)), 5)
             x8, w8 = P.nchw_to_nchwc_bf16(xb, 8), P.kcrs_to_kcrsck_bf16(wb, 8, 1)
+            t_tr = time_calls(torch, lambda: (P.nchw_to_nchwc_bf16(xb, 8, out=x8),
+                                              P.kcrs_to_kcrsck_bf16(wb, 8, 1, out=w8)), 10)
             out = torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda")
             fn = lambda: P.conv2d_fwd_bf16_blocked(x8, w8, s.C, db, out=out, stride=s.stride, pad=s.pad, act="relu")
             fn()

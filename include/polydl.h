@@ -90,6 +90,14 @@ int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int s
  * allowed (C is left as it is). */
 int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream);
 
+/* The general form the text of section "GEMM" states, C = beta*C + alpha*A*B, with both scalars
+ * applied once per element of C (the baseline listing of that section applies beta inside the
+ * reduction loop, which agrees only for beta = 1).  Same operands, layout and errors as
+ * polydl_sgemm; alpha = beta = 1 gives bit for bit the result of polydl_sgemm.  beta = 0 writes C
+ * without reading it (what C held, NaN included, does not reach the result).  K = 0 scales C. */
+int polydl_sgemm_ex(int M, int N, int K, float alpha, const float *A, const float *B, float beta, float *C,
+                    void *stream);
+
 /* ---- blocked layouts (figure "The 2-D Convolution code": the listing indexes
  * input[img][ifm_tile][h][w][ifm] and filter[ofm_tile][ifm_tile][kj][ki][ifm][ofm]) --------------
  * polydl_nchw_to_nchwc:  out[n][c/b][h][w][c%b] = in[n][c][h][w]; out has N*ceil(C/b)*H*W*b floats,

@@ -59,6 +59,8 @@ _i, _p = ctypes.c_int, ctypes.c_void_p
 lib.polydl_conv2d_fwd.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_conv2d_fwd_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_sgemm.argtypes = [_i, _i, _i, _p, _p, _p, _p]
+lib.polydl_sgemm_ex.argtypes = [_i, _i, _i, ctypes.c_float, _p, _p, ctypes.c_float, _p, _p]
+lib.polydl_sgemm_ex.restype = _i
 lib.polydl_nchw_to_nchwc.argtypes = [_i] * 5 + [_p, _p, _p]
 lib.polydl_nchwc_to_nchw.argtypes = [_i] * 5 + [_p, _p, _p]
 lib.polydl_kcrs_to_kcrsck.argtypes = [_i] * 6 + [_p, _p, _p]
@@ -133,21 +135,27 @@ def _dev16(t, name):
     return ctypes.c_void_p(t.data_ptr())
 
 
-def nchw_to_nchwc_bf16(x, b=8, stream=None):
+def nchw_to_nchwc_bf16(x, b=8, stream=None, out=None):
     """polydl_nchw_to_nchwc_bf16 on a 16-bit NCHW tensor: returns [N][ceil(C/b)][H][W][b]."""
     import torch
     N, C, H, W = x.shape
-    out = torch.empty((N, -(-C // b), H, W, b), dtype=x.dtype, device=x.device)
+    if out is None:
+        out = torch.empty((N, -(-C // b), H, W, b), dtype=x.dtype, device=x.device)
+    elif tuple(out.shape) != (N, -(-C // b), H, W, b) or out.dtype != x.dtype:
+        raise ValueError("out must be a [N][ceil(C/b)][H][W][b] tensor of the input's type")
     _check(lib.polydl_nchw_to_nchwc_bf16(N, C, H, W, b, _dev16(x, "x"), _dev16(out, "out"), _stream_ptr(stream)),
            "polydl_nchw_to_nchwc_bf16")
     return out
 
 
-def kcrs_to_kcrsck_bf16(w, bc=8, bk=1, stream=None):
+def kcrs_to_kcrsck_bf16(w, bc=8, bk=1, stream=None, out=None):
     """polydl_kcrs_to_kcrsck_bf16: returns [ceil(K/bk)][ceil(C/bc)][R][S][bc][bk] (16-bit elements)."""
     import torch
     K, C, R, S = w.shape
-    out = torch.empty((-(-K // bk), -(-C // bc), R, S, bc, bk), dtype=w.dtype, device=w.device)
+    if out is None:
+        out = torch.empty((-(-K // bk), -(-C // bc), R, S, bc, bk), dtype=w.dtype, device=w.device)
+    elif tuple(out.shape) != (-(-K // bk), -(-C // bc), R, S, bc, bk) or out.dtype != w.dtype:
+        raise ValueError("out must be a [ceil(K/bk)][ceil(C/bc)][R][S][bc][bk] tensor of the input's type")
     _check(lib.polydl_kcrs_to_kcrsck_bf16(K, C, R, S, bc, bk, _dev16(w, "w"), _dev16(out, "out"),
                                           _stream_ptr(stream)), "polydl_kcrs_to_kcrsck_bf16")
     return out
@@ -205,14 +213,20 @@ def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None
     return out
 
 
-def sgemm(A, B, C, stream=None):
-    """polydl_sgemm: C += A @ B in place on torch device tensors (row-major)."""
+def sgemm(A, B, C, stream=None, alpha=None, beta=None):
+    """polydl_sgemm: C += A @ B in place on torch device tensors (row-major); with alpha or beta
+    given, polydl_sgemm_ex: C = beta*C + alpha*A@B."""
     M, K = A.shape
     K2, N = B.shape
     if K2 != K or tuple(C.shape) != (M, N):
         raise ValueError("shape mismatch")
-    st = lib.polydl_sgemm(M, N, K, _dev(A, "A"), _dev(B, "B"), _dev(C, "C"), _stream_ptr(stream))
-    _check(st, "polydl_sgemm")
+    if alpha is None and beta is None:
+        st = lib.polydl_sgemm(M, N, K, _dev(A, "A"), _dev(B, "B"), _dev(C, "C"), _stream_ptr(stream))
+        _check(st, "polydl_sgemm")
+        return C
+    st = lib.polydl_sgemm_ex(M, N, K, ctypes.c_float(1.0 if alpha is None else alpha), _dev(A, "A"), _dev(B, "B"),
+                             ctypes.c_float(1.0 if beta is None else beta), _dev(C, "C"), _stream_ptr(stream))
+    _check(st, "polydl_sgemm_ex")
     return C
 
 

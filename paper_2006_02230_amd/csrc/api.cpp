@@ -112,13 +112,17 @@ static bool conv_in_range(int N, int C, int H, int W, int K, int R, int S, int s
     return true;
 }
 
-static int sgemm_impl(int M, int N, int K, const float *A, const float *B, float *C, void *stream)
+static int sgemm_impl(int M, int N, int K, float alpha, const float *A, const float *B, float beta, float *C,
+                      void *stream)
 {
     if (M <= 0 || N <= 0 || K < 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!C || (K > 0 && (!A || !B))) return POLYDL_ERR_NULL_POINTER;
-    if (K == 0) return POLYDL_OK;
+    if (K == 0 && beta == 1.f) return POLYDL_OK;
     polydl_tile_cfg cfg;
-    {
+    if (K == 0) {
+        // an empty product: only C = beta*C is left, any variant's epilogue does it
+        cfg_of(kVariants[0], 1, 0, 0, &cfg);
+    } else {
         std::lock_guard<std::mutex> lk(g_mu);
         cfg = g_override;
         if (!g_have_override) {
@@ -141,7 +145,7 @@ static int sgemm_impl(int M, int N, int K, const float *A, const float *B, float
     if ((uint64_t)v->bk * (uint64_t)N * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;
     uint64_t tiles = (uint64_t)((M + v->bm - 1) / v->bm) * (uint64_t)((N + v->bn - 1) / v->bn);
     if (tiles >= 0x7FFFFFFFull || cfg.split_k > 65535) return POLYDL_ERR_UNSUPPORTED;
-    SgemmProblem q{M, N, K, A, B, C};
+    SgemmProblem q{M, N, K, A, B, C, alpha, beta};
     hipError_t e = v->sgemm(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
     if (e != hipSuccess) return launch_failed(e);
     std::lock_guard<std::mutex> lk(g_mu);
@@ -198,7 +202,9 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     if (!v) return POLYDL_ERR_UNSUPPORTED;
     // a tile of bn pixels spans at most bn/PQ + 2 images; their offsets must fit 31 bits
     const int64_t span = (v->bn / (P * Q) + 2) * CHW * 4;
-    if (span >= 0x7FFFFFF0ll || (int64_t)v->bm * Kg * 4 >= 0x7FFFFFF0ll) return POLYDL_ERR_UNSUPPORTED;
+    const int64_t span_out = (v->bn / (P * Q) + 2) * (int64_t)K * P * Q * 4;
+    if (span >= 0x7FFFFFF0ll || span_out >= 0x7FFFFFF0ll || (int64_t)v->bm * Kg * 4 >= 0x7FFFFFF0ll)
+        return POLYDL_ERR_UNSUPPORTED;
     hipError_t e = v->conv(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
     if (e != hipSuccess) return launch_failed(e);
     std::lock_guard<std::mutex> lk(g_mu);
@@ -229,7 +235,13 @@ int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int s
 
 int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream)
 {
-    return sgemm_impl(M, N, K, A, B, C, stream);
+    return sgemm_impl(M, N, K, 1.f, A, B, 1.f, C, stream);
+}
+
+int polydl_sgemm_ex(int M, int N, int K, float alpha, const float *A, const float *B, float beta, float *C,
+                    void *stream)
+{
+    return sgemm_impl(M, N, K, alpha, A, B, beta, C, stream);
 }
 
 int polydl_nchw_to_nchwc(int N, int C, int H, int W, int b, const float *in, float *out, void *stream)

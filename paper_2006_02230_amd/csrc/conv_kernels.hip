@@ -22,7 +22,8 @@ struct ConvKArgs {
     int Kg, Ng;                 // reduction length C*R*S, number of output pixels N*P*Q
     uint32_t magic_RS, magic_S; // exact division of a reduction index by R*S and by S,
     uint32_t one_RS, one_S;     // see fast_div(): magic multiplier and the all-ones mask for d == 1
-    uint64_t in_bytes;
+    uint32_t recip_PQ, recip_Q; // for div_by(): pixel index -> (image, row, column)
+    uint64_t in_bytes, out_bytes;
     int tiles_m, tiles_n;
     int split_k, k_per_split;
     int raster, act;
@@ -42,7 +43,11 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic, uint32_
     return __umulhi(n, magic) + (n & ones_if_d1);
 }
 
-template <class T>
+// POINT = true: 1x1 filters without padding.  Reduction row k is channel k, every tap lies inside
+// the image, and the channel's distance from the pixel is uniform over the wave, so a load needs
+// no per-lane arithmetic at all: the lane keeps the byte offset of its pixel and the channel
+// offset rides in the instruction's uniform offset.
+template <class T, bool POINT>
 struct BLoaderIm2col {
     static constexpr int KSTEP = T::NT / T::BN;  // reduction rows covered by one pass of the workgroup
     static constexpr int ITERS = T::BK / KSTEP;
@@ -63,25 +68,40 @@ struct BLoaderIm2col {
         krow0 = __builtin_amdgcn_readfirstlane(tid / T::BN);
         lds_off = krow0 * T::LDB + col;
         // the descriptor starts at the first image this tile touches: offsets stay small
-        const int img0 = n0 / p.PQ;
+        uint32_t rem0;
+        const int img0 = (int)div_by((uint32_t)n0, (uint32_t)p.PQ, p.recip_PQ, rem0);
         const uint64_t skip = (uint64_t)img0 * p.CHW * 4;
         rsrc = make_rsrc(reinterpret_cast<const char *>(p.in) + skip, p.in_bytes - skip);
         const int colg = n0 + col;
         rmask = 0; smask = 0; pix_off = 0;
         if (colg < p.Ng) {
-            int img = colg / p.PQ, pq = colg - img * p.PQ;
-            int op = pq / p.Q, oq = pq - op * p.Q;
-            int ih0 = op * p.stride - p.pad, iw0 = oq * p.stride - p.pad;
+            uint32_t pq, oq;
+            int img = (int)div_by((uint32_t)colg, (uint32_t)p.PQ, p.recip_PQ, pq);
+            int op = (int)div_by(pq, (uint32_t)p.Q, p.recip_Q, oq);
+            int ih0 = op * p.stride - p.pad, iw0 = (int)oq * p.stride - p.pad;
             pix_off = (img - img0) * p.CHW + ih0 * p.W + iw0;
-            for (int r = 0; r < p.R; ++r)
-                if (ih0 + r >= 0 && ih0 + r < p.H) rmask |= 1u << r;
-            for (int s = 0; s < p.S; ++s)
-                if (iw0 + s >= 0 && iw0 + s < p.W) smask |= 1u << s;
+            if constexpr (!POINT) {
+                for (int r = 0; r < p.R; ++r)
+                    if (ih0 + r >= 0 && ih0 + r < p.H) rmask |= 1u << r;
+                for (int s = 0; s < p.S; ++s)
+                    if (iw0 + s >= 0 && iw0 + s < p.W) smask |= 1u << s;
+            }
         }
+        if constexpr (POINT) pix_off = colg < p.Ng ? pix_off * 4 : (int)kOobOffset;   // bytes, or out of range
     }
     template <int SET>
     __device__ __forceinline__ void load(int k0, int kend)
     {
+        if constexpr (POINT) {
+            // A row at or past kend meets zeros in the filter operand; it reads the last real
+            // channel so that what it multiplies is a finite input value of the same image
+#pragma unroll
+            for (int i = 0; i < ITERS; ++i) {
+                int kg = min(k0 + krow0 + i * KSTEP, kend - 1);  // wave-uniform
+                regs[SET][i] = buf_load1(rsrc, (uint32_t)pix_off, (uint32_t)(kg * HW) * 4u);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
             uint32_t kg = (uint32_t)(k0 + krow0 + i * KSTEP);  // wave-uniform
@@ -111,7 +131,43 @@ __device__ __forceinline__ float apply_act(float v, int act)
     return v;
 }
 
-template <class T, int AVEC>
+template <int ACT>
+__device__ __forceinline__ float act_of(float v)
+{
+    if constexpr (ACT != POLYDL_ACT_NONE) v = fmaxf(v, 0.f);
+    if constexpr (ACT == POLYDL_ACT_RELU6) v = fminf(v, 6.f);
+    return v;
+}
+
+// Bias, activation and store of the lane's 16*MB channel rows, NB adjacent pixels each as one
+// vector.  `off` is the lane's byte offset of channel row `krow`; row c of the tile lies c*row_bytes
+// further, a uniform offset.  FULL: every channel row of the tile exists.
+template <class T, int ACT, bool FULL>
+__device__ __forceinline__ void store_rows(__amdgpu_buffer_rsrc_t ro, uint32_t off, uint32_t row_bytes,
+                                           const v16f (&acc)[T::MB][T::NB], const float (&bias)[T::MB][16], int krow,
+                                           int K)
+{
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int c = 32 * bi + 8 * (r >> 2) + (r & 3);
+            if (!FULL && krow + c >= K) continue;
+            const float b = bias[bi][r];
+            if constexpr (T::NB == 4) {
+                v4f v = {act_of<ACT>(acc[bi][0][r] + b), act_of<ACT>(acc[bi][1][r] + b), act_of<ACT>(acc[bi][2][r] + b),
+                         act_of<ACT>(acc[bi][3][r] + b)};
+                buf_store4(ro, off, (uint32_t)c * row_bytes, v);
+            } else if constexpr (T::NB == 2) {
+                v2f v = {act_of<ACT>(acc[bi][0][r] + b), act_of<ACT>(acc[bi][1][r] + b)};
+                buf_store2(ro, off, (uint32_t)c * row_bytes, v);
+            } else {
+                buf_store1(ro, off, (uint32_t)c * row_bytes, act_of<ACT>(acc[bi][0][r] + b));
+            }
+        }
+}
+
+template <class T, int AVEC, bool POINT>
 __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
 {
     __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
@@ -124,7 +180,7 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
     const int kend = min(p.Kg, kbegin + p.k_per_split);
 
     ALoader<T, AVEC> al;
-    BLoaderIm2col<T> bl;
+    BLoaderIm2col<T, POINT> bl;
     al.init(p.wt, tid, m0, p.K, p.Kg, p.Kg);
     bl.init(p, tid, n0);
 
@@ -182,40 +238,59 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
         }
     }
     // epilogue.  The lane owns NB adjacent pixels starting at colg for 16*MB output channels.
+    // Addresses are a per-lane byte offset from the first image the tile touches plus a uniform
+    // offset per channel row, so a store costs no address arithmetic.
     const int colg = n0 + wn0 + T::NB * (lane & 31);
     if (colg >= p.Ng) return;
-    const int img = colg / p.PQ, pq = colg - img * p.PQ;
-    // the NB pixels are one vector store when they lie in one image and keep the alignment
-    const bool vec = (p.PQ % T::NB == 0) && (((uintptr_t)p.out & 15) == 0);
+    const int krow = m0 + wm0 + 4 * (lane >> 5);   // channel of register 0; register r adds 8*(r/4) + r%4
+    const uint32_t KPQ = (uint32_t)p.K * (uint32_t)p.PQ;
+    uint32_t rem0, pq;
+    const uint32_t img0 = div_by((uint32_t)n0, (uint32_t)p.PQ, p.recip_PQ, rem0);   // uniform
+    const uint32_t img = div_by((uint32_t)colg, (uint32_t)p.PQ, p.recip_PQ, pq);
+    const uint64_t skip = (uint64_t)img0 * KPQ * 4;
+    __amdgpu_buffer_rsrc_t ro = make_rsrc(reinterpret_cast<char *>(p.out) + skip, p.out_bytes - skip);
+    // bias of channels at or past K reads as zero (as does every channel without a bias vector)
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (uint64_t)p.K * 4 : 0);
+    float bias[T::MB][16];
 #pragma unroll
     for (int bi = 0; bi < T::MB; ++bi)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int k = m0 + acc_row(wm0, bi, r, lane);
-            if (k >= p.K) continue;
-            const float b = p.bias ? p.bias[k] : 0.f;
-            float *o = p.out + ((size_t)img * p.K + k) * p.PQ + pq;
-            if (vec) {
-                if constexpr (T::NB == 4) {
-                    v4f v = {apply_act(acc[bi][0][r] + b, p.act), apply_act(acc[bi][1][r] + b, p.act),
-                             apply_act(acc[bi][2][r] + b, p.act), apply_act(acc[bi][3][r] + b, p.act)};
-                    *reinterpret_cast<v4f *>(o) = v;
-                } else if constexpr (T::NB == 2) {
-                    v2f v = {apply_act(acc[bi][0][r] + b, p.act), apply_act(acc[bi][1][r] + b, p.act)};
-                    *reinterpret_cast<v2f *>(o) = v;
-                } else {
-                    *o = apply_act(acc[bi][0][r] + b, p.act);
-                }
-            } else {
-#pragma unroll
-                for (int bj = 0; bj < T::NB; ++bj) {
-                    int cg = colg + bj;
-                    if (cg >= p.Ng) break;
-                    int im = cg / p.PQ, q = cg - im * p.PQ;
-                    p.out[((size_t)im * p.K + k) * p.PQ + q] = apply_act(acc[bi][bj][r] + b, p.act);
-                }
-            }
+        for (int r = 0; r < 16; ++r)
+            bias[bi][r] = buf_load1(rb, (uint32_t)(krow + 32 * bi + 8 * (r >> 2) + (r & 3)) * 4u);
+    const uint32_t row_bytes = (uint32_t)p.PQ * 4u;
+    // the NB pixels are one vector store when they lie in one image and keep the alignment
+    const bool vec = (p.PQ % T::NB == 0) && (((uintptr_t)p.out & 15) == 0);
+    if (vec) {
+        const uint32_t off = ((img - img0) * KPQ + (uint32_t)krow * (uint32_t)p.PQ + pq) * 4u;
+        // uniform choices made once: which activation, and whether any channel of the tile is outside K
+        const bool full = m0 + T::BM <= p.K;
+        if (full) {
+            if (p.act == POLYDL_ACT_NONE) store_rows<T, POLYDL_ACT_NONE, true>(ro, off, row_bytes, acc, bias, krow, p.K);
+            else if (p.act == POLYDL_ACT_RELU) store_rows<T, POLYDL_ACT_RELU, true>(ro, off, row_bytes, acc, bias, krow, p.K);
+            else store_rows<T, POLYDL_ACT_RELU6, true>(ro, off, row_bytes, acc, bias, krow, p.K);
+        } else {
+            if (p.act == POLYDL_ACT_NONE) store_rows<T, POLYDL_ACT_NONE, false>(ro, off, row_bytes, acc, bias, krow, p.K);
+            else if (p.act == POLYDL_ACT_RELU) store_rows<T, POLYDL_ACT_RELU, false>(ro, off, row_bytes, acc, bias, krow, p.K);
+            else store_rows<T, POLYDL_ACT_RELU6, false>(ro, off, row_bytes, acc, bias, krow, p.K);
         }
+    } else {
+#pragma unroll
+        for (int bj = 0; bj < T::NB; ++bj) {
+            if (colg + bj >= p.Ng) break;
+            // pixel bj of the lane: same image, or among the first pixels of a following one
+            uint32_t q = pq + bj, im = img - img0;
+            while (q >= (uint32_t)p.PQ) { q -= (uint32_t)p.PQ; ++im; }
+            const uint32_t off = (im * KPQ + (uint32_t)krow * (uint32_t)p.PQ + q) * 4u;
+#pragma unroll
+            for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int c = 32 * bi + 8 * (r >> 2) + (r & 3);
+                    if (krow + c >= p.K) continue;
+                    buf_store1(ro, off, (uint32_t)c * row_bytes, apply_act(acc[bi][bj][r] + bias[bi][r], p.act));
+                }
+        }
+    }
 }
 
 template <class T>
@@ -234,6 +309,9 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     a.one_RS = a.RS == 1 ? 0xFFFFFFFFu : 0u;
     a.one_S = q.S == 1 ? 0xFFFFFFFFu : 0u;
     a.in_bytes = (uint64_t)q.N * a.CHW * 4;
+    a.out_bytes = (uint64_t)q.N * q.K * a.PQ * 4;
+    a.recip_PQ = div_recip((uint32_t)a.PQ);
+    a.recip_Q = div_recip((uint32_t)q.Q);
     a.tiles_m = (q.K + T::BM - 1) / T::BM;
     a.tiles_n = (a.Ng + T::BN - 1) / T::BN;
     int stages = (a.Kg + T::BK - 1) / T::BK;
@@ -254,8 +332,11 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     }
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
-    if (avec) hipLaunchKernelGGL((conv_kernel<T, 4>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((conv_kernel<T, 1>), grid, block, 0, stream, a);
+    const bool point = q.R == 1 && q.S == 1 && q.pad == 0;
+    if (avec && point) hipLaunchKernelGGL((conv_kernel<T, 4, true>), grid, block, 0, stream, a);
+    else if (avec) hipLaunchKernelGGL((conv_kernel<T, 4, false>), grid, block, 0, stream, a);
+    else if (point) hipLaunchKernelGGL((conv_kernel<T, 1, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((conv_kernel<T, 1, false>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 

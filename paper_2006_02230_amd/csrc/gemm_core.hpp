@@ -45,6 +45,36 @@ __device__ __forceinline__ v4f buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte
     v4i v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
     return __builtin_bit_cast(v4f, v);
 }
+// byte_off is per lane and the only part that is range-checked; uniform_off (the same for the
+// whole wave) is added to the address after the check
+__device__ __forceinline__ float buf_load1(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, (int)uniform_off, 0));
+}
+__device__ __forceinline__ void buf_store1(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, uint32_t uniform_off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), r, (int)byte_off, (int)uniform_off, 0);
+}
+__device__ __forceinline__ void buf_store2(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, uint32_t uniform_off, v2f v)
+{
+    typedef int v2i __attribute__((ext_vector_type(2)));
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(v2i, v), r, (int)byte_off, (int)uniform_off, 0);
+}
+__device__ __forceinline__ void buf_store4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, uint32_t uniform_off, v4f v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v), r, (int)byte_off, (int)uniform_off, 0);
+}
+
+// n / d and n % d for any 32-bit n and d >= 1, given recip = floor(2^32 / d) (0xFFFFFFFF for
+// d == 1): umulhi(n, recip) is the quotient or one below it, which one comparison settles.
+__device__ __forceinline__ uint32_t div_by(uint32_t n, uint32_t d, uint32_t recip, uint32_t &rem)
+{
+    uint32_t q = __umulhi(n, recip);
+    uint32_t r = n - q * d;
+    if (r >= d) { ++q; r -= d; }
+    rem = r;
+    return q;
+}
 
 template <int BM_, int BN_, int BK_, int WM_, int WN_>
 struct Tile {

@@ -10,6 +10,7 @@ struct SgemmProblem {
     int M, N, K;
     const float *A, *B;
     float *C;
+    float alpha = 1.f, beta = 1.f;   // C = beta*C + alpha*A*B
 };
 
 struct ConvProblem {
@@ -87,5 +88,9 @@ bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_repor
 // Exact unsigned division by a runtime constant d for dividends n with n*d < 2^32:
 // n / d == (n * magic) >> 32 with magic = floor(2^32 / d) + 1.
 inline uint32_t div_magic(uint32_t d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
+
+
+// Reciprocal for the device-side div_by(): floor(2^32 / d), saturated for d == 1.
+inline uint32_t div_recip(uint32_t d) { return d <= 1 ? 0xFFFFFFFFu : (uint32_t)((1ull << 32) / d); }
 
 }  // namespace polydl

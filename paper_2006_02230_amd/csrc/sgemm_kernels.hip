@@ -13,6 +13,7 @@ struct SgemmKArgs {
     int tiles_m, tiles_n;
     int split_k, k_per_split;  // k_per_split is a multiple of the stage depth
     int raster;
+    float alpha, beta;         // C = beta*C + alpha*A*B; beta == 0 writes C without reading it
     float *partials;           // split_k > 1: [tile][part][BM*BN] accumulator tiles in register order
     unsigned *counters;        // split_k > 1: per tile, how many of its reduction parts have finished
 };
@@ -90,8 +91,10 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // epilogue: C += acc
+    // epilogue: C = beta*C + alpha*acc (alpha = beta = 1 rounds exactly like C += acc)
     const int col = n0 + wn0 + T::NB * (lane & 31);
+    const float alpha = p.alpha, beta = p.beta;
+    const bool readc = beta != 0.f;
 #pragma unroll
     for (int bi = 0; bi < T::MB; ++bi)
 #pragma unroll
@@ -101,20 +104,23 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
             float *c = p.C + (size_t)row * p.N + col;
             if (CVEC && T::NB == 4) {
                 if (col < p.N) {
-                    v4f v = *reinterpret_cast<v4f *>(c);
-                    v.x += acc[bi][0][r]; v.y += acc[bi][1][r]; v.z += acc[bi][2][r]; v.w += acc[bi][3][r];
+                    v4f v = {0.f, 0.f, 0.f, 0.f};
+                    if (readc) v = *reinterpret_cast<v4f *>(c);
+                    v.x = beta * v.x + alpha * acc[bi][0][r]; v.y = beta * v.y + alpha * acc[bi][1][r];
+                    v.z = beta * v.z + alpha * acc[bi][2][r]; v.w = beta * v.w + alpha * acc[bi][3][r];
                     *reinterpret_cast<v4f *>(c) = v;
                 }
             } else if (CVEC && T::NB == 2) {
                 if (col < p.N) {
-                    v2f v = *reinterpret_cast<v2f *>(c);
-                    v.x += acc[bi][0][r]; v.y += acc[bi][1][r];
+                    v2f v = {0.f, 0.f};
+                    if (readc) v = *reinterpret_cast<v2f *>(c);
+                    v.x = beta * v.x + alpha * acc[bi][0][r]; v.y = beta * v.y + alpha * acc[bi][1][r];
                     *reinterpret_cast<v2f *>(c) = v;
                 }
             } else {
 #pragma unroll
                 for (int bj = 0; bj < T::NB; ++bj)
-                    if (col + bj < p.N) c[bj] += acc[bi][bj][r];
+                    if (col + bj < p.N) c[bj] = beta * (readc ? c[bj] : 0.f) + alpha * acc[bi][bj][r];
             }
         }
 }
@@ -136,6 +142,7 @@ static hipError_t sgemm_launch(const SgemmProblem &q, int split_k, int raster, h
     split_k = stages > 0 ? (stages + stages_per - 1) / stages_per : 1;
     a.split_k = split_k;
     a.raster = raster;
+    a.alpha = q.alpha; a.beta = q.beta;
     a.partials = nullptr;
     a.counters = nullptr;
     clear_stale_hip_error();

@@ -35,6 +35,10 @@ def test_argument_validation_without_device(lib):
     z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
     assert lib.polydl_sgemm(0, 1, 1, one, one, one, z) == -2
     assert lib.polydl_sgemm(2, 2, 2, z, one, one, z) == -1
+    lib.polydl_sgemm_ex.argtypes = [ctypes.c_int] * 3 + [ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+                                                         ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.polydl_sgemm_ex(2, 0, 2, 1.0, one, one, 1.0, one, z) == -2
+    assert lib.polydl_sgemm_ex(2, 2, 2, 1.0, one, one, 0.0, z, z) == -1
     assert lib.polydl_conv2d_fwd(1, 1, 2, 2, 1, 3, 3, 1, 0, one, one, z, one, 0, z) == -2
     assert lib.polydl_conv2d_fwd(1, 1, 4, 4, 1, 3, 3, 1, 1, z, one, z, one, 0, z) == -1
     lib.polydl_status_string.restype = ctypes.c_char_p

@@ -141,6 +141,49 @@ def test_split_reduction_is_reproducible(P):
     P.set_tile_override(None)
 
 
+@pytest.mark.parametrize("alpha,beta", [(2.0, -3.0), (0.5, 0.0), (0.0, 1.5), (-1.25, 1.0)])
+def test_alpha_beta(P, alpha, beta):
+    # section "GEMM": C = beta*C + alpha*A*B, each scalar applied once per element
+    M, N, K = 200, 136, 300
+    A, B, C0 = synth.sgemm_inputs(M, N, K, seed=77, c0="random")
+    want, ab = oracle.gemm(A, B, C0, alpha=alpha, beta=beta)
+    for v in P.variants(1):
+        for split_k in (1, 3):
+            v.split_k = split_k
+            P.set_tile_override(v)
+            C = dev(C0.copy())
+            P.sgemm(dev(A), dev(B), C, alpha=alpha, beta=beta)
+            err = oracle.scaled_error(host(C), want, ab)
+            assert err <= FP32_TOL, (v, err)
+    P.set_tile_override(None)
+
+
+def test_alpha_beta_special_cases(P):
+    import torch
+    M, N, K = 130, 67, 129
+    A, B, C0 = synth.sgemm_inputs(M, N, K, seed=78, c0="random")
+    # alpha = beta = 1 is polydl_sgemm bit for bit
+    C1, C2 = dev(C0.copy()), dev(C0.copy())
+    P.sgemm(dev(A), dev(B), C1)
+    P.sgemm(dev(A), dev(B), C2, alpha=1.0, beta=1.0)
+    assert np.array_equal(host(C1), host(C2))
+    # beta = 0 does not read C: what it held, NaN included, does not reach the result
+    Cn = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.sgemm(dev(A), dev(B), Cn, alpha=1.0, beta=0.0)
+    want, ab = oracle.gemm(A, B, None)
+    assert oracle.scaled_error(host(Cn), want, ab) <= FP32_TOL
+    # small integers with integer scalars: exact
+    Ai, Bi, Ci = synth.sgemm_inputs(M, N, K, seed=5, dist="ints", c0="random")
+    C = dev(Ci.copy())
+    P.sgemm(dev(Ai), dev(Bi), C, alpha=-2.0, beta=3.0)
+    want, _ = oracle.gemm(Ai, Bi, Ci, alpha=-2.0, beta=3.0)
+    assert np.array_equal(host(C).astype(np.float64), want)
+    # an empty product scales C
+    C = dev(C0.copy())
+    assert P.lib.polydl_sgemm_ex(M, N, 0, 2.0, None, None, 0.5, C.data_ptr(), None) == 0
+    assert np.array_equal(host(C), C0 * np.float32(0.5))
+
+
 def test_argument_errors(P):
     import ctypes
     z = ctypes.c_void_p(0)
@@ -150,3 +193,6 @@ def test_argument_errors(P):
     assert P.lib.polydl_sgemm(4, 4, 4, z, one, one, z) == -1
     assert P.lib.polydl_sgemm(4, 4, 4, one, one, z, z) == -1
     assert P.lib.polydl_sgemm(4, 4, 0, z, z, one, z) == 0   # K = 0: nothing to add
+    assert P.lib.polydl_sgemm_ex(4, 4, 0, 2.0, z, z, 1.0, one, z) == 0   # K = 0, beta = 1: C unchanged, untouched
+    assert P.lib.polydl_sgemm_ex(0, 4, 4, 1.0, one, one, 1.0, one, z) == -2
+    assert P.lib.polydl_sgemm_ex(4, 4, 4, 1.0, one, z, 1.0, one, z) == -1
