@@ -131,42 +131,6 @@ __device__ __forceinline__ float apply_act(float v, int act)
     return v;
 }
 
-template <int ACT>
-__device__ __forceinline__ float act_of(float v)
-{
-    if constexpr (ACT != POLYDL_ACT_NONE) v = fmaxf(v, 0.f);
-    if constexpr (ACT == POLYDL_ACT_RELU6) v = fminf(v, 6.f);
-    return v;
-}
-
-// Bias, activation and store of the lane's 16*MB channel rows, NB adjacent pixels each as one
-// vector.  `off` is the lane's byte offset of channel row `krow`; row c of the tile lies c*row_bytes
-// further, a uniform offset.  FULL: every channel row of the tile exists.
-template <class T, int ACT, bool FULL>
-__device__ __forceinline__ void store_rows(__amdgpu_buffer_rsrc_t ro, uint32_t off, uint32_t row_bytes,
-                                           const v16f (&acc)[T::MB][T::NB], const float (&bias)[T::MB][16], int krow,
-                                           int K)
-{
-#pragma unroll
-    for (int bi = 0; bi < T::MB; ++bi)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int c = 32 * bi + 8 * (r >> 2) + (r & 3);
-            if (!FULL && krow + c >= K) continue;
-            const float b = bias[bi][r];
-            if constexpr (T::NB == 4) {
-                v4f v = {act_of<ACT>(acc[bi][0][r] + b), act_of<ACT>(acc[bi][1][r] + b), act_of<ACT>(acc[bi][2][r] + b),
-                         act_of<ACT>(acc[bi][3][r] + b)};
-                buf_store4(ro, off, (uint32_t)c * row_bytes, v);
-            } else if constexpr (T::NB == 2) {
-                v2f v = {act_of<ACT>(acc[bi][0][r] + b), act_of<ACT>(acc[bi][1][r] + b)};
-                buf_store2(ro, off, (uint32_t)c * row_bytes, v);
-            } else {
-                buf_store1(ro, off, (uint32_t)c * row_bytes, act_of<ACT>(acc[bi][0][r] + b));
-            }
-        }
-}
-
 template <class T, int AVEC, bool POINT>
 __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
 {
@@ -262,17 +226,7 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
     const bool vec = (p.PQ % T::NB == 0) && (((uintptr_t)p.out & 15) == 0);
     if (vec) {
         const uint32_t off = ((img - img0) * KPQ + (uint32_t)krow * (uint32_t)p.PQ + pq) * 4u;
-        // uniform choices made once: which activation, and whether any channel of the tile is outside K
-        const bool full = m0 + T::BM <= p.K;
-        if (full) {
-            if (p.act == POLYDL_ACT_NONE) store_rows<T, POLYDL_ACT_NONE, true>(ro, off, row_bytes, acc, bias, krow, p.K);
-            else if (p.act == POLYDL_ACT_RELU) store_rows<T, POLYDL_ACT_RELU, true>(ro, off, row_bytes, acc, bias, krow, p.K);
-            else store_rows<T, POLYDL_ACT_RELU6, true>(ro, off, row_bytes, acc, bias, krow, p.K);
-        } else {
-            if (p.act == POLYDL_ACT_NONE) store_rows<T, POLYDL_ACT_NONE, false>(ro, off, row_bytes, acc, bias, krow, p.K);
-            else if (p.act == POLYDL_ACT_RELU) store_rows<T, POLYDL_ACT_RELU, false>(ro, off, row_bytes, acc, bias, krow, p.K);
-            else store_rows<T, POLYDL_ACT_RELU6, false>(ro, off, row_bytes, acc, bias, krow, p.K);
-        }
+        store_rows_by<T>(p.act, m0 + T::BM <= p.K, ro, off, row_bytes, acc, bias, krow, p.K);
     } else {
 #pragma unroll
         for (int bj = 0; bj < T::NB; ++bj) {

@@ -78,8 +78,9 @@ struct ConvPatchKArgs {
     int rows_full;   // patch rows one whole image contributes: (P-1)*prs + R
     int a_stage;     // floats reserved per LDS filter stage (BM*LDA rounded up to the workgroup size)
     int b_stage;     // floats reserved per LDS patch stage (rounded up likewise)
-    uint32_t magic_Wp, one_Wp, magic_rf, one_rf, magic_lda;
-    uint64_t in_bytes, wt_bytes;
+    uint32_t magic_Wp, one_Wp, magic_rf, one_rf, magic_lda, magic_S, one_S, magic_nr, one_nr;
+    uint32_t recip_PQ, recip_Q, recip_split;   // for div_by()
+    uint64_t in_bytes, wt_bytes, out_bytes;
     int tiles_m, tiles_n, raster, act;
     // split_k > 1: every tile's reduction is cut into split_k parts of stages_per_split stages;
     // workgroup t*split_k + y takes part y of tile t
@@ -190,8 +191,9 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const bool cut = p.split_k > 1;   // uniform
     int tile = blockIdx.x, part = 0;
     if (cut) {
-        tile = blockIdx.x / p.split_k;
-        part = blockIdx.x - tile * p.split_k;
+        uint32_t rem;
+        tile = (int)div_by(blockIdx.x, (uint32_t)p.split_k, p.recip_split, rem);
+        part = (int)rem;
     }
     const int cut_tile = tile;
     int tm, tn;
@@ -201,8 +203,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 
     // ---- geometry of this workgroup's pixel run (uniform) ---------------------------------
     const int nlast = min(n0 + T::BN, p.Ng) - 1;
-    const int img_a = n0 / p.PQ, p_a = (n0 - img_a * p.PQ) / p.Q;
-    const int img_b = nlast / p.PQ, p_b = (nlast - img_b * p.PQ) / p.Q;
+    uint32_t pq_a, pq_b, q_a, q_b;
+    const int img_a = (int)div_by((uint32_t)n0, (uint32_t)p.PQ, p.recip_PQ, pq_a);
+    const int p_a = (int)div_by(pq_a, (uint32_t)p.Q, p.recip_Q, q_a);
+    const int img_b = (int)div_by((uint32_t)nlast, (uint32_t)p.PQ, p.recip_PQ, pq_b);
+    const int p_b = (int)div_by(pq_b, (uint32_t)p.Q, p.recip_Q, q_b);
     int nrows0, total_rows;
     if (img_a == img_b) {
         nrows0 = (p_b - p_a) * p.prs + p.Rp;
@@ -214,7 +219,9 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const int ihb0 = p_a * p.stride - p.pad;       // first input row held for the first image
     const int chs = total_rows * p.Wp;             // patch floats per channel
     const int patch_elems = p.CB * chs;
-    const uint32_t magic_chs = chs > 1 ? 0xFFFFFFFFu / (uint32_t)chs + 1u : 0u;
+    // Multiplier for e / chs, e < MAXP*NT < 2^14: any value from 2^32/chs up to 2^18/chs above it
+    // divides exactly, so the single-precision reciprocal, nudged upwards, is good enough.
+    const uint32_t magic_chs = chs > 1 ? (uint32_t)(4294967296.0f * __frcp_rn((float)chs) * (1.0f + 0x1p-21f)) + 1u : 0u;
     const uint32_t one_chs = chs > 1 ? 0u : 0xFFFFFFFFu;
 
     const int a_stage = p.a_stage;                 // units: BM rows of pitch LDA, rounded up to NT
@@ -264,7 +271,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         bool ok = (int)e < a_elems && m0 + (int)m < p.K && kk < p.D;
         int col = kk;
         if constexpr (ROWS) {   // stage column kk = (channel, s) -> KCRS column channel*R*S + s (+ r*S per stage)
-            const int c_l = kk / p.S;
+            const int c_l = (int)fdiv((uint32_t)kk, p.magic_S, p.one_S);
             col = c_l * p.RS + (kk - c_l * p.S);
         }
         a_goff[i] = ok ? (uint32_t)(((int)m * p.Kg + col) * E::BYTES) : kOobOffset;
@@ -292,8 +299,10 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         px_img[bj] = -1;
         px_pq[bj] = 0;
         if (colg < p.Ng) {
-            int img = colg / p.PQ, pq = colg - img * p.PQ;
-            int op = pq / p.Q, oq = pq - op * p.Q;
+            uint32_t upq, uoq;
+            int img = (int)div_by((uint32_t)colg, (uint32_t)p.PQ, p.recip_PQ, upq);
+            int op = (int)div_by(upq, (uint32_t)p.Q, p.recip_Q, uoq);
+            int pq = (int)upq, oq = (int)uoq;
             int ii = img - img_a;
             int slot0 = ii == 0 ? 0 : nrows0 + (ii - 1) * p.rows_full;
             int p_lo = ii == 0 ? p_a : 0;
@@ -313,7 +322,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
 
     auto load_stage = [&](int t, int buf) {
-        const int cblk = ROWS ? t / p.nr : t;
+        const int cblk = ROWS ? (int)fdiv((uint32_t)t, p.magic_nr, p.one_nr) : t;
         const int frow = ROWS ? t - cblk * p.nr : 0;     // filter row of this stage
         const int c0 = cblk * p.CB;
         const int k0 = c0 * p.RS + frow * p.S;
@@ -342,13 +351,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         unit_t *B = Bs + buf * p.b_stage + wave * 64;
         if constexpr (ROWS) {
             const int shift = frow * p.W * E::BYTES;
-            const uint32_t magic_c = chs > 1 ? 0xFFFFFFFFu / (uint32_t)chs + 1u : 0u;
-            const uint32_t one_c = chs > 1 ? 0u : 0xFFFFFFFFu;
 #pragma unroll
             for (int i = 0; i < MAXP; ++i)
                 if (i * NT < patch_elems) {
                     bool ok = (uint32_t)(p_row[i] + frow) < (uint32_t)p.H;
-                    if (crem < p.CB) ok = ok && (int)fdiv((uint32_t)(tid + i * NT), magic_c, one_c) < crem;
+                    if (crem < p.CB) ok = ok && (int)fdiv((uint32_t)(tid + i * NT), magic_chs, one_chs) < crem;
                     lds_dma<E::BYTES>(rb, B + i * NT, ok ? p_goff[i] + (uint32_t)shift : kOobOffset);
                 }
         } else if (crem >= p.CB) {
@@ -400,7 +407,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     // ---- epilogue: bias, activation, store NKPQ ------------------------------------------------
     // The lane's NB pixels are one vector store when they lie in one image and keep the alignment.
     // A lane holds 16*MB output channels; their biases are fetched together before any store.
-    const bool vec = NB > 1 && (p.PQ % NB == 0) && (((uintptr_t)p.out & 15) == 0);
+    const bool vec = NB == 1 || ((p.PQ % NB == 0) && (((uintptr_t)p.out & 15) == 0));
     const bool full_rows = m0 + T::BM <= p.K;   // uniform: no channel of this tile is outside K
     if (cut) {
         // Every reduction part leaves its accumulator tile in scratch memory, register by register
@@ -450,43 +457,39 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+    // Addresses are a per-lane byte offset from the first image the tile touches plus a uniform
+    // offset per channel row; biases of channels at or past K (and of a missing bias vector) read
+    // as zero.
+    const int krow = m0 + wm0 + 4 * lh;   // channel of register 0; register r adds 8*(r/4) + r%4
+    const uint32_t KPQ = (uint32_t)p.K * (uint32_t)p.PQ;
+    const uint64_t o_skip = (uint64_t)img_a * KPQ * 4;
+    __amdgpu_buffer_rsrc_t ro = make_rsrc(reinterpret_cast<char *>(p.out) + o_skip, p.out_bytes - o_skip);
+    __amdgpu_buffer_rsrc_t rbias = make_rsrc(p.bias, p.bias ? (uint64_t)p.K * 4 : 0);
     float bias[MB][16];
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int k = m0 + acc_row(wm0, bi, r, lane);
-            bias[bi][r] = (p.bias && (full_rows || k < p.K)) ? p.bias[k] : 0.f;
-        }
-    if (px_img[0] >= 0) {
-        // element offset of channel 0 for the lane's first pixel; channel k adds k*PQ
-        const size_t obase = (size_t)px_img[0] * p.K * p.PQ + px_pq[0];
+        for (int r = 0; r < 16; ++r)
+            bias[bi][r] = buf_load1(rbias, (uint32_t)(krow + 32 * bi + 8 * (r >> 2) + (r & 3)) * 4u);
+    const uint32_t row_bytes = (uint32_t)p.PQ * 4u;
+    if (px_img[0] < 0) return;
+    if (vec && px_img[NB - 1] >= 0) {
+        const uint32_t off = ((uint32_t)(px_img[0] - img_a) * KPQ + (uint32_t)krow * (uint32_t)p.PQ + (uint32_t)px_pq[0]) * 4u;
+        store_rows_by<T>(p.act, full_rows, ro, off, row_bytes, acc, bias, krow, p.K);
+    } else {
 #pragma unroll
-        for (int bi = 0; bi < MB; ++bi)
+        for (int bj = 0; bj < NB; ++bj) {
+            if (px_img[bj] < 0) continue;
+            const uint32_t off = ((uint32_t)(px_img[bj] - img_a) * KPQ + (uint32_t)krow * (uint32_t)p.PQ + (uint32_t)px_pq[bj]) * 4u;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int k = m0 + acc_row(wm0, bi, r, lane);
-                if (!full_rows && k >= p.K) continue;
-                const float b = bias[bi][r];
-                float *o = p.out + obase + (size_t)k * p.PQ;
-                if (vec && px_img[NB - 1] >= 0) {
-                    if constexpr (NB == 4) {
-                        v4f v = {act_apply(acc[bi][0][r] + b, p.act), act_apply(acc[bi][1][r] + b, p.act),
-                                 act_apply(acc[bi][2][r] + b, p.act), act_apply(acc[bi][3][r] + b, p.act)};
-                        *reinterpret_cast<v4f *>(o) = v;
-                    } else if constexpr (NB == 2) {
-                        v2f v = {act_apply(acc[bi][0][r] + b, p.act), act_apply(acc[bi][1][r] + b, p.act)};
-                        *reinterpret_cast<v2f *>(o) = v;
-                    }
-                } else {
-                    o[0] = act_apply(acc[bi][0][r] + b, p.act);
+            for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-                    for (int bj = 1; bj < NB; ++bj)
-                        if (px_img[bj] >= 0)
-                            p.out[((size_t)px_img[bj] * p.K + k) * p.PQ + px_pq[bj]] =
-                                act_apply(acc[bi][bj][r] + b, p.act);
+                for (int r = 0; r < 16; ++r) {
+                    const int c = 32 * bi + 8 * (r >> 2) + (r & 3);
+                    if (krow + c >= p.K) continue;
+                    buf_store1(ro, off, (uint32_t)c * row_bytes, act_apply(acc[bi][bj][r] + bias[bi][r], p.act));
                 }
-            }
+        }
     }
 }
 
@@ -544,8 +547,13 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     a.magic_Wp = div_magic((uint32_t)a.Wp); a.one_Wp = a.Wp == 1 ? 0xFFFFFFFFu : 0u;
     a.magic_rf = div_magic((uint32_t)a.rows_full); a.one_rf = a.rows_full == 1 ? 0xFFFFFFFFu : 0u;
     a.magic_lda = div_magic((uint32_t)a.LDA);
+    a.magic_S = div_magic((uint32_t)q.S); a.one_S = q.S == 1 ? 0xFFFFFFFFu : 0u;
+    a.magic_nr = div_magic((uint32_t)a.nr); a.one_nr = a.nr == 1 ? 0xFFFFFFFFu : 0u;
+    a.recip_PQ = div_recip((uint32_t)a.PQ);
+    a.recip_Q = div_recip((uint32_t)q.Q);
     a.in_bytes = (uint64_t)q.N * a.CHW * E::BYTES;
     a.wt_bytes = (uint64_t)q.K * a.Kg * E::BYTES;
+    a.out_bytes = (uint64_t)q.N * q.K * a.PQ * 4;
     a.tiles_m = (q.K + T::BM - 1) / T::BM;
     a.tiles_n = (a.Ng + T::BN - 1) / T::BN;
     a.raster = raster;
@@ -558,16 +566,18 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
     if (split_k > a.nstages) split_k = a.nstages;
     a.stages_per_split = (a.nstages + split_k - 1) / split_k;
     a.split_k = (a.nstages + a.stages_per_split - 1) / a.stages_per_split;
+    a.recip_split = div_recip((uint32_t)a.split_k);
     if (a.split_k > 65535) return hipErrorInvalidConfiguration;
     // one stage buffer is enough when no workgroup runs more than one stage
     a.nbuf = a.stages_per_split > 1 ? 2 : 1;
     // the stage buffers and the zero unit behind them (kept a whole 64-unit row for alignment)
     const size_t lds_bytes = ((size_t)a.nbuf * ((size_t)a.a_stage + a.b_stage) + 64) * E::BYTES;
     if (lds_bytes > kMaxLdsBytes) return hipErrorInvalidConfiguration;
-    // 31-bit byte offsets: filter rows of one tile, and the images one pixel run touches
+    // 31-bit byte offsets: filter rows of one tile, and the images one pixel run touches (input and output)
     const long PQl = a.PQ;
     const long imgs = (T::BN - 1 + PQl - 1) / PQl + 1;
-    if ((long)T::BM * a.Kg * E::BYTES >= 0x7FFFFFF0l || (imgs * q.C + cb) * (long)a.HW * E::BYTES >= 0x7FFFFFF0l)
+    if ((long)T::BM * a.Kg * E::BYTES >= 0x7FFFFFF0l || (imgs * q.C + cb) * (long)a.HW * E::BYTES >= 0x7FFFFFF0l ||
+        (imgs + 1) * (long)q.K * PQl * 4 >= 0x7FFFFFF0l)
         return hipErrorInvalidConfiguration;
     if (dry) return hipSuccess;
     clear_stale_hip_error();

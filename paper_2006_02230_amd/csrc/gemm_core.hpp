@@ -16,6 +16,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "../../include/polydl.h"
 
 namespace polydl {
 
@@ -309,6 +310,60 @@ __device__ __forceinline__ void gemm_mainloop(float *lds, AL &al, BL &bl, v16f (
 __device__ __forceinline__ int acc_row(int wm0, int bi, int r, int lane)
 {
     return wm0 + 32 * bi + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+}
+
+template <int ACT>
+__device__ __forceinline__ float act_of(float v)
+{
+    if constexpr (ACT != POLYDL_ACT_NONE) v = fmaxf(v, 0.f);
+    if constexpr (ACT == POLYDL_ACT_RELU6) v = fminf(v, 6.f);
+    return v;
+}
+
+// Bias, activation and store of the lane's 16*MB channel rows, NB adjacent pixels each as one
+// vector.  `off` is the lane's byte offset of channel row `krow`; row c of the tile lies c*row_bytes
+// further, a uniform offset.  FULL: every channel row of the tile exists.
+template <class T, int ACT, bool FULL>
+__device__ __forceinline__ void store_rows(__amdgpu_buffer_rsrc_t ro, uint32_t off, uint32_t row_bytes,
+                                           const v16f (&acc)[T::MB][T::NB], const float (&bias)[T::MB][16], int krow,
+                                           int K)
+{
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int c = 32 * bi + 8 * (r >> 2) + (r & 3);
+            if (!FULL && krow + c >= K) continue;
+            const float b = bias[bi][r];
+            if constexpr (T::NB == 4) {
+                v4f v = {act_of<ACT>(acc[bi][0][r] + b), act_of<ACT>(acc[bi][1][r] + b), act_of<ACT>(acc[bi][2][r] + b),
+                         act_of<ACT>(acc[bi][3][r] + b)};
+                buf_store4(ro, off, (uint32_t)c * row_bytes, v);
+            } else if constexpr (T::NB == 2) {
+                v2f v = {act_of<ACT>(acc[bi][0][r] + b), act_of<ACT>(acc[bi][1][r] + b)};
+                buf_store2(ro, off, (uint32_t)c * row_bytes, v);
+            } else {
+                buf_store1(ro, off, (uint32_t)c * row_bytes, act_of<ACT>(acc[bi][0][r] + b));
+            }
+        }
+}
+
+// The same with the two uniform choices -- which activation, and whether every channel row of
+// the tile exists -- made once, outside the run of stores.
+template <class T>
+__device__ __forceinline__ void store_rows_by(int act, bool full, __amdgpu_buffer_rsrc_t ro, uint32_t off,
+                                              uint32_t row_bytes, const v16f (&acc)[T::MB][T::NB],
+                                              const float (&bias)[T::MB][16], int krow, int K)
+{
+    if (full) {
+        if (act == POLYDL_ACT_NONE) store_rows<T, POLYDL_ACT_NONE, true>(ro, off, row_bytes, acc, bias, krow, K);
+        else if (act == POLYDL_ACT_RELU) store_rows<T, POLYDL_ACT_RELU, true>(ro, off, row_bytes, acc, bias, krow, K);
+        else store_rows<T, POLYDL_ACT_RELU6, true>(ro, off, row_bytes, acc, bias, krow, K);
+    } else {
+        if (act == POLYDL_ACT_NONE) store_rows<T, POLYDL_ACT_NONE, false>(ro, off, row_bytes, acc, bias, krow, K);
+        else if (act == POLYDL_ACT_RELU) store_rows<T, POLYDL_ACT_RELU, false>(ro, off, row_bytes, acc, bias, krow, K);
+        else store_rows<T, POLYDL_ACT_RELU6, false>(ro, off, row_bytes, acc, bias, krow, K);
+    }
 }
 
 // Workgroup index -> tile coordinates.  raster 0: tile rows fastest.  raster 1: the hardware
