@@ -43,19 +43,38 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic, uint32_
     return __umulhi(n, magic) + (n & ones_if_d1);
 }
 
-// POINT = true: 1x1 filters without padding.  Reduction row k is channel k, every tap lies inside
-// the image, and the channel's distance from the pixel is uniform over the wave, so a load needs
-// no per-lane arithmetic at all: the lane keeps the byte offset of its pixel and the channel
-// offset rides in the instruction's uniform offset.
-template <class T, bool POINT>
+__device__ __forceinline__ uint32_t low_bits(int n) { return (uint32_t)((1ull << n) - 1ull); }   // 0 <= n <= 32
+// Bits i of 0 .. n-1 with i < lo or i >= hi (n <= 32).
+__device__ __forceinline__ uint32_t outside_bits(int lo, int hi, int n)
+{
+    lo = min(max(lo, 0), n);
+    hi = min(max(hi, 0), n);
+    return low_bits(lo) | (low_bits(n) & ~low_bits(hi));
+}
+
+// How a load finds its element and whether it lies inside the image:
+//  GATHER_ANY   any filter: per-lane row and column bit masks, offset built per lane;
+//  GATHER_POINT 1x1 filters without padding: reduction row k is channel k and every tap lies inside
+//               the image, so the lane keeps the byte offset of its pixel and the channel offset
+//               rides in the instruction's uniform offset -- no per-lane arithmetic per load;
+//  GATHER_TAPS1 / GATHER_TAPS2  filters of at most 31 / 63 taps: the lane keeps one bit per tap
+//               (set: outside the image) in one / two registers and the byte offset of tap (0,0);
+//               the tap's distance is uniform and rides in the uniform offset, so a load costs a
+//               bit extract and a merge of that bit into the top of the offset.
+enum { GATHER_ANY = 0, GATHER_POINT = 1, GATHER_TAPS1 = 2, GATHER_TAPS2 = 3 };
+
+template <class T, int MODE>
 struct BLoaderIm2col {
+    static constexpr bool POINT = MODE == GATHER_POINT;
+    static constexpr bool TAPS = MODE == GATHER_TAPS1 || MODE == GATHER_TAPS2;
+    static constexpr int LAST_BIT = MODE == GATHER_TAPS1 ? 31 : 63;   // never a tap: always set
     static constexpr int KSTEP = T::NT / T::BN;  // reduction rows covered by one pass of the workgroup
     static constexpr int ITERS = T::BK / KSTEP;
     static_assert(T::BK % KSTEP == 0, "stage depth must be a multiple of the rows loaded per pass");
     float regs[2][ITERS];
     __amdgpu_buffer_rsrc_t rsrc;
     int pix_off;      // element offset of tap (0,0), channel 0 of this pixel from the descriptor base
-    uint32_t rmask, smask;
+    uint32_t rmask, smask;   // GATHER_TAPS*: the tap bits 0-31 and 32-63
     int krow0, lds_off;
     int RS, S, HW, W;
     uint32_t magic_RS, magic_S, one_RS, one_S;
@@ -71,7 +90,11 @@ struct BLoaderIm2col {
         uint32_t rem0;
         const int img0 = (int)div_by((uint32_t)n0, (uint32_t)p.PQ, p.recip_PQ, rem0);
         const uint64_t skip = (uint64_t)img0 * p.CHW * 4;
-        rsrc = make_rsrc(reinterpret_cast<const char *>(p.in) + skip, p.in_bytes - skip);
+        // GATHER_TAPS*: per-lane offsets are those of tap (0,0), which lies up to pad rows and pad
+        // columns before the image; the descriptor starts that much earlier so that they are not
+        // negative (no load is made there: such taps are flagged outside)
+        const int lead = TAPS ? (p.pad * p.W + p.pad) * 4 : 0;
+        rsrc = make_rsrc(reinterpret_cast<const char *>(p.in) + skip - lead, p.in_bytes - skip + lead);
         const int colg = n0 + col;
         rmask = 0; smask = 0; pix_off = 0;
         if (colg < p.Ng) {
@@ -80,13 +103,26 @@ struct BLoaderIm2col {
             int op = (int)div_by(pq, (uint32_t)p.Q, p.recip_Q, oq);
             int ih0 = op * p.stride - p.pad, iw0 = (int)oq * p.stride - p.pad;
             pix_off = (img - img0) * p.CHW + ih0 * p.W + iw0;
-            if constexpr (!POINT) {
-                for (int r = 0; r < p.R; ++r)
-                    if (ih0 + r >= 0 && ih0 + r < p.H) rmask |= 1u << r;
-                for (int s = 0; s < p.S; ++s)
-                    if (iw0 + s >= 0 && iw0 + s < p.W) smask |= 1u << s;
+            // filter rows r < -ih0 or r >= H - ih0 and columns s < -iw0 or s >= W - iw0 fall outside
+            const uint32_t rows_out = outside_bits(-ih0, p.H - ih0, p.R);
+            const uint32_t cols_out = outside_bits(-iw0, p.W - iw0, p.S);
+            if constexpr (MODE == GATHER_ANY) {
+                rmask = ~rows_out;
+                smask = ~cols_out;
             }
+            if constexpr (TAPS) {
+                const uint32_t all_cols = low_bits(p.S);
+                uint64_t taps = 0;
+                for (int r = 0; r < p.R; ++r)
+                    taps |= (uint64_t)((rows_out >> r) & 1u ? all_cols : cols_out) << (r * p.S);
+                rmask = (uint32_t)taps;
+                smask = (uint32_t)(taps >> 32);
+                pix_off = pix_off * 4 + lead;
+            }
+        } else if constexpr (TAPS) {
+            rmask = 0xFFFFFFFFu; smask = 0xFFFFFFFFu;
         }
+        if constexpr (TAPS) { if (MODE == GATHER_TAPS1) rmask |= 1u << 31; else smask |= 1u << 31; }
         if constexpr (POINT) pix_off = colg < p.Ng ? pix_off * 4 : (int)kOobOffset;   // bytes, or out of range
     }
     template <int SET>
@@ -110,6 +146,15 @@ struct BLoaderIm2col {
             uint32_t r = fast_div(rs, magic_S, one_S);
             uint32_t s = rs - r * (uint32_t)S;
             int koff = (int)c * HW + (int)r * W + (int)s;
+            if constexpr (TAPS) {
+                // a row at or past kend takes the bit that is always set
+                const uint32_t t = (int)kg < kend ? rs : (uint32_t)LAST_BIT;
+                uint32_t word = rmask;
+                if constexpr (MODE == GATHER_TAPS2) word = t < 32u ? rmask : smask;
+                const uint32_t outside = (word >> (t & 31u)) & 1u;
+                regs[SET][i] = buf_load1(rsrc, (uint32_t)pix_off | (outside << 31), (uint32_t)koff * 4u);
+                continue;
+            }
             uint32_t ok = (uint32_t)((int)kg < kend) & (rmask >> r) & (smask >> s) & 1u;
             // not ok -> set the top bit: at or beyond 2^31 every descriptor reads as zero
             uint32_t off = ((uint32_t)(pix_off + koff) * 4u) | ((ok ^ 1u) << 31);
@@ -131,7 +176,7 @@ __device__ __forceinline__ float apply_act(float v, int act)
     return v;
 }
 
-template <class T, int AVEC, bool POINT>
+template <class T, int AVEC, int MODE>
 __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
 {
     __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
@@ -144,7 +189,7 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
     const int kend = min(p.Kg, kbegin + p.k_per_split);
 
     ALoader<T, AVEC> al;
-    BLoaderIm2col<T, POINT> bl;
+    BLoaderIm2col<T, MODE> bl;
     al.init(p.wt, tid, m0, p.K, p.Kg, p.Kg);
     bl.init(p, tid, n0);
 
@@ -286,11 +331,21 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     }
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
-    const bool point = q.R == 1 && q.S == 1 && q.pad == 0;
-    if (avec && point) hipLaunchKernelGGL((conv_kernel<T, 4, true>), grid, block, 0, stream, a);
-    else if (avec) hipLaunchKernelGGL((conv_kernel<T, 4, false>), grid, block, 0, stream, a);
-    else if (point) hipLaunchKernelGGL((conv_kernel<T, 1, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((conv_kernel<T, 1, false>), grid, block, 0, stream, a);
+    const int mode = (q.R == 1 && q.S == 1 && q.pad == 0) ? GATHER_POINT
+                     : a.RS <= 31 ? GATHER_TAPS1 : a.RS <= 63 ? GATHER_TAPS2 : GATHER_ANY;
+#define POLYDL_GO(AV, MODE) hipLaunchKernelGGL((conv_kernel<T, AV, MODE>), grid, block, 0, stream, a)
+    if (avec) {
+        if (mode == GATHER_POINT) POLYDL_GO(4, GATHER_POINT);
+        else if (mode == GATHER_TAPS1) POLYDL_GO(4, GATHER_TAPS1);
+        else if (mode == GATHER_TAPS2) POLYDL_GO(4, GATHER_TAPS2);
+        else POLYDL_GO(4, GATHER_ANY);
+    } else {
+        if (mode == GATHER_POINT) POLYDL_GO(1, GATHER_POINT);
+        else if (mode == GATHER_TAPS1) POLYDL_GO(1, GATHER_TAPS1);
+        else if (mode == GATHER_TAPS2) POLYDL_GO(1, GATHER_TAPS2);
+        else POLYDL_GO(1, GATHER_ANY);
+    }
+#undef POLYDL_GO
     return hipGetLastError();
 }
 
