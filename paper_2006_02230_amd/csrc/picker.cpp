@@ -186,7 +186,7 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
     double fixed = c.kernel_fixed_us;
     if (c.rounds) {
         // nothing streams the tensors faster than this, with the first and last touches exposed
-        mem_us = std::max(mem_us, (s.a_bytes + s.b_bytes + s.d_bytes) / 4000.0 * 1e-3 + 3.0);
+        mem_us = std::max(mem_us, (s.a_bytes + s.b_bytes + s.d_bytes) / 5500.0 * 1e-3 + 2.0);
         if (c.split_k > 1) fixed += c.split_c0 + c.split_c1 * c.split_k * s.d_bytes * 1e-6;
     } else if (c.split_k > 1) {
         // every part writes its accumulator tile once, coalesced; the last part of each tile reads
@@ -268,11 +268,10 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         const int rc = reg_class < 0 ? 0 : reg_class;
         c.rounds = true;
         c.kernel_fixed_us = 5.0;
-        if (mbn == 11)      { static const int R[3] = {190, 80, 60};   c.regs = R[rc]; c.eff_sat = 0.65; c.t_lat_us = 0.8; c.t_round_us = 10; }
-        else if (mbn == 21) { static const int R[3] = {190, 121, 106}; c.regs = R[rc]; c.eff_sat = 0.65; c.t_lat_us = 0.8; c.t_round_us = 12; }
-        else                { static const int R[3] = {210, 155, 140}; c.regs = R[rc]; c.eff_sat = 0.65; c.t_lat_us = 0.8; c.t_round_us = 18; }
-        if (cfg.bm == 128 && cfg.bn == 64) { static const int R[3] = {190, 100, 89}; c.regs = R[rc]; }
-        c.split_c0 = 0; c.split_c1 = 0.1;
+        if (mbn == 11)      { static const int R[3] = {192, 80, 60};   c.regs = R[rc]; c.eff_sat = 0.65; c.t_lat_us = 0.8; c.t_round_us = 6; }
+        else if (mbn == 21) { static const int R[3] = {215, 110, 89};  c.regs = R[rc]; c.eff_sat = 0.60; c.t_lat_us = 0.6; c.t_round_us = 6; }
+        else                { static const int R[3] = {247, 156, 121}; c.regs = R[rc]; c.eff_sat = 0.75; c.t_lat_us = 0.6; c.t_round_us = 6; c.split_c0 = 4; }
+        c.split_c1 = 0.1;
     } else {
         c.steps_per_stage = cfg.bk / 2.0;
         c.lds_bytes = 2.0 * (cfg.bm * (cfg.bk + 4) + cfg.bk * (cfg.bn + 4)) * 4;
@@ -281,20 +280,21 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         c.kernel_fixed_us = 10.0;
         c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 1 : ((cfg.wm * cfg.wn == 64 * 64) ? 2 : 4);
         const int mbn = (cfg.wm / 32) * 10 + cfg.wn / 32;
-        const bool contiguous = q.R == 1 && q.S == 1 && q.stride == 1;   // im2col columns are input rows
+        const bool point = q.R == 1 && q.S == 1 && q.pad == 0;   // loads without per-lane arithmetic
         c.rounds = true;
         c.kernel_fixed_us = 5.0;
         c.gather_elems = (double)cfg.bk * cfg.bn / threads;
         switch (mbn) {
-        case 11: c.regs = 70;  c.eff_sat = 0.70; c.t_lat_us = 0.6; c.t_round_us = 6;  c.gather_cycles = 40; break;
-        case 12: c.regs = 110; c.eff_sat = 0.65; c.t_lat_us = 1.0; c.t_round_us = 6;  c.gather_cycles = 20; break;
-        case 21: c.regs = 95;  c.eff_sat = 0.70; c.t_lat_us = 0.8; c.t_round_us = 8;  c.gather_cycles = 0;  break;
-        case 22: c.regs = cfg.bk == 16 ? 150 : 115; c.eff_sat = 0.60; c.t_lat_us = 0.8; c.t_round_us = 6; c.gather_cycles = 0; break;
-        case 24: c.regs = 215; c.eff_sat = 0.65; c.t_lat_us = 0.4; c.t_round_us = 10; c.gather_cycles = 20;  break;
-        default: c.regs = 240; c.eff_sat = 0.90; c.t_lat_us = 0.4; c.t_round_us = 16; c.gather_cycles = 160; break;
+        case 11: c.regs = 62;  c.eff_sat = 0.80; c.t_lat_us = 0.6; c.gather_cycles = 20; c.split_c0 = 2; break;
+        case 12: c.regs = 90;  c.eff_sat = 0.85; c.t_lat_us = 1.0; c.gather_cycles = 60; c.split_c0 = 2; break;
+        case 21: c.regs = 88;  c.eff_sat = 0.80; c.t_lat_us = 0.8; c.gather_cycles = 20; break;
+        case 22: c.regs = cfg.bk == 16 ? 136 : 104; c.eff_sat = 0.75; c.t_lat_us = 0.8; c.gather_cycles = 20; c.split_c0 = 10; break;
+        case 24: c.regs = 212; c.eff_sat = 0.70; c.t_lat_us = 0.4; c.gather_cycles = 20; break;
+        default: c.regs = 228; c.eff_sat = 0.75; c.t_lat_us = 0.4; c.gather_cycles = 0;  break;
         }
-        if (contiguous) c.gather_cycles *= 0.3;
-        c.split_c0 = 0; c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
+        c.t_round_us = 2;
+        if (point) c.gather_cycles *= 0.1;
+        c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
     }
     Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
     model(s, c, r);
