@@ -188,6 +188,14 @@ int polydl_model_sgemm(int M, int N, int K, const polydl_tile_cfg *cfg, polydl_m
 int polydl_pick_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                        polydl_tile_cfg *cfg, polydl_model_report *report);
 int polydl_pick_sgemm(int M, int N, int K, polydl_tile_cfg *cfg, polydl_model_report *report);
+/* The same two for the bfloat16 convolution (C counts channels; cfg is an algo 1 variant with its
+ * cb and split_k set): the predicted time in microseconds of one variant, and the variant
+ * polydl_conv2d_fwd_bf16_blocked uses when no override is set.  predicted_us may be NULL in the
+ * pick.  POLYDL_ERR_UNSUPPORTED for a variant that is not compiled or cannot hold the problem. */
+int polydl_model_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             const polydl_tile_cfg *cfg, double *predicted_us);
+int polydl_pick_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            polydl_tile_cfg *cfg, double *predicted_us);
 
 /* ---- variant control (the sweep forces a variant; reports read back the one used) -----------
  * polydl_set_tile_override: cfg != NULL forces that variant for every later call of the

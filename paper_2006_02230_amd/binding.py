@@ -61,6 +61,10 @@ lib.polydl_conv2d_fwd_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_sgemm.argtypes = [_i, _i, _i, _p, _p, _p, _p]
 lib.polydl_sgemm_ex.argtypes = [_i, _i, _i, ctypes.c_float, _p, _p, ctypes.c_float, _p, _p]
 lib.polydl_sgemm_ex.restype = _i
+lib.polydl_model_conv2d_bf16.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ctypes.c_double)]
+lib.polydl_pick_conv2d_bf16.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ctypes.c_double)]
+lib.polydl_model_conv2d_bf16.restype = _i
+lib.polydl_pick_conv2d_bf16.restype = _i
 lib.polydl_nchw_to_nchwc.argtypes = [_i] * 5 + [_p, _p, _p]
 lib.polydl_nchwc_to_nchw.argtypes = [_i] * 5 + [_p, _p, _p]
 lib.polydl_kcrs_to_kcrsck.argtypes = [_i] * 6 + [_p, _p, _p]
@@ -326,6 +330,22 @@ def pick_conv2d(shape):
     _check(lib.polydl_pick_conv2d(*[int(v) for v in shape], ctypes.byref(cfg), ctypes.byref(rep)),
            "polydl_pick_conv2d")
     return cfg, rep
+
+
+def model_conv2d_bf16(shape, cfg):
+    """polydl_model_conv2d_bf16: predicted microseconds of one bfloat16 variant (algo 1, cb and split_k set)."""
+    us = ctypes.c_double(0.0)
+    _check(lib.polydl_model_conv2d_bf16(*[int(v) for v in shape], ctypes.byref(cfg), ctypes.byref(us)),
+           "polydl_model_conv2d_bf16")
+    return us.value
+
+
+def pick_conv2d_bf16(shape):
+    """polydl_pick_conv2d_bf16: (TileCfg, predicted microseconds) of the bfloat16 variant ranked first."""
+    cfg, us = TileCfg(), ctypes.c_double(0.0)
+    _check(lib.polydl_pick_conv2d_bf16(*[int(v) for v in shape], ctypes.byref(cfg), ctypes.byref(us)),
+           "polydl_pick_conv2d_bf16")
+    return cfg, us.value
 
 
 def pick_sgemm(M, N, K):

@@ -474,6 +474,52 @@ int polydl_pick_conv2d(int N, int C, int H, int W, int K, int R, int S, int stri
     return POLYDL_OK;
 }
 
+// C is the channel count of the bfloat16 tensors; the kernels see blocks of eight channels.
+static bool bf16_problem(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, ConvProblem *q, int *status)
+{
+    int64_t P, Q;
+    if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) { *status = POLYDL_ERR_BAD_DIMENSION; return false; }
+    if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) { *status = POLYDL_ERR_UNSUPPORTED; return false; }
+    *q = ConvProblem{N, (C + 7) / 8, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
+    return true;
+}
+
+int polydl_model_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             const polydl_tile_cfg *cfg, double *predicted_us)
+{
+    ConvProblem q;
+    int st = POLYDL_OK;
+    if (!bf16_problem(N, C, H, W, K, R, S, stride, pad, &q, &st)) return st;
+    if (!cfg || !predicted_us) return POLYDL_ERR_NULL_POINTER;
+    for (int i = 0; i < kNumPatchBf16Variants; ++i) {
+        const PatchVariant &v = kPatchBf16Variants[i];
+        if (v.bm != cfg->bm || v.bn != cfg->bn || v.wm != cfg->wm || v.wn != cfg->wn) continue;
+        if (cfg->cb < 2 || (cfg->cb & 1) || cfg->split_k < 1) return POLYDL_ERR_UNSUPPORTED;
+        if (v.conv(q, cfg->cb, cfg->split_k, 0, nullptr, true) != hipSuccess) return POLYDL_ERR_UNSUPPORTED;
+        *predicted_us = model_conv_bf16(q, *cfg, v.threads);
+        return POLYDL_OK;
+    }
+    return POLYDL_ERR_UNSUPPORTED;
+}
+
+int polydl_pick_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            polydl_tile_cfg *cfg, double *predicted_us)
+{
+    ConvProblem q;
+    int st = POLYDL_OK;
+    if (!bf16_problem(N, C, H, W, K, R, S, stride, pad, &q, &st)) return st;
+    if (!cfg) return POLYDL_ERR_NULL_POINTER;
+    if (!pick_bf16(q, cfg)) return POLYDL_ERR_UNSUPPORTED;
+    if (predicted_us) {
+        for (int i = 0; i < kNumPatchBf16Variants; ++i) {
+            const PatchVariant &v = kPatchBf16Variants[i];
+            if (v.bm == cfg->bm && v.bn == cfg->bn && v.wm == cfg->wm && v.wn == cfg->wn)
+                *predicted_us = model_conv_bf16(q, *cfg, v.threads);
+        }
+    }
+    return POLYDL_OK;
+}
+
 int polydl_pick_sgemm(int M, int N, int K, polydl_tile_cfg *cfg, polydl_model_report *report)
 {
     if (M <= 0 || N <= 0 || K <= 0) return POLYDL_ERR_BAD_DIMENSION;

@@ -317,16 +317,20 @@ double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int thr
     const double per_split = std::ceil(nstages / std::max(1, cfg.split_k));
     const double parts = std::ceil(nstages / per_split);
     const double wp = q.S == 1 ? q.Q : q.W + 2 * q.pad;
-    const double stage_units = cfg.bm * (cb * RSp + 1) + cb * conv_patch_rows(q, cfg.bn) * wp;
-    const double lds_bytes = (per_split > 1 ? 2.0 : 1.0) * stage_units * 16;
-    const int waves_per_simd = mb * nb == 1 ? 6 : (mb * nb == 2 ? 4 : 2);
+    // the kernel's stage buffers: filter rows of odd pitch, both operands rounded up to whole
+    // passes of the workgroup
+    const double lda = (double)(((int)(cb * RSp) + 1) | 1);
+    const double stage_units = std::ceil(cfg.bm * lda / threads) * threads +
+                               std::ceil(cb * conv_patch_rows(q, cfg.bn) * wp / threads) * threads;
+    const double lds_bytes = ((per_split > 1 ? 2.0 : 1.0) * stage_units + 64) * 16;
+    const int waves_per_simd = mb * nb == 4 ? 3 : 4;   // from the kernels' register counts
     const double occ = std::max(1.0, std::min(std::floor(waves_per_simd * kSimdsPerCU / waves_per_wg),
                                               std::floor(160.0 * 1024 / lds_bytes)));
     // per wave tile: stage efficiency, per-round latency, stage latency floor, bytes per microsecond a
     // CU stages into LDS, split cost per MB of parts
-    double eff = 0.3, t_round = 6.0, t_lat = 0.8, rate = 60000.0, c1 = 0.1;
-    if (mb * nb == 2) { eff = 0.4; t_round = 8.0; c1 = 0.2; }
-    else if (mb * nb == 4) { t_lat = 0.4; rate = 31000.0; c1 = 0.4; }
+    double eff = 0.25, t_round = 3.0, t_lat = 0.8, rate = 60000.0, c1 = 0.1;
+    if (mb * nb == 2) { eff = 0.4; t_round = 4.0; c1 = 0.2; }
+    else if (mb * nb == 4) { eff = 0.4; t_round = 4.0; t_lat = 0.4; rate = 31000.0; c1 = 0.4; }
     const double t_stage = std::max(std::ceil(cb / 2.0) * RSp * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
                                         kClockHz * 1e6 / eff,
                                     (cfg.bm * cb * RSp + cb * conv_patch_rows(q, cfg.bn) * wp) * 16.0 / rate);
@@ -336,7 +340,7 @@ double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int thr
     double t = full_rounds * round_us(occ) + (rest > 1e-9 ? round_us(std::ceil(rest - 1e-9)) : 0.0);
     const double d_bytes = (double)q.N * q.K * q.P * q.Q * 4;
     const double mem_bytes = (double)q.N * q.C * 8 * q.H * q.W * 2 + (double)q.K * q.C * 8 * RS * 2 + d_bytes;
-    t = 5.0 + std::max(t, mem_bytes / 4000.0 * 1e-3 + 3.0);
+    t = 5.0 + std::max(t, mem_bytes / 6000.0 * 1e-3 + 2.0);
     if (parts > 1) t += c1 * parts * d_bytes * 1e-6;
     return t;
 }
