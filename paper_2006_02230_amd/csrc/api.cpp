@@ -143,6 +143,7 @@ static int sgemm_impl(int M, int N, int K, float alpha, const float *A, const fl
     // 32-bit byte offsets inside one workgroup's slice of A (bm rows) and of B (bk rows)
     if ((uint64_t)v->bm * (uint64_t)K * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;
     if ((uint64_t)v->bk * (uint64_t)N * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;
+    if ((uint64_t)v->bm * (uint64_t)N * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;   // and of C (bm rows)
     uint64_t tiles = (uint64_t)((M + v->bm - 1) / v->bm) * (uint64_t)((N + v->bn - 1) / v->bn);
     if (tiles >= 0x7FFFFFFFull || cfg.split_k > 65535) return POLYDL_ERR_UNSUPPORTED;
     SgemmProblem q{M, N, K, A, B, C, alpha, beta};

@@ -3,6 +3,7 @@
 #include "gemm_core.hpp"
 #include "internal.hpp"
 #include "variants.hpp"
+#include <type_traits>
 
 namespace polydl {
 
@@ -91,38 +92,51 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // epilogue: C = beta*C + alpha*acc (alpha = beta = 1 rounds exactly like C += acc)
+    // epilogue: C = beta*C + alpha*acc (alpha = beta = 1 rounds exactly like C += acc).  C is
+    // addressed by a per-lane byte offset of the lane's first row and column inside the tile's row
+    // panel plus a uniform offset per accumulator row, so a row costs no address arithmetic.
     const int col = n0 + wn0 + T::NB * (lane & 31);
+    if (col >= p.N) return;
+    const int krow = wm0 + 4 * (lane >> 5);   // row inside the tile of register 0; register r adds 8*(r/4) + r%4
+    const uint64_t panel = (uint64_t)m0 * p.N * 4;
+    __amdgpu_buffer_rsrc_t rc = make_rsrc(reinterpret_cast<char *>(p.C) + panel, (uint64_t)p.M * p.N * 4 - panel);
+    const uint32_t off = ((uint32_t)krow * (uint32_t)p.N + (uint32_t)col) * 4u;
+    const uint32_t row_bytes = (uint32_t)p.N * 4u;
     const float alpha = p.alpha, beta = p.beta;
-    const bool readc = beta != 0.f;
+    const bool readc = beta != 0.f;              // uniform
+    const bool full = m0 + T::BM <= p.M;         // uniform: every row of the tile exists
+    auto rows = [&](auto full_tag) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-    for (int bi = 0; bi < T::MB; ++bi)
+        for (int bi = 0; bi < T::MB; ++bi)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int row = m0 + acc_row(wm0, bi, r, lane);
-            if (row >= p.M) continue;
-            float *c = p.C + (size_t)row * p.N + col;
-            if (CVEC && T::NB == 4) {
-                if (col < p.N) {
+            for (int r = 0; r < 16; ++r) {
+                const int c = 32 * bi + 8 * (r >> 2) + (r & 3);
+                if (!FULL && m0 + krow + c >= p.M) continue;
+                const uint32_t uo = (uint32_t)c * row_bytes;
+                if constexpr (CVEC && T::NB == 4) {
                     v4f v = {0.f, 0.f, 0.f, 0.f};
-                    if (readc) v = *reinterpret_cast<v4f *>(c);
+                    if (readc) v = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rc, (int)off, (int)uo, 0));
                     v.x = beta * v.x + alpha * acc[bi][0][r]; v.y = beta * v.y + alpha * acc[bi][1][r];
                     v.z = beta * v.z + alpha * acc[bi][2][r]; v.w = beta * v.w + alpha * acc[bi][3][r];
-                    *reinterpret_cast<v4f *>(c) = v;
-                }
-            } else if (CVEC && T::NB == 2) {
-                if (col < p.N) {
+                    buf_store4(rc, off, uo, v);
+                } else if constexpr (CVEC && T::NB == 2) {
                     v2f v = {0.f, 0.f};
-                    if (readc) v = *reinterpret_cast<v2f *>(c);
+                    if (readc) v = __builtin_bit_cast(v2f, __builtin_amdgcn_raw_buffer_load_b64(rc, (int)off, (int)uo, 0));
                     v.x = beta * v.x + alpha * acc[bi][0][r]; v.y = beta * v.y + alpha * acc[bi][1][r];
-                    *reinterpret_cast<v2f *>(c) = v;
-                }
-            } else {
+                    buf_store2(rc, off, uo, v);
+                } else {
 #pragma unroll
-                for (int bj = 0; bj < T::NB; ++bj)
-                    if (col + bj < p.N) c[bj] = beta * (readc ? c[bj] : 0.f) + alpha * acc[bi][bj][r];
+                    for (int bj = 0; bj < T::NB; ++bj)
+                        if (col + bj < p.N) {
+                            const float c0 = readc ? buf_load1(rc, off + 4u * bj, uo) : 0.f;
+                            buf_store1(rc, off + 4u * bj, uo, beta * c0 + alpha * acc[bi][bj][r]);
+                        }
+                }
             }
-        }
+    };
+    if (full) rows(std::true_type{});
+    else rows(std::false_type{});
 }
 
 template <class T>
