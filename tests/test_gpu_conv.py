@@ -218,6 +218,41 @@ def test_filter_row_staging(P, s):
     P.set_tile_override(None)
 
 
+GATHER_MODES = [
+    synth.ConvShape("taps1_pad1x1", 2, 8, 6, 6, 16, 1, 1, 1, 1),      # one tap, but padded: not the 1x1 fast path
+    synth.ConvShape("taps1_31", 1, 2, 12, 40, 8, 1, 31, 1, 15),       # 31 taps: the most one register of tap bits holds
+    synth.ConvShape("taps2_32", 1, 2, 12, 40, 8, 1, 32, 1, 16),       # 32 taps: first size with two registers
+    synth.ConvShape("taps2_63", 1, 2, 30, 30, 8, 7, 9, 1, 3),         # 63 taps: the most two registers hold
+    synth.ConvShape("masks_64", 1, 2, 30, 30, 8, 8, 8, 1, 3),         # 64 taps: row and column masks
+    synth.ConvShape("masks_81s2", 2, 3, 21, 21, 16, 9, 9, 2, 4),
+]
+
+
+@pytest.mark.parametrize("s", GATHER_MODES, ids=lambda s: s.name)
+def test_gather_addressing_modes(P, s):
+    # the gather kernel decides tap validity in one of several ways depending on the filter size;
+    # every way, on every tile, with the reduction whole and split
+    x, w, b = synth.conv_inputs(s, seed=41, dist="normal", bias=True)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu6")
+    xi, wi, bi = synth.conv_inputs(s, seed=42, dist="ints", bias=True)
+    want_i, _ = oracle.conv2d_fwd(xi, wi, bias=bi, stride=s.stride, pad=s.pad)
+    ran = 0
+    for v in P.variants(0):
+        if v.algo != 0:
+            continue
+        for split_k in (1, 3):
+            v.split_k = split_k
+            got = try_variant(P, v, s, x, w, b, act="relu6")
+            if got is None:
+                continue
+            assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (v, split_k)
+            got_i = try_variant(P, v, s, xi, wi, bi)
+            assert np.array_equal(got_i.astype(np.float64), want_i), (v, split_k)
+            ran += 1
+    assert ran > 0
+    P.set_tile_override(None)
+
+
 def test_argument_errors(P):
     import ctypes
     z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)

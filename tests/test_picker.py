@@ -125,6 +125,24 @@ def test_sgemm_pick_valid():
         assert rep.predicted_us > 0
 
 
+def test_bf16_pick_is_a_compiled_variant_and_the_model_agrees():
+    for s in synth.RESNET50_SUITE(64):
+        shape = tuple(s)[1:]
+        cfg, us = P.pick_conv2d_bf16(shape)
+        assert cfg.algo == 1 and cfg.cb >= 2 and cfg.cb % 2 == 0 and cfg.split_k >= 1 and us > 0
+        assert P.model_conv2d_bf16(shape, cfg) == pytest.approx(us)
+        # no variant of the family with the same stage depth is predicted faster
+        for bm, bn, wm, wn in ((64, 64, 32, 32), (64, 128, 64, 32), (128, 64, 64, 32), (128, 128, 64, 64)):
+            try:
+                other = P.model_conv2d_bf16(shape, P.TileCfg(bm, bn, 0, wm, wn, cfg.split_k, 1, 0, 1, cfg.cb))
+            except P.PolydlError:
+                continue
+            assert other >= us * 0.998
+    import ctypes
+    assert P.lib.polydl_pick_conv2d_bf16(1, 1, 2, 2, 1, 3, 3, 1, 0, ctypes.byref(P.TileCfg()), None) == -2
+    assert P.lib.polydl_model_conv2d_bf16(1, 8, 4, 4, 1, 3, 3, 1, 1, None, None) == -1
+
+
 def test_argument_errors():
     import ctypes
     cfg, rep = P.TileCfg(), P.ModelReport()
