@@ -75,8 +75,9 @@ def time_calls(torch, fn, reps, batches=3):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps first; about 50 ms of them bring the clocks to their steady state")
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--sweep", action="store_true", help="also time every compiled variant per layer")
     ap.add_argument("--sweep-out", default="", help="with --sweep: write every candidate's time to this JSON file")

@@ -59,7 +59,11 @@ typedef struct polydl_tile_cfg {
     int wm, wn;       /* wave tile (multiples of 32); the workgroup has (bm/wm)*(bn/wn) waves  */
     int split_k;      /* >= 1: the reduction is cut into this many parts (one workgroup each);  */
     int layout;       /* 0: read NCHW / KCRS directly; 1: via blocked NCHWc / KCRSck copies    */
-    int raster;       /* 0: workgroups walk M fastest; 1: chunked per XCD, grouped for L2 reuse */
+    int raster;       /* 0: workgroups walk M fastest; 1: chunked per XCD, grouped for L2 reuse;
+                         2 (convolution, algo 0, split_k 1): order 0, and when the tile count
+                         leaves a last round of workgroups that at most half of the compute units
+                         take part in, each tile of that round is cut into parts along the
+                         reduction (summed through scratch tiles in a fixed order) */
     int algo;         /* convolution only.  0: im2col columns gathered element by element from
                          HBM (any shape); 1: input rows staged once per workgroup in LDS and the
                          taps formed on the LDS read (bk is ignored, the stage is cb channels)  */

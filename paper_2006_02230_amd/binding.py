@@ -376,6 +376,8 @@ def conv_candidates(shape):
                 if sk > stages:
                     break
                 out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0))
+                if sk == 1 and v.wm * v.wn <= 64 * 32:
+                    out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, 1, 0, 2, 0, 0))   # leftover tiles split
     return out
 
 

@@ -26,6 +26,10 @@ struct ConvKArgs {
     uint64_t in_bytes, out_bytes;
     int tiles_m, tiles_n;
     int split_k, k_per_split;
+    // tail_parts > 1: one-dimensional grid; the first whole_tiles tiles run their reduction whole,
+    // each later tile in tail_parts parts of tail_k reduction elements
+    int whole_tiles, tail_parts, tail_k;
+    uint32_t recip_tail;
     int raster, act;
     float *partials;            // split_k > 1: [tile][part][BM*BN] accumulator tiles in register order
     unsigned *counters;         // split_k > 1: per tile, how many of its reduction parts have finished
@@ -182,11 +186,21 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
     __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int tm, tn;
-    tile_coords(blockIdx.x, p.raster, p.tiles_m, p.tiles_n, tm, tn);
+    // which tile, and which part of its reduction (uniform)
+    int tile = blockIdx.x, part = blockIdx.y, parts = p.split_k, kps = p.k_per_split, first_split_tile = 0;
+    if (p.tail_parts > 1) {
+        part = 0; parts = 1; first_split_tile = p.whole_tiles;
+        if (tile >= p.whole_tiles) {
+            uint32_t rem;
+            tile = p.whole_tiles + (int)div_by((uint32_t)(tile - p.whole_tiles), (uint32_t)p.tail_parts, p.recip_tail, rem);
+            part = (int)rem; parts = p.tail_parts; kps = p.tail_k;
+        }
+    }
+    tile_coords(tile, p.raster, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int wm0 = (wave % T::WAVES_M) * T::WM, wn0 = (wave / T::WAVES_M) * T::WN;
-    const int kbegin = blockIdx.y * p.k_per_split;
-    const int kend = min(p.Kg, kbegin + p.k_per_split);
+    const int kbegin = part * kps;
+    const int kend = min(p.Kg, kbegin + kps);
 
     ALoader<T, AVEC> al;
     BLoaderIm2col<T, MODE> bl;
@@ -203,15 +217,16 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
 
     gemm_mainloop<T>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
 
-    // With the reduction split over blockIdx.y every part leaves its accumulator tile in scratch
+    // With the reduction of a tile split over several workgroups every part leaves its accumulator tile in scratch
     // memory (thread-contiguous, device-scope stores); the part that arrives last adds all parts
     // in index order and runs the fused epilogue.  Nothing waits on another workgroup.
-    if (p.split_k > 1) {
+    if (parts > 1) {
         __shared__ unsigned s_arrived;
         constexpr size_t TILE = (size_t)T::BM * T::BN;
         constexpr int NT = T::NT;
-        float *tile0 = p.partials + (size_t)blockIdx.x * p.split_k * TILE;
-        float *mine = tile0 + (size_t)blockIdx.y * TILE;
+        const int slot = tile - first_split_tile;   // scratch tiles and counters are numbered over the split tiles
+        float *tile0 = p.partials + (size_t)slot * parts * TILE;
+        float *mine = tile0 + (size_t)part * TILE;
 #pragma unroll
         for (int bi = 0; bi < T::MB; ++bi)
 #pragma unroll
@@ -223,18 +238,18 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's device-scope stores have completed
         __syncthreads();
         if (tid == 0)
-            s_arrived = __hip_atomic_fetch_add(p.counters + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_arrived = __hip_atomic_fetch_add(p.counters + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
-        if (__builtin_amdgcn_readfirstlane(s_arrived) != (unsigned)p.split_k - 1u) return;   // not the last part
+        if (__builtin_amdgcn_readfirstlane(s_arrived) != (unsigned)parts - 1u) return;   // not the last part
         if (tid == 0)               // leave the counter at zero for the next launch
-            __hip_atomic_store(p.counters + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.counters + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int bi = 0; bi < T::MB; ++bi)
 #pragma unroll
             for (int bj = 0; bj < T::NB; ++bj)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
-        for (int sp = 0; sp < p.split_k; ++sp) {
+        for (int sp = 0; sp < parts; ++sp) {
             const float *part = tile0 + (size_t)sp * TILE;
 #pragma unroll
             for (int bi = 0; bi < T::MB; ++bi)
@@ -319,17 +334,32 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     int stages_per = (stages + split_k - 1) / split_k;
     a.k_per_split = stages_per * T::BK;
     a.split_k = (stages + stages_per - 1) / stages_per;
-    a.raster = raster;
+    const bool tail = raster == 2;   // tile order of raster 0, leftover tiles split
+    a.raster = tail ? 0 : raster;
     a.act = q.act;
     a.partials = nullptr;
     a.counters = nullptr;
     clear_stale_hip_error();
+    const int tiles = a.tiles_m * a.tiles_n;
+    a.whole_tiles = tiles; a.tail_parts = 1; a.tail_k = a.k_per_split; a.recip_tail = 0;
+    dim3 grid((unsigned)tiles, (unsigned)a.split_k), block(T::NT);
     if (a.split_k > 1) {
-        const size_t bytes = (size_t)a.tiles_m * a.tiles_n * a.split_k * T::BM * T::BN * sizeof(float);
-        hipError_t e = splitk_scratch(stream, bytes, a.tiles_m * a.tiles_n, &a.partials, &a.counters);
+        const size_t bytes = (size_t)tiles * a.split_k * T::BM * T::BN * sizeof(float);
+        hipError_t e = splitk_scratch(stream, bytes, tiles, &a.partials, &a.counters);
         if (e != hipSuccess) return e;
+    } else {
+        // raster 2: an unsplit grid whose last round would leave most compute units idle has the
+        // tiles of that round split
+        const TailSplit ts = tail ? tail_split(tiles, stages, compute_units()) : TailSplit{0, 1, stages};
+        if (ts.parts > 1) {
+            a.whole_tiles = tiles - ts.tiles; a.tail_parts = ts.parts; a.tail_k = ts.stages_per_part * T::BK;
+            a.recip_tail = div_recip((uint32_t)ts.parts);
+            const size_t bytes = (size_t)ts.tiles * ts.parts * T::BM * T::BN * sizeof(float);
+            hipError_t e = splitk_scratch(stream, bytes, ts.tiles, &a.partials, &a.counters);
+            if (e != hipSuccess) return e;
+            grid = dim3((unsigned)(a.whole_tiles + ts.tiles * ts.parts), 1u);
+        }
     }
-    dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)a.split_k), block(T::NT);
     const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
     const int mode = (q.R == 1 && q.S == 1 && q.pad == 0) ? GATHER_POINT
                      : a.RS <= 31 ? GATHER_TAPS1 : a.RS <= 63 ? GATHER_TAPS2 : GATHER_ANY;

@@ -70,6 +70,28 @@ hipError_t launch_bnorm_act(const float *x, float *y, const float *gamma, const 
 // scratch.cpp: partial-tile buffer (>= partial_bytes) and zeroed arrival counters (>= tiles) for
 // split-reduction launches on this device and stream
 hipError_t splitk_scratch(hipStream_t stream, size_t partial_bytes, int tiles, float **partials, unsigned **counters);
+int compute_units();   // of the current device
+
+// Workgroups of one launch are all resident at once or run in rounds; either way a compute unit
+// takes a whole number of them, so `tiles % cus` leftover tiles make one more round that most
+// compute units sit out.  When those leftovers would occupy at most half of the compute units,
+// the gather kernel cuts each of them into `parts` pieces along the reduction (one workgroup
+// each, summed through scratch tiles like any split reduction), so that the last round is short
+// for everyone.  parts == 1: no tail split.
+struct TailSplit { int tiles, parts, stages_per_part; };
+inline TailSplit tail_split(int tiles, int stages, int cus)
+{
+    TailSplit t{0, 1, stages};
+    const int rem = tiles % cus;
+    if (tiles <= cus || rem == 0 || rem * 2 > cus || stages < 2) return t;
+    int want = cus / rem;
+    if (want > stages) want = stages;
+    if (want < 2) return t;
+    t.stages_per_part = (stages + want - 1) / want;
+    t.parts = (stages + t.stages_per_part - 1) / t.stages_per_part;
+    t.tiles = t.parts > 1 ? rem : 0;
+    return t;
+}
 
 // hipGetLastError() reports the last error of any HIP call of this thread, including benign ones
 // left by the caller (an event query that was not ready, say).  Launchers clear that state first

@@ -101,6 +101,7 @@ struct Cand {
     double gather_elems = 0;     // B elements a thread gathers per stage (im2col addressing in the ALUs)
     double gather_cycles = 0;    // cycles of that addressing per element
     double split_c0 = 0, split_c1 = 0;   // split reduction: microseconds, and microseconds per MB of parts
+    bool tail_split = false;     // the kernel cuts the leftover tiles of an unsplit grid (tail_split())
 };
 
 // Constants below were fitted to an exhaustive sweep of the compiled family on the ResNet-50-shaped
@@ -142,7 +143,21 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
         const double by_regs = std::floor(waves_per_simd * kSimdsPerCU / waves_per_wg);
         const double by_lds = std::floor(160.0 * 1024 / c.lds_bytes);
         const double occ = std::max(1.0, std::min(by_regs, by_lds));
-        const double per_cu = wgs / kCUs;
+        double per_cu = wgs / kCUs;
+        const double stages_all = std::ceil(steps / c.steps_per_stage);
+        // leftover tiles cut into pieces: whole tiles are dealt evenly, the pieces make a short tail
+        double tail_us = 0;
+        if (c.tail_split && c.split_k == 1 && wgs < 2e9) {
+            const TailSplit ts = tail_split((int)wgs, (int)stages_all, kCUs);
+            if (ts.parts > 1) {
+                per_cu = (wgs - ts.tiles) / kCUs;
+                const double pieces = std::ceil((double)ts.tiles * ts.parts / kCUs);
+                const double simd_share0 = std::ceil(waves_per_wg / kSimdsPerCU);
+                tail_us = 4.0 + pieces * ts.stages_per_part *
+                                    (c.steps_per_stage * mb * nb * 64.0 * simd_share0 / kClockHz * 1e6 / c.eff_sat +
+                                     c.gather_elems * c.gather_cycles / kClockHz * 1e6);
+            }
+        }
         const double full_rounds = std::floor(per_cu / occ);
         const double rest = per_cu - full_rounds * occ;
         const double stages = std::ceil(steps / c.steps_per_stage);
@@ -150,7 +165,7 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
         const double t_stage = c.steps_per_stage * mb * nb * 64.0 * simd_share / kClockHz * 1e6 / c.eff_sat +
                                c.gather_elems * c.gather_cycles / kClockHz * 1e6;
         auto round_us = [&](double n) { return c.t_round_us + stages * std::max(n * t_stage, c.t_lat_us); };
-        mfma_us = full_rounds * round_us(occ) + (rest > 1e-9 ? round_us(std::ceil(rest - 1e-9)) : 0.0);
+        mfma_us = full_rounds * round_us(occ) + (rest > 1e-9 ? round_us(std::ceil(rest - 1e-9)) : 0.0) + tail_us;
     }
     // ---- working sets (bytes) and where algorithm 2 places them -------------------------------
     const double ws_acc = (double)c.wm * c.wn * 4;                         // accumulators over the reduction
@@ -293,6 +308,7 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         default: c.regs = 228; c.eff_sat = 0.75; c.t_lat_us = 0.4; c.gather_cycles = 0;  break;
         }
         c.t_round_us = 2;
+        c.tail_split = cfg.raster == 2;
         if (point) c.gather_cycles *= 0.1;
         c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
     }
@@ -400,6 +416,13 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
             polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0};
             model_conv(q, c, v.threads, 0, &rep);
             if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
+            // the same with the leftover tiles of the last round split (wave tiles up to 64x32:
+            // with larger ones the pieces measured slower than the round they save)
+            if (sk == 1 && v.wm * v.wn <= 64 * 32) {
+                c.raster = 2;
+                model_conv(q, c, v.threads, 0, &rep);
+                if (rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; }
+            }
         }
     }
     return have;

@@ -63,4 +63,19 @@ hipError_t splitk_scratch(hipStream_t stream, size_t partial_bytes, int tiles, f
     return hipSuccess;
 }
 
+// Compute units of the current device (asked once per device).
+int compute_units()
+{
+    static std::map<int, int> cus;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    auto it = cus.find(dev);
+    if (it != cus.end()) return it->second;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    cus[dev] = n;
+    return n;
+}
+
 }  // namespace polydl
