@@ -253,6 +253,37 @@ def test_gather_addressing_modes(P, s):
     P.set_tile_override(None)
 
 
+LEFTOVER = [
+    synth.ConvShape("tail64", 17, 8, 32, 32, 64, 3, 3, 1, 1),     # 272 tiles of 64x64: 16 leftover tiles, 5 stages
+    synth.ConvShape("tail1x1", 9, 40, 48, 40, 70, 1, 1, 1, 0),    # two tile rows, short reduction, ragged channels
+    synth.ConvShape("tail128", 5, 4, 64, 64, 130, 3, 3, 1, 1),    # 320 tiles of 128x128: 64 leftover tiles
+]
+
+
+@pytest.mark.parametrize("s", LEFTOVER, ids=lambda s: s.name)
+def test_leftover_tiles_split(P, s):
+    # raster 2: the tiles beyond the last full round of the compute units are cut along the reduction
+    x, w, b = synth.conv_inputs(s, seed=43, dist="normal", bias=True)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+    xi, wi, bi = synth.conv_inputs(s, seed=44, dist="ints", bias=True)
+    want_i, _ = oracle.conv2d_fwd(xi, wi, bias=bi, stride=s.stride, pad=s.pad)
+    ran = 0
+    for v in P.variants(0):
+        if v.algo != 0:
+            continue
+        v.raster, v.split_k = 2, 1
+        got = try_variant(P, v, s, x, w, b, act="relu")
+        if got is None:
+            continue
+        assert oracle.scaled_error(got, want, ab) <= FP32_TOL, v
+        assert np.array_equal(try_variant(P, v, s, x, w, b, act="relu"), got), v     # fixed summation order
+        got_i = try_variant(P, v, s, xi, wi, bi)
+        assert np.array_equal(got_i.astype(np.float64), want_i), v
+        ran += 1
+    assert ran > 0
+    P.set_tile_override(None)
+
+
 def test_argument_errors(P):
     import ctypes
     z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
