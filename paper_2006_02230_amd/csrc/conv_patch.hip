@@ -237,6 +237,11 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     int p_row[ROWS ? MAXP : 1];
 #pragma unroll
     for (int i = 0; i < MAXP; ++i) {
+        if (i * NT >= patch_elems) {   // uniform: no pass of the workgroup reaches this entry
+            p_goff[i] = kOobOffset;
+            if constexpr (ROWS) p_row[i] = -0x40000000;
+            continue;
+        }
         uint32_t e = (uint32_t)(tid + i * NT);
         uint32_t c_l = fdiv(e, magic_chs, one_chs);
         uint32_t rem = e - c_l * (uint32_t)chs;
@@ -265,6 +270,10 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     uint32_t a_goff[MAXA];
 #pragma unroll
     for (int i = 0; i < MAXA; ++i) {
+        if (i * NT >= a_elems) {   // uniform
+            a_goff[i] = kOobOffset;
+            continue;
+        }
         uint32_t e = (uint32_t)(tid + i * NT);
         uint32_t m = fdiv(e, p.magic_lda, 0u);
         int kk = (int)(e - m * (uint32_t)p.LDA);
