@@ -266,6 +266,29 @@ def main():
             fl = conv_flops(s, Pq, Qq)
             bf_rows.append(dict(layer=i, us=round(ms * 1e3, 2), tflops=round(fl / (ms * 1e-3) / 1e12, 2),
                                 layout_us=round(t_tr * 1e3, 2), tile=P.get_last_tile().as_dict()))
+            if args.sweep:
+                shape = tuple(s)[1:]
+                cands = []
+                t_sweep = time.perf_counter()
+                for v in P.conv_candidates_bf16(shape):
+                    try:
+                        P.set_tile_override(v)
+                        fn()
+                        vms = time_calls(torch, fn, 8, batches=2)
+                        pred = P.model_conv2d_bf16(shape, v)
+                    except P.PolydlError:
+                        continue
+                    cands.append(dict(us=round(vms * 1e3, 2), pred_us=round(pred, 2), cfg=v.as_dict()))
+                t_sweep = time.perf_counter() - t_sweep
+                P.set_tile_override(None)
+                cands.sort(key=lambda c: c["us"])
+                t_pick = time.perf_counter()
+                pcfg, pus = P.pick_conv2d_bf16(shape)
+                t_pick = time.perf_counter() - t_pick
+                bf_rows[-1].update(sweep_best_us=cands[0]["us"], sweep_best_tile=cands[0]["cfg"],
+                                   pick_over_best=round(cands[0]["us"] / (ms * 1e3), 4), candidates=len(cands),
+                                   predicted_us=round(pus, 2), pick_seconds=round(t_pick, 5),
+                                   sweep_seconds=round(t_sweep, 3))
             bf_ms += ms
             tr_ms += t_tr
             bf_flops += fl

@@ -207,7 +207,7 @@ int polydl_pick_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, int
  * cannot serve returns POLYDL_ERR_UNSUPPORTED); cfg == NULL returns to the reuse-model pick.
  * polydl_get_last_tile: the variant the most recent successful conv/sgemm call launched.
  * polydl_num_variants / polydl_get_variant: enumerate the compiled family
- * (kind 0 = convolution, 1 = sgemm). */
+ * (kind 0 = convolution, 1 = sgemm, 2 = bfloat16 convolution). */
 int polydl_set_tile_override(const polydl_tile_cfg *cfg);
 int polydl_get_last_tile(polydl_tile_cfg *cfg);
 int polydl_num_variants(int kind);

@@ -381,6 +381,25 @@ def conv_candidates(shape):
     return out
 
 
+def conv_candidates_bf16(shape):
+    """The (variant, cb, split_k) space of the bfloat16 convolution the sweep times: every compiled
+    tile, stage depths of 2 .. 32 eight-channel blocks, the split factors the picker ranks."""
+    N, C, H, W, K, R, S, stride, pad = [int(v) for v in shape]
+    units = -(-C // 8)
+    stage_rows = 1 if R >= 5 else R
+    out = []
+    for v in variants(2):
+        for cb in (2, 4, 6, 8, 12, 16, 24, 32):
+            if cb > ((units + 1) & ~1):
+                break
+            stages = -(-units // cb) * (R // stage_rows)
+            for sk in (1, 2, 3, 4, 6, 8, 12, 16):
+                if sk > stages:
+                    break
+                out.append(TileCfg(v.bm, v.bn, 0, v.wm, v.wn, sk, 1, 0, 1, cb))
+    return out
+
+
 def set_tile_override(cfg=None, **kw):
     """Force a variant (TileCfg or keyword fields) for later calls; None returns to the picker."""
     if cfg is None and not kw:
@@ -399,7 +418,7 @@ def get_last_tile():
 
 
 def variants(kind=0):
-    """The compiled variant family (kind 0 = convolution, 1 = sgemm) as a list of TileCfg."""
+    """The compiled variant family (kind 0 = convolution, 1 = sgemm, 2 = bfloat16 convolution) as a list of TileCfg."""
     n = lib.polydl_num_variants(kind)
     if n < 0:
         raise PolydlError(n, "polydl_num_variants")

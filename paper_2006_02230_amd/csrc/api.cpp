@@ -560,14 +560,18 @@ int polydl_get_last_tile(polydl_tile_cfg *cfg)
 int polydl_num_variants(int kind)
 {
     if (kind == 0) return kNumVariants + kNumPatchVariants;
+    if (kind == 2) return kNumPatchBf16Variants;
     return kind == 1 ? kNumVariants : POLYDL_ERR_UNSUPPORTED;
 }
 
 int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg)
 {
     if (!cfg) return POLYDL_ERR_NULL_POINTER;
-    if ((kind != 0 && kind != 1) || index < 0 || index >= polydl_num_variants(kind)) return POLYDL_ERR_UNSUPPORTED;
-    if (index < kNumVariants) cfg_of(kVariants[index], 1, 0, 0, cfg);
+    if (kind < 0 || kind > 2 || index < 0 || index >= polydl_num_variants(kind)) return POLYDL_ERR_UNSUPPORTED;
+    if (kind == 2) {
+        cfg_of_patch(kPatchBf16Variants[index], 0, 0, cfg);
+        cfg->layout = 1;
+    } else if (index < kNumVariants) cfg_of(kVariants[index], 1, 0, 0, cfg);
     else cfg_of_patch(kPatchVariants[index - kNumVariants], 0, 0, cfg);
     return POLYDL_OK;
 }
