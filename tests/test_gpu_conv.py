@@ -225,6 +225,8 @@ GATHER_MODES = [
     synth.ConvShape("taps2_63", 1, 2, 30, 30, 8, 7, 9, 1, 3),         # 63 taps: the most two registers hold
     synth.ConvShape("masks_64", 1, 2, 30, 30, 8, 8, 8, 1, 3),         # 64 taps: row and column masks
     synth.ConvShape("masks_81s2", 2, 3, 21, 21, 16, 9, 9, 2, 4),
+    synth.ConvShape("point_1x1", 3, 20, 8, 6, 70, 1, 1, 1, 0),        # 1x1 fast path, reduction shorter than two stages
+    synth.ConvShape("point_1x1_big", 5, 33, 16, 12, 130, 1, 1, 1, 0),   # tiles crossing images, channel tail, ragged K
 ]
 
 
