@@ -10,11 +10,11 @@ from .binding import (lib, PolydlError, TileCfg, conv2d_fwd, sgemm, set_tile_ove
                       reuse_bucket, reuse_cost, model_conv2d, model_sgemm, pick_conv2d, pick_sgemm,
                       conv_candidates, nchw_to_nchwc_bf16, kcrs_to_kcrsck_bf16, conv2d_fwd_bf16_blocked,
                       conv2d_fwd_bf16, bnorm_fwd, model_conv2d_bf16, pick_conv2d_bf16,
-                      conv_candidates_bf16)
+                      conv_candidates_bf16, sgemm_candidates)
 
 __all__ = ["lib", "PolydlError", "TileCfg", "conv2d_fwd", "sgemm", "set_tile_override",
            "get_last_tile", "variants", "status_string", "LIB_PATH", "nchw_to_nchwc", "nchwc_to_nchw",
            "kcrs_to_kcrsck", "bias_add", "activation", "ModelReport", "reuse_bucket", "reuse_cost",
            "model_conv2d", "model_sgemm", "pick_conv2d", "pick_sgemm", "conv_candidates",
            "nchw_to_nchwc_bf16", "kcrs_to_kcrsck_bf16", "conv2d_fwd_bf16_blocked", "conv2d_fwd_bf16", "bnorm_fwd",
-           "model_conv2d_bf16", "pick_conv2d_bf16", "conv_candidates_bf16"]
+           "model_conv2d_bf16", "pick_conv2d_bf16", "conv_candidates_bf16", "sgemm_candidates"]

@@ -381,6 +381,20 @@ def conv_candidates(shape):
     return out
 
 
+def sgemm_candidates(M, N, K):
+    """Every (variant, split_k, raster) the picker ranks for an SGEMM: the sweep's search space."""
+    splits = (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128)
+    out = []
+    for v in variants(1):
+        stages = -(-K // v.bk)
+        for sk in splits:
+            if sk > stages:
+                break
+            for raster in (0, 1):
+                out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, raster, 0, 0))
+    return out
+
+
 def conv_candidates_bf16(shape):
     """The (variant, cb, split_k) space of the bfloat16 convolution the sweep times: every compiled
     tile, stage depths of 2 .. 32 eight-channel blocks, the split factors the picker ranks."""

@@ -380,7 +380,9 @@ void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads,
     c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 1 : ((cfg.wm * cfg.wn == 64 * 64) ? 2 : 4);
     model(s, c, r);
     if (cfg.split_k > 1) {   // every part writes its tile to scratch once, the last one reads them all back
-        r->fixed_us = c.kernel_fixed_us + 2.0 * cfg.split_k * (double)q.M * q.N * 4 / kHbmGBs * 1e-3;
+        // plus the hand-over itself (store, count, read back), which no amount of bandwidth shortens
+        r->fixed_us = c.kernel_fixed_us + 2.0 * cfg.split_k * (double)q.M * q.N * 4 / kHbmGBs * 1e-3 +
+                      0.4 * (cfg.split_k - 1);
         r->predicted_us = std::max(r->mfma_us, r->mem_us) + r->fixed_us;
     }
 }
