@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "66cda7050d4a85cb90d6a67908640d0c6e46756116b4e360fe180a206f15197a", "batch": 32, "fetch_bytes": 704748149, "write_bytes": 388098064}
+HBM_TRAFFIC = {"csrc_sha256": "2ad33f0f9454dcf2c137f962551f2fad313cb9eeaeef9872eeb7ed3b8ab20e29", "batch": 32, "fetch_bytes": 704672781, "write_bytes": 388211048}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
