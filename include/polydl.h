@@ -88,6 +88,16 @@ int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int s
                           const float *in, const float *wt, const float *bias, float *out,
                           int act /* polydl_act */, void *stream);
 
+/* The same with an element-wise operator BEFORE the convolution fused in as well (the symmetric
+ * case of section "Operator Fusion": an element-wise operator fused with the heavy operator that
+ * follows it): out = act(conv(pre_act(in)) + bias), where pre_act (a polydl_act) is applied to
+ * every input element as it is read, so the activated input is never written to memory.  Padding
+ * contributes zeros (ReLU and ReLU6 of zero).  Served by the gather kernel (algo 0) only: with a
+ * forced algo 1 variant and pre_act != POLYDL_ACT_NONE the call returns POLYDL_ERR_UNSUPPORTED. */
+int polydl_conv2d_fwd_pre_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              const float *in, const float *wt, const float *bias, float *out,
+                              int pre_act /* polydl_act */, int act /* polydl_act */, void *stream);
+
 /* ---- matrix product ------------------------------------------------------------------------
  * C[i][j] += sum_k A[i][k] * B[k][j]   (alpha = beta = 1, the reading taken of section "GEMM").
  * Row-major, A is M x K, B is K x N, C is M x N and is read and accumulated into.  K = 0 is

@@ -58,6 +58,8 @@ class ModelReport(ctypes.Structure):
 _i, _p = ctypes.c_int, ctypes.c_void_p
 lib.polydl_conv2d_fwd.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_conv2d_fwd_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
+lib.polydl_conv2d_fwd_pre_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _i, _p]
+lib.polydl_conv2d_fwd_pre_act.restype = _i
 lib.polydl_sgemm.argtypes = [_i, _i, _i, _p, _p, _p, _p]
 lib.polydl_sgemm_ex.argtypes = [_i, _i, _i, ctypes.c_float, _p, _p, ctypes.c_float, _p, _p]
 lib.polydl_sgemm_ex.restype = _i
@@ -200,8 +202,9 @@ def conv2d_fwd_bf16(x, w, bias=None, out=None, stride=1, pad=0, act=None, worksp
     return out
 
 
-def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None):
-    """polydl_conv2d_fwd_act on torch device tensors x (NCHW), w (KCRS); returns out (NKPQ)."""
+def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None, pre_act=None):
+    """polydl_conv2d_fwd_act on torch device tensors x (NCHW), w (KCRS); returns out (NKPQ).
+    With pre_act given, polydl_conv2d_fwd_pre_act: the convolution of pre_act(x)."""
     import torch
     N, C, H, W = x.shape
     K, C2, R, S = w.shape
@@ -211,8 +214,13 @@ def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None
     Q = (W + 2 * pad - S) // stride + 1
     if out is None:
         out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.float32, device=x.device)
-    st = lib.polydl_conv2d_fwd_act(N, C, H, W, K, R, S, stride, pad, _dev(x, "x"), _dev(w, "w"),
-                                   _dev(bias, "bias"), _dev(out, "out"), ACT[act], _stream_ptr(stream))
+    if pre_act is None:
+        st = lib.polydl_conv2d_fwd_act(N, C, H, W, K, R, S, stride, pad, _dev(x, "x"), _dev(w, "w"),
+                                       _dev(bias, "bias"), _dev(out, "out"), ACT[act], _stream_ptr(stream))
+    else:
+        st = lib.polydl_conv2d_fwd_pre_act(N, C, H, W, K, R, S, stride, pad, _dev(x, "x"), _dev(w, "w"),
+                                           _dev(bias, "bias"), _dev(out, "out"), ACT[pre_act], ACT[act],
+                                           _stream_ptr(stream))
     _check(st, "polydl_conv2d_fwd")
     return out
 

@@ -42,7 +42,7 @@ static bool g_have_override = false;
 static polydl_tile_cfg g_override;
 static polydl_tile_cfg g_last = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 // picks already made, keyed by the problem's dimensions (the ranking depends on nothing else)
-static std::map<std::array<int, 9>, polydl_tile_cfg> g_conv_plans;
+static std::map<std::array<int, 10>, polydl_tile_cfg> g_conv_plans;   // shape, and whether the input is activated on the way in
 static std::map<std::array<int, 3>, polydl_tile_cfg> g_sgemm_plans;
 
 static const Variant *find_variant(const polydl_tile_cfg &c)
@@ -155,9 +155,11 @@ static int sgemm_impl(int M, int N, int K, float alpha, const float *A, const fl
 }
 
 static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
-                     const float *in, const float *wt, const float *bias, float *out, int act,
+                     const float *in, const float *wt, const float *bias, float *out, int pre_act, int act,
                      void *stream)
 {
+    if (pre_act != POLYDL_ACT_NONE && pre_act != POLYDL_ACT_RELU && pre_act != POLYDL_ACT_RELU6)
+        return POLYDL_ERR_UNSUPPORTED;
     int64_t P, Q;
     if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
     if (!in || !wt || !out) return POLYDL_ERR_NULL_POINTER;
@@ -165,7 +167,7 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         return POLYDL_ERR_UNSUPPORTED;
     if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
     const int64_t Kg = (int64_t)C * R * S, CHW = (int64_t)C * H * W;
-    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act};
+    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act, pre_act};
     polydl_tile_cfg cfg;
     bool forced;
     {
@@ -174,7 +176,7 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         cfg = g_override;
     }
     if (!forced) {
-        const std::array<int, 9> key = {N, C, H, W, K, R, S, stride, pad};
+        const std::array<int, 10> key = {N, C, H, W, K, R, S, stride, pad, pre_act != POLYDL_ACT_NONE};
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_conv_plans.find(key);
         if (it != g_conv_plans.end()) {
@@ -187,6 +189,7 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     }
     if (cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
     if (cfg.algo == 1) {
+        if (pre_act != POLYDL_ACT_NONE) return POLYDL_ERR_UNSUPPORTED;   // a forced patch-kernel variant
         const PatchVariant *pv = find_patch_variant(cfg);
         if (!pv) return POLYDL_ERR_UNSUPPORTED;
         if (cfg.cb == 0) cfg.cb = choose_cb(*pv, q);
@@ -223,7 +226,7 @@ int polydl_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int strid
                       const float *in, const float *wt, const float *bias, float *out,
                       int fuse_relu, void *stream)
 {
-    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out,
+    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, POLYDL_ACT_NONE,
                      fuse_relu ? POLYDL_ACT_RELU : POLYDL_ACT_NONE, stream);
 }
 
@@ -231,7 +234,14 @@ int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int s
                           const float *in, const float *wt, const float *bias, float *out, int act,
                           void *stream)
 {
-    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, act, stream);
+    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, POLYDL_ACT_NONE, act, stream);
+}
+
+int polydl_conv2d_fwd_pre_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              const float *in, const float *wt, const float *bias, float *out, int pre_act,
+                              int act, void *stream)
+{
+    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, pre_act, act, stream);
 }
 
 int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream)

@@ -31,6 +31,7 @@ struct ConvKArgs {
     int whole_tiles, tail_parts, tail_k;
     uint32_t recip_tail;
     int raster, act;
+    int pre_act;                // activation applied to every input element as its stage is filled
     float *partials;            // split_k > 1: [tile][part][BM*BN] accumulator tiles in register order
     unsigned *counters;         // split_k > 1: per tile, how many of its reduction parts have finished
 };
@@ -80,12 +81,12 @@ struct BLoaderIm2col {
     int pix_off;      // element offset of tap (0,0), channel 0 of this pixel from the descriptor base
     uint32_t rmask, smask;   // GATHER_TAPS*: the tap bits 0-31 and 32-63
     int krow0, lds_off;
-    int RS, S, HW, W;
+    int RS, S, HW, W, pre_act;
     uint32_t magic_RS, magic_S, one_RS, one_S;
 
     __device__ __forceinline__ void init(const ConvKArgs &p, int tid, int n0)
     {
-        RS = p.RS; S = p.S; HW = p.HW; W = p.W;
+        RS = p.RS; S = p.S; HW = p.HW; W = p.W; pre_act = p.pre_act;
         magic_RS = p.magic_RS; magic_S = p.magic_S; one_RS = p.one_RS; one_S = p.one_S;
         const int col = tid % T::BN;
         krow0 = __builtin_amdgcn_readfirstlane(tid / T::BN);
@@ -165,9 +166,19 @@ struct BLoaderIm2col {
             regs[SET][i] = buf_load1(rsrc, off);
         }
     }
+    // The element-wise operator that precedes the convolution is applied where its operand is
+    // first touched (the symmetric case of section "Operator Fusion": fused with the first iteration
+    // of the heavy operator's reduction loops); zero fill stays zero under ReLU and ReLU6.
     template <int SET>
-    __device__ __forceinline__ void store(float *Bs, int) const
+    __device__ __forceinline__ void store(float *Bs, int)
     {
+        if (pre_act != POLYDL_ACT_NONE) {   // uniform
+#pragma unroll
+            for (int i = 0; i < ITERS; ++i) {
+                float v = fmaxf(regs[SET][i], 0.f);
+                regs[SET][i] = pre_act == POLYDL_ACT_RELU6 ? fminf(v, 6.f) : v;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) Bs[lds_off + i * KSTEP * T::LDB] = regs[SET][i];
     }
@@ -337,6 +348,7 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     const bool tail = raster == 2;   // tile order of raster 0, leftover tiles split
     a.raster = tail ? 0 : raster;
     a.act = q.act;
+    a.pre_act = q.pre_act;
     a.partials = nullptr;
     a.counters = nullptr;
     clear_stale_hip_error();

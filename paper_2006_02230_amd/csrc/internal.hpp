@@ -19,6 +19,7 @@ struct ConvProblem {
     const float *bias;
     float *out;
     int act;
+    int pre_act = 0;       // polydl_act applied to every input element as it is read (gather kernel only)
 };
 
 // One compiled variant: its tile parameters and the launchers instantiated for it.
@@ -104,7 +105,7 @@ double reuse_cost(int nlevels, const double *levels, double mem, const double *w
 void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, int reg_class, polydl_model_report *r);
 void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r);
 double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads);   // predicted microseconds
-bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
+bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);   // q.pre_act: gather kernel only
 bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
 
 // Exact unsigned division by a runtime constant d for dividends n with n*d < 2^32:

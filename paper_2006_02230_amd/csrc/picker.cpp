@@ -394,7 +394,8 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
     bool have = false;
     polydl_model_report rep;
     const int cpad = (q.C + 1) & ~1;
-    for (int i = 0; i < kNumPatchVariants; ++i) {
+    // the patch kernel copies input rows straight into LDS and cannot touch them on the way
+    for (int i = 0; i < (q.pre_act ? 0 : kNumPatchVariants); ++i) {
         const PatchVariant &v = kPatchVariants[i];
         for (int cb = 2; cb <= cpad && cb <= 64; cb += 2) {
             if (cpad % cb != 0) continue;

@@ -286,6 +286,72 @@ def test_leftover_tiles_split(P, s):
     P.set_tile_override(None)
 
 
+@pytest.mark.parametrize("s", [SMALL[0], SMALL[2], SMALL[3], SMALL[4], SMALL[6]], ids=lambda s: s.name)
+def test_activation_before_the_convolution(P, s):
+    # out = act(conv(pre_act(x)) + bias): the oracle applies the element-wise operator to the input
+    # first and then convolves; the gather kernel applies it as it fills a stage
+    from oracle import elementwise
+    x, w, b = synth.conv_inputs(s, seed=51, dist="normal", bias=True)
+    x = (x * 4).astype(np.float32)                     # some values beyond 6
+    for pre, fn in (("relu", elementwise.relu), ("relu6", elementwise.relu6)):
+        xa = fn(x.astype(np.float64)).astype(np.float32)   # exact: max/min of float32 values
+        want, ab = oracle.conv2d_fwd(xa, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+        ran = 0
+        for v in P.variants(0):
+            P.set_tile_override(v)
+            for split_k in (1, 2):
+                v.split_k = split_k
+                P.set_tile_override(v)
+                try:
+                    got = host(P.conv2d_fwd(dev(x), dev(w), dev(b), stride=s.stride, pad=s.pad, act="relu", pre_act=pre))
+                except P.PolydlError as e:
+                    assert e.status == -3
+                    if v.algo == 0:
+                        continue          # outside that variant's limits
+                    break                 # the patch kernel does not take the operator
+                assert v.algo == 0
+                assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (v, pre)
+                ran += 1
+        assert ran > 0
+    P.set_tile_override(None)
+    # through the picker: only gather variants are ranked
+    got = host(P.conv2d_fwd(dev(x), dev(w), dev(b), stride=s.stride, pad=s.pad, act="relu", pre_act="relu6"))
+    assert P.get_last_tile().algo == 0
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL
+    # and pre_act none is the plain call bit for bit
+    a = host(P.conv2d_fwd(dev(x), dev(w), dev(b), stride=s.stride, pad=s.pad, act="relu", pre_act="none"))
+    c = host(P.conv2d_fwd(dev(x), dev(w), dev(b), stride=s.stride, pad=s.pad, act="relu"))
+    assert np.array_equal(a, c)
+
+
+def test_random_shapes_through_the_picker(P):
+    # no forced variant: whatever the picker chooses for each of a seeded set of random problems
+    # (kernel, tile, split, workgroup order) must agree with the definition
+    rng = np.random.default_rng(2024)
+    P.set_tile_override(None)
+    seen = set()
+    for t in range(40):
+        R = int(rng.choice([1, 1, 2, 3, 3, 3, 5, 7]))
+        S = R if rng.random() < 0.8 else int(rng.choice([1, 2, 3, 4]))
+        stride = int(rng.choice([1, 1, 1, 2, 3]))
+        pad = int(rng.integers(0, max(R, S)))
+        H = int(rng.integers(max(R - 2 * pad, 1), 40))
+        W = int(rng.integers(max(S - 2 * pad, 1), 40))
+        N, C, K = int(rng.integers(1, 9)), int(rng.integers(1, 70)), int(rng.integers(1, 200))
+        s = synth.ConvShape("rnd%d" % t, N, C, H, W, K, R, S, stride, pad)
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        x, w, b = synth.conv_inputs(s, seed=500 + t, dist="normal", bias=bool(t % 3))
+        act = [None, "relu", "relu6"][t % 3]
+        want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act=act)
+        got = run_conv(P, s, x, w, b, act=act)
+        assert got.shape == want.shape, s
+        assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (s, P.get_last_tile())
+        tile = P.get_last_tile()
+        seen.add((tile.algo, tile.bm, tile.bn, tile.split_k > 1, tile.raster))
+    assert len(seen) >= 3      # the set is varied enough to reach several kinds of pick
+
+
 def test_argument_errors(P):
     import ctypes
     z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
