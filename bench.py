@@ -359,6 +359,23 @@ def main():
                       output_bytes=ob, algorithmic_bytes_saved=4 * ob,
                       note="the two extra kernels each read and write the whole output once: four passes "
                            "over it that the fused epilogue never makes")
+        # the element-wise operator BEFORE the convolution: fused into the operand staging against a
+        # separate in-place pass over the input (ReLU is idempotent, so repeating it changes nothing)
+        pre_fused = lambda: P.conv2d_fwd(dx, dw, db, out=out, stride=s.stride, pad=s.pad, act="relu", pre_act="relu")
+
+        def pre_separate():
+            P.activation(dx, "relu")
+            P.conv2d_fwd(dx, dw, db, out=out, stride=s.stride, pad=s.pad, act="relu")
+        pre_fused(); pre_separate()
+        samples = {"f": [], "s": []}
+        for _ in range(5):
+            samples["f"].append(time_calls(torch, pre_fused, 20, batches=1))
+            samples["s"].append(time_calls(torch, pre_separate, 20, batches=1))
+        t_pf, t_ps = (sorted(samples[k])[2] for k in ("f", "s"))
+        fusion["relu_before"] = dict(workload="ReLU + conv+bias+ReLU on the same layer", fused_us=round(t_pf * 1e3, 2),
+                                     separate_us=round(t_ps * 1e3, 2), speedup=round(t_ps / t_pf, 3),
+                                     input_bytes=4.0 * s.N * s.C * s.H * s.W,
+                                     algorithmic_bytes_saved=8.0 * s.N * s.C * s.H * s.W)
         del dx, dw, out
 
     # batch normalisation + ReLU in one pass against the two operators as two kernels, on the
