@@ -43,6 +43,42 @@ __global__ __launch_bounds__(256) void nchwc_kernel(const V *__restrict__ src, V
     }
 }
 
+// NCHW -> NCHW8c for 16-bit elements when H*W is a multiple of 8 and both tensors are 16-byte
+// aligned.  One workgroup moves 8 channels x 512 pixels: a thread loads 16 bytes (8 pixels of one
+// channel), the 8 x 512 tile is turned in LDS, and a thread stores 16 bytes (the 8 channels of one
+// pixel): every access to memory is 128 bits wide.  Channels beyond C are zeros.
+__global__ __launch_bounds__(256) void nchw8c_16bit_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                           int C, int HW, int Cb)
+{
+    constexpr int PIX = 512, PITCH = PIX + 8;            // pitch keeps rows 16-byte aligned
+    __shared__ __attribute__((aligned(16))) uint16_t tile[8 * PITCH];
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const int t = threadIdx.x;
+    const int hw0 = blockIdx.x * PIX, cb = blockIdx.y, n = blockIdx.z;
+    const int npix = min(PIX, HW - hw0);                 // a multiple of 8
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int u = t + i * 256;                       // 8 channels x 64 groups of 8 pixels
+        const int ci = u >> 6, g = u & 63, c = cb * 8 + ci;
+        u4 v = {0u, 0u, 0u, 0u};
+        if (c < C && g * 8 < npix) v = *reinterpret_cast<const u4 *>(src + ((size_t)n * C + c) * HW + hw0 + g * 8);
+        *reinterpret_cast<u4 *>(tile + ci * PITCH + g * 8) = v;
+    }
+    __syncthreads();
+    uint16_t *o = dst + (((size_t)n * Cb + cb) * HW + hw0) * 8;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int px = t + i * 256;
+        if (px >= npix) continue;
+        unsigned int w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            w[j] = (unsigned int)tile[(2 * j) * PITCH + px] | ((unsigned int)tile[(2 * j + 1) * PITCH + px] << 16);
+        u4 v = {w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<u4 *>(o + (size_t)px * 8) = v;
+    }
+}
+
 // KCRS -> KCRSck: one thread per element of the blocked tensor (weights are small and packed
 // once per tensor).  Elements whose channel indices fall beyond K or C are zeros.
 template <class V>
@@ -164,6 +200,11 @@ hipError_t launch_nchwc(const void *src, void *dst, int N, int C, int HW, int b,
     } else {
         const uint16_t *s = static_cast<const uint16_t *>(src);
         uint16_t *d = static_cast<uint16_t *>(dst);
+        if (to_blocked && b == 8 && HW % 8 == 0 && ((uintptr_t)src & 15) == 0 && ((uintptr_t)dst & 15) == 0) {
+            dim3 g8((unsigned)((HW + 511) / 512), (unsigned)Cb, (unsigned)N);
+            hipLaunchKernelGGL(nchw8c_16bit_kernel, g8, dim3(256), 0, st, s, d, C, HW, Cb);
+            return hipGetLastError();
+        }
         if (to_blocked) hipLaunchKernelGGL((nchwc_kernel<uint16_t, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
         else hipLaunchKernelGGL((nchwc_kernel<uint16_t, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
     }

@@ -57,6 +57,16 @@ def test_layout_transforms_bit_exact(P, s):
     assert np.array_equal(w8, oracle.kcrs_to_kcrsck(wb, 8, 1))
 
 
+@pytest.mark.parametrize("N,C,H,W", [(2, 3, 32, 40), (3, 20, 8, 8), (1, 64, 56, 56), (2, 9, 24, 24), (1, 8, 4, 2)])
+def test_wide_activation_transform_bit_exact(P, N, C, H, W):
+    # pixel planes that are a multiple of 8 elements take the kernel that moves 16 bytes per access:
+    # planes shorter and longer than its 512-pixel tiles, channel counts that leave a block part empty
+    rng = np.random.default_rng(N * 1000 + C)
+    xb = rng.integers(0, 1 << 16, size=(N, C, H, W), dtype=np.uint16)
+    x8 = host(P.nchw_to_nchwc_bf16(dev16(xb), 8)).view(np.uint16)
+    assert np.array_equal(x8, oracle.nchw_to_nchwc(xb, 8))
+
+
 @pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
 def test_bf16_conv_parity(P, s):
     xb, wb, xw, ww, b = bf16_inputs(s, 52)
