@@ -200,7 +200,7 @@ def main():
                 try:
                     P.set_tile_override(v)
                     run_layer(L)
-                    vms = time_calls(torch, lambda L=L: run_layer(L), 8, batches=2)
+                    vms = time_calls(torch, lambda L=L: run_layer(L), 8, batches=3)
                 except P.PolydlError:
                     continue
                 pred = P.model_conv2d(shape, v).predicted_us
@@ -302,7 +302,7 @@ def main():
                     try:
                         P.set_tile_override(v)
                         fn()
-                        vms = time_calls(torch, fn, 8, batches=2)
+                        vms = time_calls(torch, fn, 8, batches=3)
                         pred = P.model_conv2d_bf16(shape, v)
                     except P.PolydlError:
                         continue

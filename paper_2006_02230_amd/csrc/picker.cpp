@@ -300,17 +300,17 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         c.kernel_fixed_us = 5.0;
         c.gather_elems = (double)cfg.bk * cfg.bn / threads;
         switch (mbn) {
-        case 11: c.regs = 62;  c.eff_sat = 0.80; c.t_lat_us = 0.6; c.gather_cycles = 20; c.split_c0 = 2; break;
-        case 12: c.regs = 90;  c.eff_sat = 0.85; c.t_lat_us = 1.0; c.gather_cycles = 60; c.split_c0 = 2; break;
-        case 21: c.regs = 88;  c.eff_sat = 0.80; c.t_lat_us = 0.8; c.gather_cycles = 20; break;
-        case 22: c.regs = cfg.bk == 16 ? 136 : 104; c.eff_sat = 0.75; c.t_lat_us = 0.8; c.gather_cycles = 20; c.split_c0 = 10; break;
-        case 24: c.regs = 212; c.eff_sat = 0.70; c.t_lat_us = 0.4; c.gather_cycles = 20; break;
-        default: c.regs = 228; c.eff_sat = 0.75; c.t_lat_us = 0.4; c.gather_cycles = 0;  break;
+        case 11: c.regs = 62;  c.eff_sat = 0.70; c.t_lat_us = 0.6; c.t_round_us = 2; c.gather_cycles = 0;  break;
+        case 12: c.regs = 90;  c.eff_sat = 0.80; c.t_lat_us = 1.0; c.t_round_us = 4; c.gather_cycles = 20; c.split_c0 = 2; break;
+        case 21: c.regs = 88;  c.eff_sat = 0.90; c.t_lat_us = 0.8; c.t_round_us = 4; c.gather_cycles = 40; break;
+        case 22: c.regs = cfg.bk == 16 ? 136 : 104; c.eff_sat = 0.80; c.t_lat_us = 0.8; c.t_round_us = 2; c.gather_cycles = 40;
+                 c.split_c0 = 8; c.split_c1 = 0.2; break;
+        case 24: c.regs = 212; c.eff_sat = 0.70; c.t_lat_us = 0.4; c.t_round_us = 2; c.gather_cycles = 20; c.split_c0 = 15; c.split_c1 = 0.6; break;
+        default: c.regs = 228; c.eff_sat = 0.80; c.t_lat_us = 0.4; c.t_round_us = 4; c.gather_cycles = 20; c.split_c0 = 15; c.split_c1 = 1.0; break;
         }
-        c.t_round_us = 2;
         c.tail_split = cfg.raster == 2;
         if (point) c.gather_cycles *= 0.1;
-        c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
+        if (c.split_c1 == 0) c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
     }
     Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
     model(s, c, r);
