@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "a73cd11d090e43af16d3345b7046c02700992a7ad95b2bb6a6800256427f107d", "batch": 32, "fetch_bytes": 703448792, "write_bytes": 387948528}
+HBM_TRAFFIC = {"csrc_sha256": "ef87118c1285ac9b041f5fe1f6c43439b248800b8311ff697b53dac09bf17285", "batch": 32, "fetch_bytes": 743194785, "write_bytes": 457865504}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
