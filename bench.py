@@ -451,7 +451,7 @@ def main():
                             "tensors" % (args.batch, args.batch),
                    roofline={"bound": "hbm", "achieved": round(b_big / (t_bf * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(b_big / (t_bf * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                             "kernel": "polydl::nchwc_kernel, NCHW -> NCHW16c of the large activation "
+                             "kernel": "polydl::nchwc_wide_kernel, NCHW -> NCHW16c of the large activation "
                                        "(%.0f MB read + written per launch)" % (b_big / 1e6)},
                    large=dict(to_blocked_us=round(t_bf * 1e3, 2), to_blocked_gbs=round(b_big / (t_bf * 1e-3) / 1e9, 1),
                               from_blocked_us=round(t_bb * 1e3, 2), from_blocked_gbs=round(b_big / (t_bb * 1e-3) / 1e9, 1)),

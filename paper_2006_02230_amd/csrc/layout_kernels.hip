@@ -43,6 +43,57 @@ __global__ __launch_bounds__(256) void nchwc_kernel(const V *__restrict__ src, V
     }
 }
 
+// The same permutation for float tensors with 128-bit accesses on both sides: block sizes that are
+// a multiple of 4 (up to 32), pixel planes a multiple of 4 floats, 16-byte aligned tensors.  One
+// workgroup moves b channels x 256 pixels.  NCHW side: a thread moves four pixels of one channel;
+// NCHWc side: four channels of one pixel, so consecutive threads touch consecutive 16 bytes.
+// The LDS tile is [b][260]: rows stay 16-byte aligned and the strided side conflicts two-way.
+template <bool TO_BLOCKED>
+__global__ __launch_bounds__(256) void nchwc_wide_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                         int C, int HW, int b, int Cb)
+{
+    constexpr int PITCH = 260;
+    extern __shared__ __attribute__((aligned(16))) unsigned char tile_raw[];
+    float *tile = reinterpret_cast<float *>(tile_raw);   // [b][PITCH]
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int t = threadIdx.x;
+    const int hw0 = blockIdx.x * 256, cb = blockIdx.y, n = blockIdx.z;
+    const int npix = min(256, HW - hw0);                 // a multiple of 4
+    const int quads = b >> 2;                            // groups of four channels in a block
+    const size_t blocked0 = (((size_t)n * Cb + cb) * HW + hw0) * b;
+    if (TO_BLOCKED) {
+        // rows of the NCHW tensor: unit u = (channel, group of four pixels)
+        for (int u = t; u < b * 64; u += 256) {
+            const int ci = u >> 6, g = u & 63, c = cb * b + ci;
+            f4 v = {0.f, 0.f, 0.f, 0.f};
+            if (c < C && g * 4 < npix) v = *reinterpret_cast<const f4 *>(src + ((size_t)n * C + c) * HW + hw0 + g * 4);
+            *reinterpret_cast<f4 *>(tile + ci * PITCH + g * 4) = v;
+        }
+        __syncthreads();
+        // blocked tensor: unit e = (pixel, group of four channels), consecutive in memory
+        for (int e = t; e < npix * quads; e += 256) {
+            const int px = e / quads, cj = e - px * quads;
+            f4 v = {tile[(4 * cj) * PITCH + px], tile[(4 * cj + 1) * PITCH + px], tile[(4 * cj + 2) * PITCH + px],
+                    tile[(4 * cj + 3) * PITCH + px]};
+            *reinterpret_cast<f4 *>(dst + blocked0 + (size_t)e * 4) = v;
+        }
+    } else {
+        for (int e = t; e < npix * quads; e += 256) {
+            const int px = e / quads, cj = e - px * quads;
+            const f4 v = *reinterpret_cast<const f4 *>(src + blocked0 + (size_t)e * 4);
+            tile[(4 * cj) * PITCH + px] = v.x; tile[(4 * cj + 1) * PITCH + px] = v.y;
+            tile[(4 * cj + 2) * PITCH + px] = v.z; tile[(4 * cj + 3) * PITCH + px] = v.w;
+        }
+        __syncthreads();
+        for (int u = t; u < b * 64; u += 256) {
+            const int ci = u >> 6, g = u & 63, c = cb * b + ci;
+            if (c < C && g * 4 < npix)
+                *reinterpret_cast<f4 *>(dst + ((size_t)n * C + c) * HW + hw0 + g * 4) =
+                    *reinterpret_cast<const f4 *>(tile + ci * PITCH + g * 4);
+        }
+    }
+}
+
 // NCHW -> NCHW8c for 16-bit elements when H*W is a multiple of 8 and both tensors are 16-byte
 // aligned.  One workgroup moves 8 channels x 512 pixels: a thread loads 16 bytes (8 pixels of one
 // channel), the 8 x 512 tile is turned in LDS, and a thread stores 16 bytes (the 8 channels of one
@@ -195,6 +246,12 @@ hipError_t launch_nchwc(const void *src, void *dst, int N, int C, int HW, int b,
     if (elem_bytes == 4) {
         const float *s = static_cast<const float *>(src);
         float *d = static_cast<float *>(dst);
+        if (b % 4 == 0 && HW % 4 == 0 && ((uintptr_t)src & 15) == 0 && ((uintptr_t)dst & 15) == 0) {
+            const size_t wide_lds = (size_t)b * 260 * sizeof(float);
+            if (to_blocked) hipLaunchKernelGGL((nchwc_wide_kernel<true>), grid, dim3(256), wide_lds, st, s, d, C, HW, b, Cb);
+            else hipLaunchKernelGGL((nchwc_wide_kernel<false>), grid, dim3(256), wide_lds, st, s, d, C, HW, b, Cb);
+            return hipGetLastError();
+        }
         if (to_blocked) hipLaunchKernelGGL((nchwc_kernel<float, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
         else hipLaunchKernelGGL((nchwc_kernel<float, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
     } else {

@@ -20,7 +20,9 @@ def P():
 
 
 @pytest.mark.parametrize("N,C,H,W,b", [(2, 8, 5, 7, 4), (1, 3, 30, 30, 4), (3, 10, 17, 19, 8), (2, 64, 56, 56, 16),
-                                        (1, 5, 1, 1, 2), (2, 33, 14, 14, 32), (1, 7, 23, 300, 1)])
+                                        (1, 5, 1, 1, 2), (2, 33, 14, 14, 32), (1, 7, 23, 300, 1),
+                                        # planes that are a multiple of four floats: the 128-bit kernel
+                                        (3, 20, 8, 6, 8), (1, 16, 40, 36, 16), (2, 5, 64, 64, 12), (1, 40, 2, 2, 20)])
 def test_nchwc_roundtrip_and_parity(P, N, C, H, W, b):
     x = synth.uniform_pm1(41, 0, (N, C, H, W))
     want = oracle.nchw_to_nchwc(x, b)
