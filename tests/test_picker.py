@@ -125,6 +125,21 @@ def test_sgemm_pick_valid():
         assert rep.predicted_us > 0
 
 
+def test_leftover_tiles_in_the_model():
+    # 64x64 tiles of the gather kernel.  Layer 2 of the suite at N = 32 has 1568 tiles = 6 * 256 + 32:
+    # cutting the 32 leftover tiles (raster 2) must be predicted faster than a seventh round for them.
+    # A grid that is a whole number of rounds has nothing left over: same prediction either way.
+    plain = P.TileCfg(64, 64, 16, 32, 32, 1, 0, 0, 0, 0)
+    cut = P.TileCfg(64, 64, 16, 32, 32, 1, 0, 2, 0, 0)
+    shape = (32, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert P.model_conv2d(shape, cut).predicted_us < P.model_conv2d(shape, plain).predicted_us - 3.0
+    shape_even = (256, 64, 8, 8, 64, 3, 3, 1, 1)      # 256 * 64 pixels / 64 = 256 tiles: nothing left over
+    assert P.model_conv2d(shape_even, cut).predicted_us == pytest.approx(P.model_conv2d(shape_even, plain).predicted_us)
+    # a grid of less than one round is the split factor's business: left alone
+    shape_most = (4, 64, 56, 56, 64, 3, 3, 1, 1)      # 196 tiles
+    assert P.model_conv2d(shape_most, cut).predicted_us == pytest.approx(P.model_conv2d(shape_most, plain).predicted_us)
+
+
 def test_bf16_pick_is_a_compiled_variant_and_the_model_agrees():
     for s in synth.RESNET50_SUITE(64):
         shape = tuple(s)[1:]
