@@ -17,7 +17,8 @@
  *     nothing is enqueued and no output byte is written;
  *   - tensors are dense, contiguous float32 unless stated; input and output must not overlap;
  *   - memory of its own: a convolution or matrix product whose reduction is split over
- *     several workgroups (split_k > 1) keeps partial tiles and arrival counters in a
+ *     several workgroups (split_k > 1, or the leftover tiles of raster 2) keeps partial tiles
+ *     and arrival counters in a
  *     device buffer the library allocates with hipMalloc on first need, one per (device, stream),
  *     grows on demand and keeps until the process ends; growing it waits for the device.  Calls
  *     on ONE stream share it safely (they run in order); calls on different streams use
