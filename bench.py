@@ -216,6 +216,20 @@ def main():
                             pick_over_best=round(best["us"] / (ms * 1e3), 4), candidates=len(cands),
                             predicted_us=round(prep.predicted_us, 2), pick_seconds=round(t_pick, 5),
                             sweep_seconds=round(t_sweep, 3))
+            # the learned ranking's choice among the same candidates (tournament of the pairwise network),
+            # timed like the model's pick
+            if os.path.exists(P.RANKER_PARAMS_PATH):
+                P.ranker_load()
+                t_learn = time.perf_counter()
+                lcfg, _, lwins, lgames = P.pick_conv2d_learned(shape)
+                t_learn = time.perf_counter() - t_learn
+                P.set_tile_override(lcfg)
+                run_layer(L)
+                lms = time_calls(torch, lambda L=L: run_layer(L), reps)
+                P.set_tile_override(forced)
+                rows[-1].update(learned_tile=lcfg.as_dict(), learned_us=round(lms * 1e3, 2),
+                                learned_over_best=round(best["us"] / (lms * 1e3), 4),
+                                learned_wins=[lwins, lgames], learned_pick_seconds=round(t_learn, 4))
             sweep_dump.append(dict(layer=i, shape=list(shape), picked=pcfg.as_dict(), picked_us=round(ms * 1e3, 2),
                                    candidates=cands))
     if args.no_layer_rows:

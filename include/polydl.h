@@ -212,6 +212,53 @@ int polydl_model_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, in
 int polydl_pick_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                             polydl_tile_cfg *cfg, double *predicted_us);
 
+/* ---- learned ranking (section "DNN-based ranking algorithm") ---------------------------------
+ * A feed-forward network compares two variants from their statistics; every variant plays every
+ * other one and the variants are ranked by games won.  All pointers are host pointers; all
+ * arithmetic is double precision on the host.
+ *
+ * Network (that section and its architecture figure): 2*POLYDL_RANKER_STATS inputs, hidden
+ * layers of 64, 32, 16 and 8 units with relu, relu, softsign and relu, two outputs under a
+ * softmax.  An output above theta (the paper uses 0.6) counts as 1: the first output means the
+ * first variant wins, the second output the second variant, neither a draw.
+ *
+ * Statistics of a variant, POLYDL_RANKER_STATS doubles, all >= 0: the four level_bytes and the
+ * mem_bytes of its model report (the result of algorithm "Compute working set sizes w.r.t cache
+ * sizes", which is all the paper feeds its network), then mfma_us, mem_us and fixed_us of the same
+ * report, which carry what the split factor and the grid's fit to the chip change.  Before they
+ * enter the network the byte counts of both variants are divided by the sum of the byte counts
+ * of both, and the times by the sum of the times of both (the paper's normalisation, once per
+ * unit of measurement; a sum of 0 leaves zeros).  Network input: variant 1's eight, variant 2's eight.
+ *
+ * polydl_ranker_num_params: length of the parameter vector.
+ * polydl_ranker_set_params: copies the parameters (per layer: weights W[out][in] row-major, then
+ *   biases b[out]); count must equal polydl_ranker_num_params(), every value finite.  Until it
+ *   has succeeded once the calls below return POLYDL_ERR_UNSUPPORTED.  Process-wide.
+ * polydl_ranker_stats_conv2d: the statistics of one fp32 convolution variant (errors as
+ *   polydl_model_conv2d).
+ * polydl_ranker_play: one game; probs[2] (may be NULL) receives the two outputs, *winner (may be
+ *   NULL) 1, 2 or 0 for a draw.
+ * polydl_ranker_tournament: stats holds n * POLYDL_RANKER_STATS doubles, 0 <= n <= 4096.  Every
+ *   ordered pair (i first, j second), i != j, plays once: n*(n-1) games.  wins[n] (may be NULL)
+ *   receives the games each variant won, order[n] (may be NULL) the variants from most to fewest
+ *   wins, equal wins in the order given.
+ * polydl_pick_conv2d_learned: the tournament over the same candidates polydl_pick_conv2d ranks;
+ *   *cfg receives the winner, *report (may be NULL) its model report, *wins (may be NULL) its
+ *   games won out of *games (may be NULL) = 2 * (candidates - 1) played.  polydl_conv2d_fwd does
+ *   not use it: it is reported next to the model's pick and the sweep.
+ * POLYDL_ERR_BAD_DIMENSION for a wrong count, a negative or non-finite statistic or a theta
+ * outside [0, 1]. */
+#define POLYDL_RANKER_STATS 8
+int polydl_ranker_num_params(void);
+int polydl_ranker_set_params(const double *params, int count);
+int polydl_ranker_stats_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const polydl_tile_cfg *cfg, double *stats);
+int polydl_ranker_play(const double *stats1, const double *stats2, double theta, double *probs, int *winner);
+int polydl_ranker_tournament(int n, const double *stats, double theta, int *wins, int *order);
+int polydl_pick_conv2d_learned(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               double theta, polydl_tile_cfg *cfg, polydl_model_report *report, int *wins,
+                               int *games);
+
 /* ---- variant control (the sweep forces a variant; reports read back the one used) -----------
  * polydl_set_tile_override: cfg != NULL forces that variant for every later call of the
  * calling process (POLYDL_ERR_UNSUPPORTED if it is not a compiled variant; a later problem it

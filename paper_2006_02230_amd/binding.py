@@ -67,6 +67,17 @@ lib.polydl_model_conv2d_bf16.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), cty
 lib.polydl_pick_conv2d_bf16.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), ctypes.POINTER(ctypes.c_double)]
 lib.polydl_model_conv2d_bf16.restype = _i
 lib.polydl_pick_conv2d_bf16.restype = _i
+_dp, _ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)
+lib.polydl_ranker_num_params.argtypes = []
+lib.polydl_ranker_set_params.argtypes = [_dp, _i]
+lib.polydl_ranker_stats_conv2d.argtypes = [_i] * 9 + [ctypes.POINTER(TileCfg), _dp]
+lib.polydl_ranker_play.argtypes = [_dp, _dp, ctypes.c_double, _dp, _ip]
+lib.polydl_ranker_tournament.argtypes = [_i, _dp, ctypes.c_double, _ip, _ip]
+lib.polydl_pick_conv2d_learned.argtypes = [_i] * 9 + [ctypes.c_double, ctypes.POINTER(TileCfg),
+                                                      ctypes.POINTER(ModelReport), _ip, _ip]
+for _f in (lib.polydl_ranker_num_params, lib.polydl_ranker_set_params, lib.polydl_ranker_stats_conv2d,
+           lib.polydl_ranker_play, lib.polydl_ranker_tournament, lib.polydl_pick_conv2d_learned):
+    _f.restype = _i
 lib.polydl_nchw_to_nchwc.argtypes = [_i] * 5 + [_p, _p, _p]
 lib.polydl_nchwc_to_nchw.argtypes = [_i] * 5 + [_p, _p, _p]
 lib.polydl_kcrs_to_kcrsck.argtypes = [_i] * 6 + [_p, _p, _p]
@@ -338,6 +349,71 @@ def pick_conv2d(shape):
     _check(lib.polydl_pick_conv2d(*[int(v) for v in shape], ctypes.byref(cfg), ctypes.byref(rep)),
            "polydl_pick_conv2d")
     return cfg, rep
+
+
+RANKER_STATS = 8
+RANKER_PARAMS_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "ranker_params.txt")
+
+
+def _doubles(values, count=None):
+    values = [float(v) for v in values]
+    if count is not None and len(values) != count:
+        raise ValueError("expected %d values, got %d" % (count, len(values)))
+    return (ctypes.c_double * len(values))(*values)
+
+
+def ranker_num_params():
+    return lib.polydl_ranker_num_params()
+
+
+def ranker_set_params(params):
+    """polydl_ranker_set_params: load the pairwise network's parameters (flat sequence of floats)."""
+    buf = _doubles(params)
+    _check(lib.polydl_ranker_set_params(buf, len(buf)), "polydl_ranker_set_params")
+
+
+def ranker_load(path=None):
+    """Read a parameter file (one number per line, '#' comments) and load it into the library."""
+    vals = []
+    with open(path or RANKER_PARAMS_PATH) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                vals.append(float(line))
+    ranker_set_params(vals)
+
+
+def ranker_stats_conv2d(shape, cfg):
+    """polydl_ranker_stats_conv2d: the statistics of one variant the network is fed."""
+    out = (ctypes.c_double * RANKER_STATS)()
+    _check(lib.polydl_ranker_stats_conv2d(*[int(v) for v in shape], ctypes.byref(cfg), out),
+           "polydl_ranker_stats_conv2d")
+    return list(out)
+
+
+def ranker_play(stats1, stats2, theta=0.6):
+    """polydl_ranker_play: (winner, [p1, p2]); winner 1, 2 or 0 for a draw."""
+    probs, winner = (ctypes.c_double * 2)(), ctypes.c_int(-1)
+    _check(lib.polydl_ranker_play(_doubles(stats1, RANKER_STATS), _doubles(stats2, RANKER_STATS), theta, probs,
+                                  ctypes.byref(winner)), "polydl_ranker_play")
+    return winner.value, list(probs)
+
+
+def ranker_tournament(stats, theta=0.6):
+    """polydl_ranker_tournament over a list of statistics vectors: (wins, order)."""
+    n = len(stats)
+    flat = _doubles([v for s in stats for v in s], n * RANKER_STATS)
+    wins, order = (ctypes.c_int * max(n, 1))(), (ctypes.c_int * max(n, 1))()
+    _check(lib.polydl_ranker_tournament(n, flat, theta, wins, order), "polydl_ranker_tournament")
+    return list(wins)[:n], list(order)[:n]
+
+
+def pick_conv2d_learned(shape, theta=0.6):
+    """polydl_pick_conv2d_learned: (TileCfg, ModelReport, games won, games played) of the tournament's winner."""
+    cfg, rep, wins, games = TileCfg(), ModelReport(), ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib.polydl_pick_conv2d_learned(*[int(v) for v in shape], theta, ctypes.byref(cfg), ctypes.byref(rep),
+                                          ctypes.byref(wins), ctypes.byref(games)), "polydl_pick_conv2d_learned")
+    return cfg, rep, wins.value, games.value
 
 
 def model_conv2d_bf16(shape, cfg):

@@ -5,6 +5,7 @@
 #include <array>
 #include <map>
 #include <mutex>
+#include <vector>
 #include "internal.hpp"
 #include "variants.hpp"
 
@@ -457,6 +458,7 @@ int polydl_model_conv2d(int N, int C, int H, int W, int K, int R, int S, int str
     ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
     int rc = 0;
     if (cfg->algo == 1) rc = find_patch_variant(*cfg)->reg_class(q, cfg->cb < 2 ? 2 : cfg->cb);
+    if (rc < 0) return POLYDL_ERR_UNSUPPORTED;   // a stage of this depth does not fit the kernel's LDS or registers
     model_conv(q, *cfg, threads_of(*cfg), rc, report);
     return POLYDL_OK;
 }
@@ -482,6 +484,77 @@ int polydl_pick_conv2d(int N, int C, int H, int W, int K, int R, int S, int stri
     polydl_model_report rep;
     if (!pick_conv(q, cfg, &rep)) return POLYDL_ERR_UNSUPPORTED;
     if (report) *report = rep;
+    return POLYDL_OK;
+}
+
+int polydl_ranker_num_params(void) { return ranker_num_params(); }
+
+int polydl_ranker_set_params(const double *params, int count)
+{
+    if (!params) return POLYDL_ERR_NULL_POINTER;
+    if (count != ranker_num_params()) return POLYDL_ERR_BAD_DIMENSION;
+    for (int i = 0; i < count; ++i)
+        if (!(params[i] == params[i]) || params[i] > 1e300 || params[i] < -1e300) return POLYDL_ERR_BAD_DIMENSION;
+    ranker_set_params(params);
+    return POLYDL_OK;
+}
+
+int polydl_ranker_stats_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               const polydl_tile_cfg *cfg, double *stats)
+{
+    if (!stats) return POLYDL_ERR_NULL_POINTER;
+    polydl_model_report rep;
+    const int rc = polydl_model_conv2d(N, C, H, W, K, R, S, stride, pad, cfg, &rep);
+    if (rc != POLYDL_OK) return rc;
+    ranker_stats(rep, stats);
+    return POLYDL_OK;
+}
+
+static bool stats_ok(const double *stats, int64_t count)
+{
+    for (int64_t i = 0; i < count; ++i)
+        if (!(stats[i] >= 0) || stats[i] > 1e300) return false;   // also rejects NaN
+    return true;
+}
+
+int polydl_ranker_play(const double *stats1, const double *stats2, double theta, double *probs, int *winner)
+{
+    if (!stats1 || !stats2) return POLYDL_ERR_NULL_POINTER;
+    if (!stats_ok(stats1, POLYDL_RANKER_STATS) || !stats_ok(stats2, POLYDL_RANKER_STATS) || !(theta >= 0 && theta <= 1))
+        return POLYDL_ERR_BAD_DIMENSION;
+    return ranker_play(stats1, stats2, theta, probs, winner) ? POLYDL_OK : POLYDL_ERR_UNSUPPORTED;
+}
+
+int polydl_ranker_tournament(int n, const double *stats, double theta, int *wins, int *order)
+{
+    if (n < 0 || n > 4096) return POLYDL_ERR_BAD_DIMENSION;
+    if (n > 0 && !stats) return POLYDL_ERR_NULL_POINTER;
+    if (!stats_ok(stats, (int64_t)n * POLYDL_RANKER_STATS) || !(theta >= 0 && theta <= 1)) return POLYDL_ERR_BAD_DIMENSION;
+    return ranker_tournament(n, stats, theta, wins, order) ? POLYDL_OK : POLYDL_ERR_UNSUPPORTED;
+}
+
+int polydl_pick_conv2d_learned(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                               double theta, polydl_tile_cfg *cfg, polydl_model_report *report, int *wins,
+                               int *games)
+{
+    int64_t P, Q;
+    if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
+    if (!cfg) return POLYDL_ERR_NULL_POINTER;
+    if (!(theta >= 0 && theta <= 1)) return POLYDL_ERR_BAD_DIMENSION;
+    if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q) || !ranker_ready()) return POLYDL_ERR_UNSUPPORTED;
+    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
+    std::vector<ConvCandidate> cands;
+    conv_candidates(q, &cands);
+    if (cands.empty()) return POLYDL_ERR_UNSUPPORTED;
+    const int n = (int)cands.size();
+    std::vector<double> stats((size_t)n * POLYDL_RANKER_STATS);
+    for (int i = 0; i < n; ++i) ranker_stats(cands[i].rep, &stats[(size_t)i * POLYDL_RANKER_STATS]);
+    std::vector<int> w(n), order(n);
+    if (!ranker_tournament(n, stats.data(), theta, w.data(), order.data())) return POLYDL_ERR_UNSUPPORTED;
+    *cfg = cands[order[0]].cfg;
+    if (report) *report = cands[order[0]].rep;
+    if (wins) *wins = w[order[0]];
+    if (games) *games = 2 * (n - 1);
     return POLYDL_OK;
 }
 

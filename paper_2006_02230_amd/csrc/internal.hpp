@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <vector>
 #include "../../include/polydl.h"
 
 namespace polydl {
@@ -107,6 +108,18 @@ void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads,
 double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads);   // predicted microseconds
 bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);   // q.pre_act: gather kernel only
 bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *rep);
+struct ConvCandidate { polydl_tile_cfg cfg; polydl_model_report rep; };
+// every (variant, stage depth, split factor, leftover-tile switch) pick_conv ranks, with its model report
+void conv_candidates(const ConvProblem &q, std::vector<ConvCandidate> *out);
+
+// ranker.cpp
+int ranker_num_params();
+void ranker_set_params(const double *params);   // ranker_num_params() doubles, copied
+bool ranker_ready();
+void ranker_stats(const polydl_model_report &r, double *stats);   // POLYDL_RANKER_STATS doubles
+// false while no parameters are loaded
+bool ranker_play(const double *stats1, const double *stats2, double theta, double *probs, int *winner);
+bool ranker_tournament(int n, const double *stats, double theta, int *wins, int *order);
 
 // Exact unsigned division by a runtime constant d for dividends n with n*d < 2^32:
 // n / d == (n * magic) >> 32 with magic = floor(2^32 / d) + 1.

@@ -389,10 +389,10 @@ void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads,
 
 static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
 
-bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *best_rep)
+void conv_candidates(const ConvProblem &q, std::vector<ConvCandidate> *out)
 {
-    bool have = false;
-    polydl_model_report rep;
+    out->clear();
+    ConvCandidate cand;
     const int cpad = (q.C + 1) & ~1;
     // the patch kernel copies input rows straight into LDS and cannot touch them on the way
     for (int i = 0; i < (q.pre_act ? 0 : kNumPatchVariants); ++i) {
@@ -404,9 +404,9 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
             const int nstages = (q.C + cb - 1) / cb;
             for (int sk : kSplits) {
                 if (sk > nstages) break;
-                polydl_tile_cfg c = {v.bm, v.bn, 0, v.wm, v.wn, sk, 0, 0, 1, cb};
-                model_conv(q, c, v.threads, rc, &rep);
-                if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
+                cand.cfg = {v.bm, v.bn, 0, v.wm, v.wn, sk, 0, 0, 1, cb};
+                model_conv(q, cand.cfg, v.threads, rc, &cand.rep);
+                out->push_back(cand);
             }
         }
     }
@@ -416,19 +416,31 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
         const long stages = (Kg + v.bk - 1) / v.bk;
         for (int sk : kSplits) {
             if (sk > stages) break;
-            polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0};
-            model_conv(q, c, v.threads, 0, &rep);
-            if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
+            cand.cfg = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0};
+            model_conv(q, cand.cfg, v.threads, 0, &cand.rep);
+            out->push_back(cand);
             // the same with the leftover tiles of the last round split (wave tiles up to 64x32:
             // with larger ones the pieces measured slower than the round they save)
             if (sk == 1 && v.wm * v.wn <= 64 * 32) {
-                c.raster = 2;
-                model_conv(q, c, v.threads, 0, &rep);
-                if (rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; }
+                cand.cfg.raster = 2;
+                model_conv(q, cand.cfg, v.threads, 0, &cand.rep);
+                out->push_back(cand);
             }
         }
     }
-    return have;
+}
+
+bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report *best_rep)
+{
+    std::vector<ConvCandidate> cands;
+    conv_candidates(q, &cands);
+    const ConvCandidate *b = nullptr;
+    for (const ConvCandidate &c : cands)
+        if (!b || c.rep.predicted_us < b->rep.predicted_us) b = &c;
+    if (!b) return false;
+    *best = b->cfg;
+    *best_rep = b->rep;
+    return true;
 }
 
 bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *best_rep)
