@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "af6b65fa4a8875b5dd66036cf7f839ad3f59095f2aeafe2a805c69a5954657d3", "batch": 32, "fetch_bytes": 742725096, "write_bytes": 457842312}
+HBM_TRAFFIC = {"csrc_sha256": "9ca7ceb83d14396b5ca428102de53781ffddcfad7503b7354ab66b7d1bcbfc94", "batch": 32, "fetch_bytes": 742890082, "write_bytes": 457804552}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000

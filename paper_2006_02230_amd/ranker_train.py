@@ -8,6 +8,8 @@ measured sweeps of this library's own convolution variants, and report how its p
 --import-sweeps  packs sweep files into ranker_data/conv_fp32_sweeps.json (shape, variant, microseconds).
 --train          fits the network and writes ranker_params.txt, the file ranker_load() reads.
 --report FILE    evaluates the parameters on disk and writes a markdown summary.
+--sizes-only     the paper's own inputs: the three times are withheld (set to 0) from training and
+                 evaluation; nothing is written, the figures are printed (with --train).
 
 Following the experimental set-up section of the paper, 70 % of the code versions (drawn at random,
 seeded) form the training set and one network serves all problems.  A training example is an
@@ -48,7 +50,7 @@ def import_sweeps(paths, out_path=DATA):
     return len(problems), sum(len(p["rows"]) for p in problems)
 
 
-def load_table(path=DATA):
+def load_table(path=DATA, sizes_only=False):
     """Arrays over all measured variants: problem index, microseconds, model prediction, statistics."""
     data = json.load(open(path))
     assert data["fields"] == CFG_FIELDS + ["us"]
@@ -67,8 +69,10 @@ def load_table(path=DATA):
             pred.append(rep.predicted_us)
             stats.append(P.ranker_stats_conv2d(shape, cfg))
             cfgs.append(cfg)
-    return (np.array(group), np.array(us, dtype=np.float64), np.array(pred), np.array(stats, dtype=np.float64),
-            cfgs, shapes)
+    stats = np.array(stats, dtype=np.float64)
+    if sizes_only:
+        stats[:, N_SIZES:] = 0.0
+    return np.array(group), np.array(us, dtype=np.float64), np.array(pred), stats, cfgs, shapes
 
 
 def split_mask(n, seed):
@@ -184,13 +188,17 @@ def write_params(flat, path, note):
             f.write("%.17g\n" % x)
 
 
-def evaluate(table, seed=0, theta=0.6):
-    """Uses the parameters loaded in the library.  Returns a dict of figures and per-problem rows."""
+def read_params(path):
+    with open(path) as f:
+        return [float(l) for l in f if l.strip() and not l.startswith("#")]
+
+
+def evaluate(table, flat, seed=0, theta=0.6):
+    """Loads the parameters into the library, which plays the tournaments.  Returns a dict of figures
+    and per-problem rows."""
     group, us, pred, stats, cfgs, shapes = table
     train_mask = split_mask(len(us), seed)
-    flat = []
-    with open(P.RANKER_PARAMS_PATH) as f:
-        flat = [float(l) for l in f if l.strip() and not l.startswith("#")]
+    P.ranker_set_params(flat)
     layers = unflatten(flat)
     out = {"rows": []}
     for name, sel in (("train", train_mask), ("held_out", ~train_mask)):
@@ -222,7 +230,7 @@ def evaluate(table, seed=0, theta=0.6):
     return out
 
 
-def write_report(res, path, command):
+def write_report(res, path, command, note=""):
     def name(c):
         if c["algo"] == 1:
             return "patch %dx%d/%dx%d cb %d split %d" % (c["bm"], c["bn"], c["wm"], c["wn"], c["cb"], c["split_k"])
@@ -248,6 +256,8 @@ def write_report(res, path, command):
              % (len(res["rows"]), res["mean_learned_all"], res["max_learned_all"], res["mean_model_all"],
                 res["max_model_all"], res["mean_learned_held"], res["max_learned_held"], res["mean_model_held"],
                 res["max_model_held"], res["mean_learned_top5pct_all"], res["max_learned_top5pct_all"]))
+    if note:
+        o.append("\n" + note)
     with open(path, "w") as f:
         f.write("\n".join(o) + "\n")
 
@@ -258,13 +268,21 @@ def main():
     ap.add_argument("--train", action="store_true")
     ap.add_argument("--report", default="")
     ap.add_argument("--report-command", default="", help="text of the commands, quoted in the report")
+    ap.add_argument("--report-note", default="", help="a closing paragraph for the report")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--epochs", type=int, default=30)
     ap.add_argument("--margin", type=float, default=0.01)
+    ap.add_argument("--sizes-only", action="store_true")
     args = ap.parse_args()
     if args.import_sweeps:
         files = [f for pat in args.import_sweeps for f in sorted(glob.glob(pat))]
         print("packed %d problems, %d measured variants" % import_sweeps(files))
+    if args.sizes_only:
+        table = load_table(sizes_only=True)
+        flat = train(table, args.seed, args.epochs, margin=args.margin)
+        res = evaluate(table, flat, args.seed)
+        print(json.dumps({k: v for k, v in res.items() if k != "rows"}))
+        return
     table = None
     if args.train:
         table = load_table()
@@ -274,9 +292,8 @@ def main():
                       % (len(table[1]), len(table[5]), args.seed, args.epochs)])
     if args.report:
         table = table or load_table()
-        P.ranker_load()
-        res = evaluate(table, args.seed)
-        write_report(res, args.report, args.report_command)
+        res = evaluate(table, read_params(P.RANKER_PARAMS_PATH), args.seed)
+        write_report(res, args.report, args.report_command, args.report_note)
         print(json.dumps({k: v for k, v in res.items() if k != "rows"}))
 
 
