@@ -67,7 +67,14 @@ typedef struct polydl_tile_cfg {
                          reduction (summed through scratch tiles in a fixed order) */
     int algo;         /* convolution only.  0: im2col columns gathered element by element from
                          HBM (any shape); 1: input rows staged once per workgroup in LDS and the
-                         taps formed on the LDS read (bk is ignored, the stage is cb channels)  */
+                         taps formed on the LDS read (bk is ignored, the stage is cb channels);
+                         2: pointwise kernel for R = S = 1, stride 1, pad 0, C in {16, 32, 64},
+                         K a multiple of 64 with 128 <= K and K*C <= 16384, H*W even, tensors
+                         below 2 GiB, in/out 8-byte and wt/bias 16-byte aligned: the filter
+                         stays in LDS, a wave loads 64 pixels straight into registers and forms
+                         the output channels 64 at a time.  One variant (bm = bn = wm = wn = 64,
+                         bk = 0, split_k = 1, raster = 0, cb = 0); forced on any other problem the
+                         call returns POLYDL_ERR_UNSUPPORTED */
     int cb;           /* algo 1: input channels per stage, even, >= 2; 0 lets the library choose */
 } polydl_tile_cfg;
 
@@ -94,7 +101,7 @@ int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int s
  * follows it): out = act(conv(pre_act(in)) + bias), where pre_act (a polydl_act) is applied to
  * every input element as it is read, so the activated input is never written to memory.  Padding
  * contributes zeros (ReLU and ReLU6 of zero).  Served by the gather kernel (algo 0) only: with a
- * forced algo 1 variant and pre_act != POLYDL_ACT_NONE the call returns POLYDL_ERR_UNSUPPORTED. */
+ * forced algo 1 or algo 2 variant and pre_act != POLYDL_ACT_NONE the call returns POLYDL_ERR_UNSUPPORTED. */
 int polydl_conv2d_fwd_pre_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                               const float *in, const float *wt, const float *bias, float *out,
                               int pre_act /* polydl_act */, int act /* polydl_act */, void *stream);

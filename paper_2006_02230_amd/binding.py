@@ -445,7 +445,9 @@ def conv_candidates(shape):
     cpad = (C + 1) & ~1
     out = []
     for v in variants(0):
-        if v.algo == 1:
+        if v.algo == 2:
+            out.append(v)                      # pointwise kernel: one shape, no knobs
+        elif v.algo == 1:
             for cb in range(2, min(cpad, 64) + 1, 2):
                 if cpad % cb:
                     continue

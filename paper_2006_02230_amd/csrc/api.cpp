@@ -188,7 +188,28 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
             g_conv_plans[key] = cfg;
         }
     }
+    const bool point_aligned = !(((uintptr_t)in | (uintptr_t)out) & 7) && !((uintptr_t)wt & 15) && !((uintptr_t)bias & 15);
+    if (!forced && cfg.algo == 2 && !point_aligned) {
+        // the pointwise kernel moves pixel pairs as 8-byte words and filter and bias as 16-byte
+        // words: for tensors aligned to less take the best of the other candidates (not cached:
+        // the plan is about shapes)
+        std::vector<ConvCandidate> cands;
+        conv_candidates(q, &cands);
+        const ConvCandidate *b = nullptr;
+        for (const ConvCandidate &c : cands)
+            if (c.cfg.algo != 2 && (!b || c.rep.predicted_us < b->rep.predicted_us)) b = &c;
+        if (!b) return POLYDL_ERR_UNSUPPORTED;
+        cfg = b->cfg;
+    }
     if (cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
+    if (cfg.algo == 2) {
+        if (!is_conv_point_cfg(cfg) || !conv_point_fits(q) || !point_aligned) return POLYDL_ERR_UNSUPPORTED;
+        hipError_t pe = conv_point_launch(q, (hipStream_t)stream);
+        if (pe != hipSuccess) return launch_failed(pe);
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_last = cfg;
+        return POLYDL_OK;
+    }
     if (cfg.algo == 1) {
         if (pre_act != POLYDL_ACT_NONE) return POLYDL_ERR_UNSUPPORTED;   // a forced patch-kernel variant
         const PatchVariant *pv = find_patch_variant(cfg);
@@ -452,10 +473,16 @@ int polydl_model_conv2d(int N, int C, int H, int W, int K, int R, int S, int str
     int64_t P, Q;
     if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
     if (!cfg || !report) return POLYDL_ERR_NULL_POINTER;
-    const bool known = cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
-                                      : (cfg->algo == 0 && find_variant(*cfg) != nullptr);
+    const bool known = cfg->algo == 2 ? is_conv_point_cfg(*cfg)
+                                      : (cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
+                                                        : (cfg->algo == 0 && find_variant(*cfg) != nullptr));
     if (!known || !conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
     ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
+    if (cfg->algo == 2) {
+        if (!conv_point_fits(q)) return POLYDL_ERR_UNSUPPORTED;
+        model_conv_point(q, report);
+        return POLYDL_OK;
+    }
     int rc = 0;
     if (cfg->algo == 1) rc = find_patch_variant(*cfg)->reg_class(q, cfg->cb < 2 ? 2 : cfg->cb);
     if (rc < 0) return POLYDL_ERR_UNSUPPORTED;   // a stage of this depth does not fit the kernel's LDS or registers
@@ -622,8 +649,9 @@ int polydl_set_tile_override(const polydl_tile_cfg *cfg)
         g_have_override = false;
         return POLYDL_OK;
     }
-    const bool known = cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
-                                      : (cfg->algo == 0 && find_variant(*cfg) != nullptr);
+    const bool known = cfg->algo == 2 ? is_conv_point_cfg(*cfg)
+                                      : (cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
+                                                        : (cfg->algo == 0 && find_variant(*cfg) != nullptr));
     if (!known || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
         cfg->raster > 2 || (cfg->raster == 2 && cfg->algo != 0) || cfg->cb < 0 || (cfg->cb & 1))
         return POLYDL_ERR_UNSUPPORTED;
@@ -642,7 +670,7 @@ int polydl_get_last_tile(polydl_tile_cfg *cfg)
 
 int polydl_num_variants(int kind)
 {
-    if (kind == 0) return kNumVariants + kNumPatchVariants;
+    if (kind == 0) return kNumVariants + kNumPatchVariants + 1;   // the last one is the pointwise kernel
     if (kind == 2) return kNumPatchBf16Variants;
     return kind == 1 ? kNumVariants : POLYDL_ERR_UNSUPPORTED;
 }
@@ -655,7 +683,8 @@ int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg)
         cfg_of_patch(kPatchBf16Variants[index], 0, 0, cfg);
         cfg->layout = 1;
     } else if (index < kNumVariants) cfg_of(kVariants[index], 1, 0, 0, cfg);
-    else cfg_of_patch(kPatchVariants[index - kNumVariants], 0, 0, cfg);
+    else if (index < kNumVariants + kNumPatchVariants) cfg_of_patch(kPatchVariants[index - kNumVariants], 0, 0, cfg);
+    else *cfg = conv_point_cfg();
     return POLYDL_OK;
 }
 

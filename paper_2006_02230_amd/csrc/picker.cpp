@@ -202,6 +202,9 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
     if (c.rounds) {
         // nothing streams the tensors faster than this, with the first and last touches exposed
         mem_us = std::max(mem_us, (s.a_bytes + s.b_bytes + s.d_bytes) / 5500.0 * 1e-3 + 2.0);
+        // a layer that mostly writes is slower than that: measured on the pointwise layers of the
+        // suite (batch 16 .. 128, either kernel), the output leaves at about 3.15 TB/s
+        mem_us = std::max(mem_us, (s.a_bytes + s.b_bytes) / 20000.0 * 1e-3 + s.d_bytes / 3150.0 * 1e-3 + 2.0);
         if (c.split_k > 1) fixed += c.split_c0 + c.split_c1 * c.split_k * s.d_bytes * 1e-6;
     } else if (c.split_k > 1) {
         // every part writes its accumulator tile once, coalesced; the last part of each tile reads
@@ -389,10 +392,49 @@ void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads,
 
 static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
 
+// Pointwise kernel (filter resident in LDS, pixels loaded straight into registers): a unit is
+// 64 pixels x 64 output channels, C/2 * 4 matrix instructions; units are dealt to the waves in
+// equal runs, so the busiest SIMD runs ceil(units / SIMDs) of them one after another.  The tensors
+// are streamed once.
+void model_conv_point(const ConvProblem &q, polydl_model_report *r)
+{
+    std::memset(r, 0, sizeof(*r));
+    uint32_t units, wgs;
+    conv_point_shape(q, kCUs, &units, &wgs);
+    const double pixels = (double)q.N * q.H * q.W;
+    const double in_bytes = pixels * q.C * 4, out_bytes = pixels * q.K * 4, wt_bytes = (double)q.K * q.C * 4;
+    const double unit_us = (q.C / 2.0) * 4.0 * 64.0 / kClockHz * 1e6;
+    const double per_simd = std::ceil((double)units / (kCUs * kSimdsPerCU));
+    r->mfma_us = per_simd * unit_us / 0.85;
+    // measured over batch sizes 16 .. 128 on 64 -> 64 and 64 -> 256 channels at 56 x 56 (back-to-back
+    // launches on the same buffers): the time follows the bytes written, at 3.3 TB/s; the input,
+    // re-read from the last-level cache, hardly shows
+    r->mem_us = (in_bytes + wt_bytes) / 20000.0 * 1e-3 + out_bytes / 3300.0 * 1e-3;
+    // launch, filling LDS with the filter (more of it with more channel groups), first loads, last stores
+    r->fixed_us = 7.0 + 0.5 * (q.K / 64 - 1);
+    r->predicted_us = std::max(r->mfma_us, r->mem_us) + r->fixed_us;
+    r->workgroups = (int)wgs;
+    r->simd_load = per_simd;
+    // working sets: accumulators of a unit; the pixel registers reused by the channel groups; the
+    // filter in LDS reused by every unit; the whole problem
+    const double ws[4] = {64.0 * 64 * 4, 64.0 * q.C * 4, wt_bytes, in_bytes + out_bytes + wt_bytes};
+    double sizes[4], weights[4];
+    for (int i = 0; i < 4; ++i) { sizes[i] = kLevels[i].capacity; weights[i] = 1.0 / kLevels[i].gbytes_per_s; }
+    reuse_bucket(4, ws, 4, sizes, r->level_bytes, &r->mem_bytes);
+    r->eq1_cost = reuse_cost(4, r->level_bytes, r->mem_bytes, weights, 1.0 / kHbmGBs);
+    r->n_ws = 4;
+    for (int i = 0; i < 4; ++i) r->ws[i] = ws[i];
+}
+
 void conv_candidates(const ConvProblem &q, std::vector<ConvCandidate> *out)
 {
     out->clear();
     ConvCandidate cand;
+    if (conv_point_fits(q)) {
+        cand.cfg = conv_point_cfg();
+        model_conv_point(q, &cand.rep);
+        out->push_back(cand);
+    }
     const int cpad = (q.C + 1) & ~1;
     // the patch kernel copies input rows straight into LDS and cannot touch them on the way
     for (int i = 0; i < (q.pre_act ? 0 : kNumPatchVariants); ++i) {

@@ -50,7 +50,7 @@ def test_variant_table(lib):
     import paper_2006_02230_amd as p
     vs = p.variants(0)
     assert len(vs) >= 4 and len(vs) > len(p.variants(1))
-    assert {v.algo for v in vs} == {0, 1}
+    assert {v.algo for v in vs} == {0, 1, 2}
     for v in vs:
         assert v.bm % v.wm == 0 and v.bn % v.wn == 0 and v.bk % 8 == 0
     bad = p.TileCfg(17, 64, 16, 32, 32, 1, 0, 0, 0, 0)

@@ -25,8 +25,8 @@ def run_conv(P, s, x, w, b=None, act=None):
 
 def try_variant(P, v, s, x, w, b=None, act=None):
     """Run one forced variant; None if that variant declares the problem outside its limits."""
-    P.set_tile_override(v)
     try:
+        P.set_tile_override(v)
         return run_conv(P, s, x, w, b, act)
     except P.PolydlError as e:
         if e.status == -3:
@@ -51,7 +51,7 @@ SMALL = [
 def test_all_variants_random(P, s):
     x, w, b = synth.conv_inputs(s, seed=31, dist="normal", bias=True)
     want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
-    ran = {0: 0, 1: 0}
+    ran = {0: 0, 1: 0, 2: 0}
     for v in P.variants(0):
         for raster in (0, 1):
             v.raster = raster
@@ -148,6 +148,8 @@ def test_split_k_random(P):
     want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1)
     want_r, ab_r = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1, act="relu")
     for v in P.variants(0):
+        if v.algo == 2:
+            continue            # the pointwise kernel has no split
         v.split_k = 4
         got = try_variant(P, v, s, x, w, b)
         assert got is not None and oracle.scaled_error(got, want, ab) <= FP32_TOL, v
@@ -298,6 +300,8 @@ def test_activation_before_the_convolution(P, s):
         want, ab = oracle.conv2d_fwd(xa, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
         ran = 0
         for v in P.variants(0):
+            if v.algo == 2:
+                continue        # pointwise kernel: no split, no operator on the way in (covered by its own tests)
             P.set_tile_override(v)
             for split_k in (1, 2):
                 v.split_k = split_k
@@ -350,6 +354,77 @@ def test_random_shapes_through_the_picker(P):
         tile = P.get_last_tile()
         seen.add((tile.algo, tile.bm, tile.bn, tile.split_k > 1, tile.raster))
     assert len(seen) >= 2      # whole and split reductions at least
+
+
+POINTWISE = [
+    synth.ConvShape("c64", 2, 64, 56, 56, 128, 1, 1, 1, 0),        # 98 tiles of 64 pixels, two channel groups
+    synth.ConvShape("groups", 1, 64, 7, 6, 256, 1, 1, 1, 0),        # 42 pixels: one ragged tile, four channel groups
+    synth.ConvShape("c32", 3, 32, 5, 4, 128, 1, 1, 1, 0),          # tiles straddle images (20 pixels each)
+    synth.ConvShape("c16", 5, 16, 9, 2, 1024, 1, 1, 1, 0),         # sixteen groups, filter fills LDS
+    synth.ConvShape("many", 16, 16, 64, 66, 192, 1, 1, 1, 0),      # 3168 units for 2048 waves: runs of one and two
+]
+
+
+def point_variant(P):
+    v = [v for v in P.variants(0) if v.algo == 2]
+    assert len(v) == 1
+    return v[0]
+
+
+@pytest.mark.parametrize("s", POINTWISE, ids=lambda s: s.name)
+def test_pointwise_kernel(P, s):
+    v = point_variant(P)
+    x, w, b = synth.conv_inputs(s, seed=71, dist="normal", bias=True)
+    for act, bias in (("relu", b), (None, None), ("relu6", b)):
+        want, ab = oracle.conv2d_fwd(x, w, bias=bias, stride=1, pad=0, act=act)
+        got = try_variant(P, v, s, x, w, bias, act=act)
+        assert got is not None and P.get_last_tile().algo == 2
+        assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (s.name, act)
+    # exact cases: small integers, and a one-hot filter that copies one input channel
+    xi, wi, bi = synth.conv_inputs(s, seed=72, dist="ints", bias=True)
+    want, _ = oracle.conv2d_fwd(xi, wi, bias=bi, stride=1, pad=0)
+    assert np.array_equal(try_variant(P, v, s, xi, wi, bi).astype(np.float64), want)
+    w1 = np.zeros_like(w)
+    w1[s.K - 1, s.C - 3, 0, 0] = 1.0
+    got = try_variant(P, v, s, x, w1)
+    assert np.array_equal(got[:, s.K - 1], x[:, s.C - 3]) and not got[:, :s.K - 1].any()
+    P.set_tile_override(None)
+
+
+def test_pointwise_kernel_limits_and_fallback(P):
+    import torch
+    v = point_variant(P)
+    # shapes it does not take: odd pixel count, stride 2, 3x3, channel counts outside its family
+    for s in (synth.ConvShape("odd", 1, 64, 7, 7, 64, 1, 1, 1, 0), synth.ConvShape("s2", 1, 64, 8, 8, 64, 1, 1, 2, 0),
+              synth.ConvShape("k3", 1, 64, 8, 8, 64, 3, 3, 1, 1), synth.ConvShape("c24", 1, 24, 8, 8, 64, 1, 1, 1, 0),
+              synth.ConvShape("k96", 1, 64, 8, 8, 96, 1, 1, 1, 0), synth.ConvShape("big", 1, 64, 8, 8, 512, 1, 1, 1, 0),
+              synth.ConvShape("k64", 1, 64, 8, 8, 64, 1, 1, 1, 0)):
+        x, w, _ = synth.conv_inputs(s, seed=73, dist="normal")
+        assert try_variant(P, v, s, x, w) is None, s.name
+        with pytest.raises(P.PolydlError):
+            P.model_conv2d(tuple(s)[1:], v)
+    P.set_tile_override(None)
+    # a problem where the picker chooses it (64 -> 256 channels at 56 x 56, batch 64), checked on sampled
+    # outputs; with tensors that are only 4-byte aligned the call still succeeds through another kernel
+    s = synth.ConvShape("pick", 64, 64, 56, 56, 256, 1, 1, 1, 0)
+    cfg, _ = P.pick_conv2d(tuple(s)[1:])
+    assert cfg.algo == 2
+    x, w, b = synth.conv_inputs(s, seed=74, dist="normal", bias=True)
+    idx = sample_indices(s.N * s.K * s.H * s.W, 4096, seed=75)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=0, act="relu", at=idx)
+    got = run_conv(P, s, x, w, b, act="relu")
+    assert P.get_last_tile().as_dict() == cfg.as_dict()
+    assert oracle.scaled_error(got.reshape(-1)[idx], want, ab) <= FP32_TOL
+    xd = torch.empty(x.size + 1, dtype=torch.float32, device="cuda")[1:].view(x.shape)
+    xd.copy_(torch.from_numpy(x))
+    assert xd.data_ptr() % 8 == 4
+    got = host(P.conv2d_fwd(xd, dev(w), dev(b), stride=1, pad=0, act="relu"))
+    assert P.get_last_tile().algo != 2
+    assert oracle.scaled_error(got.reshape(-1)[idx], want, ab) <= FP32_TOL
+    P.set_tile_override(v)
+    with pytest.raises(P.PolydlError):
+        P.conv2d_fwd(xd, dev(w), dev(b), stride=1, pad=0, act="relu")
+    P.set_tile_override(None)
 
 
 def test_argument_errors(P):
