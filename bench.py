@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "9ca7ceb83d14396b5ca428102de53781ffddcfad7503b7354ab66b7d1bcbfc94", "batch": 32, "fetch_bytes": 742890082, "write_bytes": 457804552}
+HBM_TRAFFIC = {"csrc_sha256": "0aa65605d9ebbf1bb492c83fa4b93cd0493a5dcbd5827f318270e80edaf3192d", "batch": 32, "fetch_bytes": 743100103, "write_bytes": 457826896}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
