@@ -72,7 +72,7 @@ typedef struct polydl_tile_cfg {
                          K a multiple of 64 with 128 <= K and K*C <= 16384, H*W even, tensors
                          below 2 GiB, in/out 8-byte and wt/bias 16-byte aligned: the filter
                          stays in LDS, a wave loads 64 pixels straight into registers and forms
-                         the output channels 64 at a time.  One variant (bm = bn = wm = wn = 64,
+                         the output channels 32 at a time.  One variant (bm = wm = 32, bn = wn = 64,
                          bk = 0, split_k = 1, raster = 0, cb = 0); forced on any other problem the
                          call returns POLYDL_ERR_UNSUPPORTED */
     int cb;           /* algo 1: input channels per stage, even, >= 2; 0 lets the library choose */

@@ -8,9 +8,10 @@
 //   * a wave owns 64 pixels at a time and loads their C channels from global memory straight
 //     into the registers the matrix instruction reads -- lane j of each half-wave holds pixels
 //     2j and 2j+1 (one 8-byte load per channel pair), the half-waves hold even and odd channels;
-//   * with those registers it produces the output channels in groups of 64 (accumulators: 2x2
-//     blocks of 32x32), bias and activation applied on the way out (section "Operator Fusion"),
-//     each lane storing its two pixels of a channel row as one 8-byte store;
+//   * with those registers it produces the output channels in groups of 32 (accumulators: two
+//     blocks of 32x32, one per pixel of the lane's pair; groups of 64 measured 10 % slower), bias
+//     and activation applied on the way out (section "Operator Fusion"), each lane storing its
+//     two pixels of a channel row as one 8-byte store;
 //   * (pixel tile, channel group) units are dealt to the waves of a grid that fits the chip once
 //     in contiguous, equal runs, so a wave reloads pixels only when its run crosses a tile.
 // No barrier after the filter is in LDS; waves never wait for each other.
@@ -24,7 +25,7 @@ struct ConvPointKArgs {
     const float *in, *wt, *bias;
     float *out;
     int N, C, K, HW;
-    int groups;             // K / 64
+    int groups;             // K / 32
     uint32_t units;         // pixel tiles * groups
     uint32_t per, rem;      // units per wave; the first rem waves take one more
     uint32_t recip_groups, recip_HW;
@@ -40,21 +41,19 @@ __device__ __forceinline__ v2f buf_load2(__amdgpu_buffer_rsrc_t r, uint32_t byte
 
 template <int ACT>
 __device__ __forceinline__ void point_store(__amdgpu_buffer_rsrc_t ro, uint32_t vo, uint32_t row_bytes, int k0,
-                                            const v4f (&bias)[2][4], const v16f (&acc)[2][2])
+                                            const v4f (&bias)[4], const v16f (&acc)[2])
 {
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int q = 0; q < 4; ++q) {
+        // accumulator registers 4q .. 4q+3 are four consecutive channels
+        const int kq = k0 + 8 * q;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            // accumulator registers 4q .. 4q+3 are four consecutive channels
-            const int kq = k0 + mb * 32 + 8 * q;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = 4 * q + i;
-                v2f v = {act_of<ACT>(acc[mb][0][r] + bias[mb][q][i]), act_of<ACT>(acc[mb][1][r] + bias[mb][q][i])};
-                buf_store2(ro, vo, (uint32_t)(kq + i) * row_bytes, v);
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int r = 4 * q + i;
+            v2f v = {act_of<ACT>(acc[0][r] + bias[q][i]), act_of<ACT>(acc[1][r] + bias[q][i])};
+            buf_store2(ro, vo, (uint32_t)(kq + i) * row_bytes, v);
         }
+    }
 }
 
 // C8 = C / 8.  256 threads; LDS holds wt as float4 At[C8][2][K]:
@@ -102,12 +101,10 @@ __global__ __launch_bounds__(256, 2) void conv_point_kernel(const ConvPointKArgs
     uint32_t tile = div_by(u, (uint32_t)p.groups, p.recip_groups, g);
     uint32_t have = 0xFFFFFFFFu, vo = kOobOffset;
     v2f b[C8 * 4];
-    // the lane's 32 bias values of a channel group (zeros without a bias)
-    v4f bias[2][4];
+    // the lane's 16 bias values of a channel group (zeros without a bias)
+    v4f bias[4];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) bias[mb][q] = buf_load4(rb, (uint32_t)(g * 64 + mb * 32 + 8 * q + 4 * half) * 4u);
+    for (int q = 0; q < 4; ++q) bias[q] = buf_load4(rb, (uint32_t)(g * 32 + 8 * q + 4 * half) * 4u);
     for (; u < end; ++u) {
         if (tile != have) {
             // the lane's two pixels: 2j and 2j+1 of the tile, in one image since H*W is even
@@ -123,40 +120,30 @@ __global__ __launch_bounds__(256, 2) void conv_point_kernel(const ConvPointKArgs
         }
         // the next unit's bias values travel while this unit's products are formed
         const uint32_t gn = g + 1 == (uint32_t)p.groups ? 0u : g + 1;
-        v4f bias_next[2][4];
+        v4f bias_next[4];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int q = 0; q < 4; ++q) bias_next[q] = buf_load4(rb, (uint32_t)(gn * 32 + 8 * q + 4 * half) * 4u);
+        v16f acc[2];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                bias_next[mb][q] = buf_load4(rb, (uint32_t)(gn * 64 + mb * 32 + 8 * q + 4 * half) * 4u);
-        v16f acc[2][2];
+        for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
-        const v4f *a_base = At + half * K + g * 64 + j;
+            for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+        const v4f *a_base = At + half * K + g * 32 + j;
 #pragma unroll
         for (int sg = 0; sg < C8; ++sg) {
+            const v4f a = a_base[sg * 2 * K];
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                const v4f a = a_base[sg * 2 * K + mb * 32];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].x, acc[mb][0], 0, 0, 0);
-                    acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].y, acc[mb][1], 0, 0, 0);
-                }
+            for (int i = 0; i < 4; ++i) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].x, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].y, acc[1], 0, 0, 0);
             }
         }
-        const int k0 = (int)g * 64;
+        const int k0 = (int)g * 32;
         if (p.act == POLYDL_ACT_NONE) point_store<POLYDL_ACT_NONE>(ro, vo, row_bytes, k0, bias, acc);
         else if (p.act == POLYDL_ACT_RELU) point_store<POLYDL_ACT_RELU>(ro, vo, row_bytes, k0, bias, acc);
         else point_store<POLYDL_ACT_RELU6>(ro, vo, row_bytes, k0, bias, acc);
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) bias[mb][q] = bias_next[mb][q];
+        for (int q = 0; q < 4; ++q) bias[q] = bias_next[q];
         if (++g == (uint32_t)p.groups) { g = 0; ++tile; }
     }
 }
@@ -166,8 +153,8 @@ bool conv_point_fits(const ConvProblem &q)
     const int64_t HW = (int64_t)q.H * q.W;
     if (q.R != 1 || q.S != 1 || q.stride != 1 || q.pad != 0 || q.pre_act != POLYDL_ACT_NONE) return false;
     if (q.C != 16 && q.C != 32 && q.C != 64) return false;
-    // at least two channel groups share the pixels a wave holds (with one group the kernel measured
-    // no faster than the staged one); the filter has to fit the 64 KB of LDS
+    // at least four channel groups share the pixels a wave holds (with 64 output channels the kernel
+    // measured no faster than the staged one); the filter has to fit the 64 KB of LDS
     if (q.K % 64 != 0 || q.K < 128 || (int64_t)q.K * q.C > 16384) return false;
     if (HW % 2 != 0) return false;
     // every byte offset, tile base and unit count stays below 2^31
@@ -180,7 +167,7 @@ void conv_point_shape(const ConvProblem &q, int cus, uint32_t *units, uint32_t *
 {
     const int64_t total = (int64_t)q.N * q.H * q.W;
     const uint32_t tiles = (uint32_t)((total + 63) / 64);
-    *units = tiles * (uint32_t)(q.K / 64);
+    *units = tiles * (uint32_t)(q.K / 32);
     const uint32_t fit = (uint32_t)cus * 2u;                 // two workgroups per compute unit (LDS)
     const uint32_t need = (*units + 3) / 4;
     *workgroups = need < fit ? need : fit;
@@ -192,7 +179,7 @@ hipError_t conv_point_launch(const ConvProblem &q, hipStream_t stream)
     ConvPointKArgs a;
     a.in = (const float *)q.in; a.wt = (const float *)q.wt; a.bias = q.bias; a.out = q.out;
     a.N = q.N; a.C = q.C; a.K = q.K; a.HW = q.H * q.W;
-    a.groups = q.K / 64;
+    a.groups = q.K / 32;
     uint32_t wgs;
     conv_point_shape(q, compute_units(), &a.units, &wgs);
     const uint32_t waves = wgs * 4;

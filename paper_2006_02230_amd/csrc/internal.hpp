@@ -113,15 +113,15 @@ struct ConvCandidate { polydl_tile_cfg cfg; polydl_model_report rep; };
 void conv_candidates(const ConvProblem &q, std::vector<ConvCandidate> *out);
 
 // conv_point.hip: pointwise convolution with the filter resident in LDS (cfg.algo == 2; one variant:
-// 64 output channels x 64 pixels per wave and unit, 256 threads)
+// 32 output channels x 64 pixels per wave and unit, 256 threads)
 bool conv_point_fits(const ConvProblem &q);
 void conv_point_shape(const ConvProblem &q, int cus, uint32_t *units, uint32_t *workgroups);
 hipError_t conv_point_launch(const ConvProblem &q, hipStream_t stream);
 void model_conv_point(const ConvProblem &q, polydl_model_report *r);
-inline polydl_tile_cfg conv_point_cfg() { return polydl_tile_cfg{64, 64, 0, 64, 64, 1, 0, 0, 2, 0}; }
+inline polydl_tile_cfg conv_point_cfg() { return polydl_tile_cfg{32, 64, 0, 32, 64, 1, 0, 0, 2, 0}; }
 inline bool is_conv_point_cfg(const polydl_tile_cfg &c)
 {
-    return c.algo == 2 && c.bm == 64 && c.bn == 64 && c.bk == 0 && c.wm == 64 && c.wn == 64 && c.split_k <= 1 &&
+    return c.algo == 2 && c.bm == 32 && c.bn == 64 && c.bk == 0 && c.wm == 32 && c.wn == 64 && c.split_k <= 1 &&
            c.layout == 0 && c.raster == 0 && c.cb == 0;
 }
 

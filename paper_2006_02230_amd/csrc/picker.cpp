@@ -393,7 +393,7 @@ void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads,
 static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
 
 // Pointwise kernel (filter resident in LDS, pixels loaded straight into registers): a unit is
-// 64 pixels x 64 output channels, C/2 * 4 matrix instructions; units are dealt to the waves in
+// 64 pixels x 32 output channels, C/2 * 2 matrix instructions; units are dealt to the waves in
 // equal runs, so the busiest SIMD runs ceil(units / SIMDs) of them one after another.  The tensors
 // are streamed once.
 void model_conv_point(const ConvProblem &q, polydl_model_report *r)
@@ -403,21 +403,20 @@ void model_conv_point(const ConvProblem &q, polydl_model_report *r)
     conv_point_shape(q, kCUs, &units, &wgs);
     const double pixels = (double)q.N * q.H * q.W;
     const double in_bytes = pixels * q.C * 4, out_bytes = pixels * q.K * 4, wt_bytes = (double)q.K * q.C * 4;
-    const double unit_us = (q.C / 2.0) * 4.0 * 64.0 / kClockHz * 1e6;
+    const double unit_us = (q.C / 2.0) * 2.0 * 64.0 / kClockHz * 1e6;
     const double per_simd = std::ceil((double)units / (kCUs * kSimdsPerCU));
     r->mfma_us = per_simd * unit_us / 0.85;
     // measured over batch sizes 16 .. 128 on 64 -> 64 and 64 -> 256 channels at 56 x 56 (back-to-back
     // launches on the same buffers): the time follows the bytes written, at 3.3 TB/s; the input,
     // re-read from the last-level cache, hardly shows
     r->mem_us = (in_bytes + wt_bytes) / 20000.0 * 1e-3 + out_bytes / 3300.0 * 1e-3;
-    // launch, filling LDS with the filter (more of it with more channel groups), first loads, last stores
-    r->fixed_us = 7.0 + 0.5 * (q.K / 64 - 1);
+    r->fixed_us = 7.0;                               // launch, filling LDS with the filter, first loads, last stores
     r->predicted_us = std::max(r->mfma_us, r->mem_us) + r->fixed_us;
     r->workgroups = (int)wgs;
     r->simd_load = per_simd;
     // working sets: accumulators of a unit; the pixel registers reused by the channel groups; the
     // filter in LDS reused by every unit; the whole problem
-    const double ws[4] = {64.0 * 64 * 4, 64.0 * q.C * 4, wt_bytes, in_bytes + out_bytes + wt_bytes};
+    const double ws[4] = {32.0 * 64 * 4, 64.0 * q.C * 4, wt_bytes, in_bytes + out_bytes + wt_bytes};
     double sizes[4], weights[4];
     for (int i = 0; i < 4; ++i) { sizes[i] = kLevels[i].capacity; weights[i] = 1.0 / kLevels[i].gbytes_per_s; }
     reuse_bucket(4, ws, 4, sizes, r->level_bytes, &r->mem_bytes);
