@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "0aa65605d9ebbf1bb492c83fa4b93cd0493a5dcbd5827f318270e80edaf3192d", "batch": 32, "fetch_bytes": 743100103, "write_bytes": 457826896}
+HBM_TRAFFIC = {"csrc_sha256": "02a338c6c9966dbda88f2785fbac05f2a51982d22b9cd8c5bd09bb05a32e5cde", "batch": 32, "fetch_bytes": 733704955, "write_bytes": 457799872}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
