@@ -178,6 +178,7 @@ int polydl_bnorm_fwd(int N, int K, int P, int Q, const float *x, const float *ga
 int polydl_activation(int64_t count, float *y, int act, void *stream);
 
 /* ---- the reuse model (sections "Working set size computation" and "Poly-ranking algorithm") ------
+ * polydl_reuse_analyse (declared below, before polydl_reuse_bucket): the working sets of a small loop nest.
  * polydl_reuse_bucket: algorithm "Compute working set sizes w.r.t cache sizes": the n working set
  *   sizes ws[] are sorted ascending and each is added to the first of the nlevels levels (fastest
  *   first, capacities sizes[]) where it still fits beside what is already there; the rest is
@@ -202,6 +203,41 @@ typedef struct polydl_model_report {
     double simd_load;   /* waves the busiest SIMD has to run one after another */
 } polydl_model_report;
 
+/* polydl_reuse_analyse: algorithm "Compute working set sizes" (section "Working set size
+ * computation") on a small perfect loop nest, by enumerating its iterations (no polyhedral
+ * library): at most POLYDL_REUSE_MAX_LOOPS loops with extents >= 1 and at most
+ * POLYDL_REUSE_MAX_ITERATIONS iterations in all, outermost loop first, executed in that order;
+ * parallel[l] != 0 marks loop l parallel (parallel may be NULL = none).  refs are nrefs (1 .. 16)
+ * array references with affine subscripts: subscript d of a reference is
+ * offset[d] + sum_l coef[d][l] * iterator[l].  A dependence is a pair of references to the same
+ * array with all pairs of iterations (I before I') in which they touch the same element; reads
+ * and writes are not distinguished, and reference pairs with identical iteration pairs are
+ * reported once (n_pairs of them; src_ref/tgt_ref name the first).  Sequential dependence:
+ * source = its lexicographically first source iteration, min_target/max_target = that source's
+ * first and last target, ws[0] = WS_min and, if the targets differ, ws[1] = WS_max: distinct
+ * array elements touched from the source up to and including the target.  A dependence that
+ * spans iterations of a parallel loop (parallel = 1): ws[0] = WS_par, the elements touched by the
+ * whole nest with the iterators outside the outermost such loop held at the source's values.
+ * Sizes are in elements.  All pointers are host pointers.  *ndeps receives the number of
+ * dependences found; the first min(*ndeps, max_deps) are written.  POLYDL_ERR_BAD_DIMENSION for
+ * sizes outside the limits above, POLYDL_ERR_UNSUPPORTED if a dependence has more than 2^23
+ * iteration pairs. */
+#define POLYDL_REUSE_MAX_LOOPS 8
+#define POLYDL_REUSE_MAX_ITERATIONS 65536
+typedef struct polydl_loop_ref {
+    int array;                                  /* which array (any integer id) */
+    int rank;                                   /* number of subscripts, 1 .. 4 */
+    int coef[4][POLYDL_REUSE_MAX_LOOPS];
+    int offset[4];
+} polydl_loop_ref;
+typedef struct polydl_reuse_dep {
+    int src_ref, tgt_ref, n_pairs, parallel;
+    int n_ws;
+    double ws[2];
+    int source[POLYDL_REUSE_MAX_LOOPS], min_target[POLYDL_REUSE_MAX_LOOPS], max_target[POLYDL_REUSE_MAX_LOOPS];
+} polydl_reuse_dep;
+int polydl_reuse_analyse(int nloops, const int *extents, const int *parallel, int nrefs, const polydl_loop_ref *refs,
+                         int max_deps, polydl_reuse_dep *deps, int *ndeps);
 int polydl_reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem);
 double polydl_reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight);
 int polydl_model_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,

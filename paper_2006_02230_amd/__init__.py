@@ -12,7 +12,7 @@ from .binding import (lib, PolydlError, TileCfg, conv2d_fwd, sgemm, set_tile_ove
                       conv2d_fwd_bf16, bnorm_fwd, model_conv2d_bf16, pick_conv2d_bf16,
                       conv_candidates_bf16, sgemm_candidates, ranker_num_params, ranker_set_params,
                       ranker_load, ranker_stats_conv2d, ranker_play, ranker_tournament, pick_conv2d_learned,
-                      RANKER_STATS, RANKER_PARAMS_PATH)
+                      RANKER_STATS, RANKER_PARAMS_PATH, reuse_analyse)
 
 __all__ = ["lib", "PolydlError", "TileCfg", "conv2d_fwd", "sgemm", "set_tile_override",
            "get_last_tile", "variants", "status_string", "LIB_PATH", "nchw_to_nchwc", "nchwc_to_nchw",
@@ -21,4 +21,4 @@ __all__ = ["lib", "PolydlError", "TileCfg", "conv2d_fwd", "sgemm", "set_tile_ove
            "nchw_to_nchwc_bf16", "kcrs_to_kcrsck_bf16", "conv2d_fwd_bf16_blocked", "conv2d_fwd_bf16", "bnorm_fwd",
            "model_conv2d_bf16", "pick_conv2d_bf16", "conv_candidates_bf16", "sgemm_candidates",
            "ranker_num_params", "ranker_set_params", "ranker_load", "ranker_stats_conv2d", "ranker_play",
-           "ranker_tournament", "pick_conv2d_learned", "RANKER_STATS", "RANKER_PARAMS_PATH"]
+           "ranker_tournament", "pick_conv2d_learned", "RANKER_STATS", "RANKER_PARAMS_PATH", "reuse_analyse"]

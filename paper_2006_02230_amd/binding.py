@@ -351,6 +351,52 @@ def pick_conv2d(shape):
     return cfg, rep
 
 
+REUSE_MAX_LOOPS = 8
+
+
+class LoopRef(ctypes.Structure):
+    """Mirror of polydl_loop_ref."""
+    _fields_ = [("array", ctypes.c_int), ("rank", ctypes.c_int), ("coef", (ctypes.c_int * REUSE_MAX_LOOPS) * 4),
+                ("offset", ctypes.c_int * 4)]
+
+
+class ReuseDep(ctypes.Structure):
+    """Mirror of polydl_reuse_dep."""
+    _fields_ = [("src_ref", ctypes.c_int), ("tgt_ref", ctypes.c_int), ("n_pairs", ctypes.c_int),
+                ("parallel", ctypes.c_int), ("n_ws", ctypes.c_int), ("ws", ctypes.c_double * 2),
+                ("source", ctypes.c_int * REUSE_MAX_LOOPS), ("min_target", ctypes.c_int * REUSE_MAX_LOOPS),
+                ("max_target", ctypes.c_int * REUSE_MAX_LOOPS)]
+
+
+lib.polydl_reuse_analyse.argtypes = [_i, _ip, _ip, _i, ctypes.POINTER(LoopRef), _i, ctypes.POINTER(ReuseDep), _ip]
+lib.polydl_reuse_analyse.restype = _i
+
+
+def reuse_analyse(extents, refs, parallel=None, max_deps=64):
+    """polydl_reuse_analyse.  refs: [(array id, [[coefficient per loop] per subscript], [offset per subscript])];
+    parallel: one flag per loop.  Returns a list of dicts (one per dependence)."""
+    n = len(extents)
+    ext = (ctypes.c_int * n)(*[int(e) for e in extents])
+    par = None if parallel is None else (ctypes.c_int * n)(*[int(bool(f)) for f in parallel])
+    arr = (LoopRef * len(refs))()
+    for r, (array, coef, offset) in enumerate(refs):
+        arr[r].array, arr[r].rank = int(array), len(coef)
+        for d, row in enumerate(coef):
+            for l, c in enumerate(row):
+                arr[r].coef[d][l] = int(c)
+            arr[r].offset[d] = int(offset[d])
+    deps, nd = (ReuseDep * max_deps)(), ctypes.c_int(0)
+    _check(lib.polydl_reuse_analyse(n, ext, par, len(refs), arr, max_deps, deps, ctypes.byref(nd)),
+           "polydl_reuse_analyse")
+    out = []
+    for d in deps[:min(nd.value, max_deps)]:
+        out.append({"src_ref": d.src_ref, "tgt_ref": d.tgt_ref, "n_pairs": d.n_pairs, "parallel": bool(d.parallel),
+                    "ws": [int(v) for v in list(d.ws)[:d.n_ws]], "source": tuple(d.source[:n]),
+                    "min_target": None if d.parallel else tuple(d.min_target[:n]),
+                    "max_target": None if d.parallel else tuple(d.max_target[:n])})
+    return out
+
+
 RANKER_STATS = 8
 RANKER_PARAMS_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "ranker_params.txt")
 

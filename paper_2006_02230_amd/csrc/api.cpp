@@ -447,6 +447,33 @@ int polydl_activation(int64_t count, float *y, int act, void *stream)
     return launch_act(y, (size_t)count, act, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
 }
 
+int polydl_reuse_analyse(int nloops, const int *extents, const int *parallel, int nrefs, const polydl_loop_ref *refs,
+                         int max_deps, polydl_reuse_dep *deps, int *ndeps)
+{
+    if (!extents || !refs || !ndeps || (max_deps > 0 && !deps)) return POLYDL_ERR_NULL_POINTER;
+    if (nloops < 1 || nloops > POLYDL_REUSE_MAX_LOOPS || nrefs < 1 || nrefs > 16 || max_deps < 0)
+        return POLYDL_ERR_BAD_DIMENSION;
+    int64_t count = 1;
+    for (int l = 0; l < nloops; ++l) {
+        if (extents[l] < 1) return POLYDL_ERR_BAD_DIMENSION;
+        count *= extents[l];
+        if (count > POLYDL_REUSE_MAX_ITERATIONS) return POLYDL_ERR_BAD_DIMENSION;
+    }
+    for (int r = 0; r < nrefs; ++r) {
+        if (refs[r].rank < 1 || refs[r].rank > 4) return POLYDL_ERR_BAD_DIMENSION;
+        for (int d = 0; d < refs[r].rank; ++d) {
+            // subscripts must stay well inside int
+            int64_t reach = refs[r].offset[d] < 0 ? -(int64_t)refs[r].offset[d] : refs[r].offset[d];
+            for (int l = 0; l < nloops; ++l) {
+                const int64_t c = refs[r].coef[d][l] < 0 ? -(int64_t)refs[r].coef[d][l] : refs[r].coef[d][l];
+                reach += c * extents[l];
+            }
+            if (reach > 0x3FFFFFFF) return POLYDL_ERR_BAD_DIMENSION;
+        }
+    }
+    return reuse_analyse(nloops, extents, parallel, nrefs, refs, max_deps, deps, ndeps);
+}
+
 int polydl_reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem)
 {
     if (n < 0 || nlevels < 0) return POLYDL_ERR_BAD_DIMENSION;

@@ -125,6 +125,10 @@ inline bool is_conv_point_cfg(const polydl_tile_cfg &c)
            c.layout == 0 && c.raster == 0 && c.cb == 0;
 }
 
+// reuse_analyse.cpp (arguments already validated)
+int reuse_analyse(int nloops, const int *extents, const int *parallel, int nrefs, const polydl_loop_ref *refs,
+                  int max_deps, polydl_reuse_dep *deps, int *ndeps);
+
 // ranker.cpp
 int ranker_num_params();
 void ranker_set_params(const double *params);   // ranker_num_params() doubles, copied
