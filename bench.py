@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "02a338c6c9966dbda88f2785fbac05f2a51982d22b9cd8c5bd09bb05a32e5cde", "batch": 32, "fetch_bytes": 733704955, "write_bytes": 457799872}
+HBM_TRAFFIC = {"csrc_sha256": "184f6064a719ca96ae2bdf8c0d0036a8ee5fd711ffe8debf57d51d858cdcc655", "batch": 32, "fetch_bytes": 734026161, "write_bytes": 457906408}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
