@@ -220,8 +220,8 @@ typedef struct polydl_model_report {
  * whole nest with the iterators outside the outermost such loop held at the source's values.
  * Sizes are in elements.  All pointers are host pointers.  *ndeps receives the number of
  * dependences found; the first min(*ndeps, max_deps) are written.  POLYDL_ERR_BAD_DIMENSION for
- * sizes outside the limits above, POLYDL_ERR_UNSUPPORTED if a dependence has more than 2^23
- * iteration pairs. */
+ * sizes outside the limits above, POLYDL_ERR_UNSUPPORTED if a dependence has more than 2^20
+ * iteration pairs or all dependences together more than 2^24. */
 #define POLYDL_REUSE_MAX_LOOPS 8
 #define POLYDL_REUSE_MAX_ITERATIONS 65536
 typedef struct polydl_loop_ref {
@@ -281,7 +281,7 @@ int polydl_pick_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S, int
  *   polydl_model_conv2d).
  * polydl_ranker_play: one game; probs[2] (may be NULL) receives the two outputs, *winner (may be
  *   NULL) 1, 2 or 0 for a draw.
- * polydl_ranker_tournament: stats holds n * POLYDL_RANKER_STATS doubles, 0 <= n <= 4096.  Every
+ * polydl_ranker_tournament: stats holds n * POLYDL_RANKER_STATS doubles, 0 <= n <= 1024 (a full tournament of 1024 takes a few seconds).  Every
  *   ordered pair (i first, j second), i != j, plays once: n*(n-1) games.  wins[n] (may be NULL)
  *   receives the games each variant won, order[n] (may be NULL) the variants from most to fewest
  *   wins, equal wins in the order given.

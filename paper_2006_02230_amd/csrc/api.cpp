@@ -581,7 +581,7 @@ int polydl_ranker_play(const double *stats1, const double *stats2, double theta,
 
 int polydl_ranker_tournament(int n, const double *stats, double theta, int *wins, int *order)
 {
-    if (n < 0 || n > 4096) return POLYDL_ERR_BAD_DIMENSION;
+    if (n < 0 || n > 1024) return POLYDL_ERR_BAD_DIMENSION;   // n*(n-1) games of about 4000 multiply-adds each
     if (n > 0 && !stats) return POLYDL_ERR_NULL_POINTER;
     if (!stats_ok(stats, (int64_t)n * POLYDL_RANKER_STATS) || !(theta >= 0 && theta <= 1)) return POLYDL_ERR_BAD_DIMENSION;
     return ranker_tournament(n, stats, theta, wins, order) ? POLYDL_OK : POLYDL_ERR_UNSUPPORTED;

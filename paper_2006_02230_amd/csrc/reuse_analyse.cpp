@@ -79,7 +79,8 @@ int reuse_analyse(int nloops, const int *extents, const int *parallel, int nrefs
     std::vector<const Pairs *> order;
     std::vector<std::vector<std::pair<int, int>>> members;
     std::vector<std::vector<int>> where(nelems);
-    const size_t kMaxPairs = 8u << 20;
+    const size_t kMaxPairs = 1u << 20, kMaxStored = 16u << 20;   // per dependence, and over all of them
+    size_t stored = 0;
     for (int s = 0; s < nrefs; ++s)
         for (int t = 0; t < nrefs; ++t) {
             if (refs[s].array != refs[t].array) continue;
@@ -94,7 +95,9 @@ int reuse_analyse(int nloops, const int *extents, const int *parallel, int nrefs
                 }
             }
             if (pairs.empty()) continue;
+            const size_t added = pairs.size();
             auto ins = index.insert({std::move(pairs), (int)members.size()});
+            if (ins.second && (stored += added) > kMaxStored) return POLYDL_ERR_UNSUPPORTED;
             if (ins.second) { order.push_back(&ins.first->first); members.emplace_back(); }
             members[ins.first->second].push_back({s, t});
         }

@@ -41,6 +41,7 @@ def test_parameter_count_and_argument_errors():
         P.ranker_play([float("inf")] + [1.0] * 7, [1.0] * 8)
     assert P.lib.polydl_ranker_tournament(-1, None, 0.6, None, None) == -2
     assert P.lib.polydl_ranker_tournament(3, None, 0.6, None, None) == -1
+    assert P.lib.polydl_ranker_tournament(1025, (ctypes.c_double * (1025 * 8))(), 0.6, None, None) == -2
     assert P.ranker_tournament([]) == ([], [])
 
 

@@ -91,3 +91,13 @@ def test_argument_errors():
     assert f(2, big, None, 1, ref, 0, None, ctypes.byref(nd)) == -2
     ref[0].rank = 5
     assert f(2, ext, None, 1, ref, 0, None, ctypes.byref(nd)) == -2
+
+
+def test_too_many_iteration_pairs_are_refused():
+    # one reference that always touches the same element: 4096 iterations make 8 million pairs
+    with pytest.raises(P.PolydlError) as e:
+        P.reuse_analyse([64, 64], [(0, [[0, 0]], [0])])
+    assert e.value.status == -3
+    # the same nest, small: one dependence, everything is one element
+    deps = P.reuse_analyse([4, 4], [(0, [[0, 0]], [0])])
+    assert len(deps) == 1 and deps[0]["ws"] == [1] and deps[0]["max_target"] == (3, 3)
