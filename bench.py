@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "184f6064a719ca96ae2bdf8c0d0036a8ee5fd711ffe8debf57d51d858cdcc655", "batch": 32, "fetch_bytes": 734026161, "write_bytes": 457906408}
+HBM_TRAFFIC = {"csrc_sha256": "f7baa3ff06c1e61e2bdd1e08a70878d7b475b7d49abb9985afdf07e3f70dc926", "batch": 32, "fetch_bytes": 734067454, "write_bytes": 457868344}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
