@@ -100,4 +100,5 @@ def test_too_many_iteration_pairs_are_refused():
     assert e.value.status == -3
     # the same nest, small: one dependence, everything is one element
     deps = P.reuse_analyse([4, 4], [(0, [[0, 0]], [0])])
-    assert len(deps) == 1 and deps[0]["ws"] == [1] and deps[0]["max_target"] == (3, 3)
+    assert len(deps) == 1 and deps[0]["ws"] == [1, 1]              # WS_min and WS_max: the one element
+    assert deps[0]["min_target"] == (0, 1) and deps[0]["max_target"] == (3, 3)
