@@ -233,7 +233,7 @@ def evaluate(table, flat, seed=0, theta=0.6):
 def write_report(res, path, command, note=""):
     def name(c):
         if c["algo"] == 2:
-            return "pointwise 64x64"
+            return "pointwise 32x64"
         if c["algo"] == 1:
             return "patch %dx%d/%dx%d cb %d split %d" % (c["bm"], c["bn"], c["wm"], c["wn"], c["cb"], c["split_k"])
         return "gather %dx%dx%d/%dx%d split %d%s" % (c["bm"], c["bn"], c["bk"], c["wm"], c["wn"], c["split_k"],
