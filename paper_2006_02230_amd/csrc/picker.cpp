@@ -195,9 +195,11 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
     const int a_level = std::min(shared_level, std::max(2, level_of(s.a_bytes)));
     const int b_level = std::min(shared_level, std::max(2, level_of(s.b_bytes)));
     double mem_us = 0;
-    mem_us += (a_traffic - s.a_bytes) / rate_of(a_level) * 1e-3;           // re-fetches
-    mem_us += (b_traffic > s.b_bytes ? b_traffic - s.b_bytes : 0) / rate_of(b_level) * 1e-3;
+    double refetch_us = (a_traffic - s.a_bytes) / rate_of(a_level) * 1e-3;           // re-fetches
+    refetch_us += (b_traffic > s.b_bytes ? b_traffic - s.b_bytes : 0) / rate_of(b_level) * 1e-3;
     mem_us += (s.a_bytes + s.b_bytes + s.d_bytes) / kHbmGBs * 1e-3;        // compulsory
+    if (c.rounds) mem_us = std::max(mem_us, refetch_us);                   // caches and memory work side by side
+    else mem_us += refetch_us;
     double fixed = c.kernel_fixed_us;
     if (c.rounds) {
         // nothing streams the tensors faster than this, with the first and last touches exposed
