@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "f7baa3ff06c1e61e2bdd1e08a70878d7b475b7d49abb9985afdf07e3f70dc926", "batch": 32, "fetch_bytes": 734067454, "write_bytes": 457868344}
+HBM_TRAFFIC = {"csrc_sha256": "fa779a9ab7e660bf3b3aca7189b4eb0e6964271e0bc8260af9aa7332ec5db9d2", "batch": 32, "fetch_bytes": 733920506, "write_bytes": 457864632}
 
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
