@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import synth
-from gpu_util import BF16_TOL, host, sample_indices
+from gpu_util import BF16_TOL, FP32_TOL, host
 
 pytestmark = pytest.mark.gpu
 
@@ -101,14 +101,20 @@ def test_bf16_small_integers_exact(P, s):
 
 
 @pytest.mark.parametrize("layer", range(8))
-def test_resnet_suite_bf16_full_size_sampled(P, layer):
-    # batch 64, the configuration the benchmark's bf16 rows time
+def test_resnet_suite_bf16_full_size(P, layer):
+    # batch 64, the configuration the benchmark's bf16 rows time: every output against the oracle run
+    # on the widened bfloat16 values, in chunks of 16 images to bound host memory.  Products of two
+    # bfloat16 values are exact in fp32, so only fp32 accumulation error remains: the fp32 bound is
+    # held (a dropped reduction term is about 1/(C*R*S) of the scale and would pass the 1e-2 contract)
     s = synth.RESNET50_SUITE(64)[layer]
     xb, wb, xw, ww, b = bf16_inputs(s, 200 + layer)
     got = host(P.conv2d_fwd_bf16(dev16(xb), dev16(wb), dev32(b), stride=s.stride, pad=s.pad, act="relu"))
-    idx = sample_indices(got.size, 20000, seed=layer)
-    want, ab = oracle.conv2d_fwd(xw, ww, bias=b, stride=s.stride, pad=s.pad, act="relu", at=idx)
-    assert oracle.scaled_error(got.ravel()[idx], want, ab) <= BF16_TOL
+    tile = P.get_last_tile()
+    for n0 in range(0, s.N, 16):
+        want, ab = oracle.conv2d_fwd(xw[n0:n0 + 16], ww, bias=b, stride=s.stride, pad=s.pad, act="relu")
+        err = oracle.scaled_error(got[n0:n0 + 16], want, ab)
+        assert err <= BF16_TOL, (tile, n0)
+        assert err <= FP32_TOL, (tile, n0)
 
 
 def test_argument_errors(P):

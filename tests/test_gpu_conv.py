@@ -4,7 +4,7 @@ import pytest
 
 import oracle
 import synth
-from gpu_util import FP32_TOL, dev, host, sample_indices
+from gpu_util import FP32_TOL, dev, host
 
 pytestmark = pytest.mark.gpu
 
@@ -121,25 +121,55 @@ def test_config1_full_compare(P):
 
 
 @pytest.mark.parametrize("layer", range(8))
-def test_resnet_suite_full_size_sampled(P, layer):
-    # batch 32, the picker's own configuration (what the benchmark times); the oracle evaluates
-    # sampled outputs one by one
+def test_resnet_suite_full_size(P, layer):
+    # batch 32, the picker's own configuration (what the benchmark times): EVERY output of the
+    # layer against the oracle
     s = synth.RESNET50_SUITE(32)[layer]
     x, w, b = synth.conv_inputs(s, seed=100 + layer, dist="normal", bias=True)
     got = run_conv(P, s, x, w, b, act="relu")
     Pq, Qq = synth.out_hw(s)
     assert got.shape == (s.N, s.K, Pq, Qq)
-    idx = sample_indices(got.size, 30000, seed=layer)
-    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu", at=idx)
-    assert oracle.scaled_error(got.ravel()[idx], want, ab) <= FP32_TOL
-    # property at full size: summing the output over channels equals convolving with the summed
-    # filter (linearity in the filter), checked without the activation on a second call
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL, P.get_last_tile()
+    # without bias and activation (another epilogue path of the same launch configuration)
     got0 = run_conv(P, s, x, w)
-    wsum = w.astype(np.float64).sum(axis=0, keepdims=True).astype(np.float32)
-    ref, refab = oracle.conv2d_fwd(x[:1], wsum, stride=s.stride, pad=s.pad)
-    tot = got0[:1].astype(np.float64).sum(axis=1, keepdims=True)
-    scale = np.abs(got0[:1]).astype(np.float64).sum(axis=1, keepdims=True) + refab
-    assert np.max(np.abs(tot - ref) / scale) <= 1e-4
+    want0, ab0 = oracle.conv2d_fwd(x, w, stride=s.stride, pad=s.pad)
+    assert oracle.scaled_error(got0, want0, ab0) <= FP32_TOL, P.get_last_tile()
+
+
+@pytest.mark.parametrize("layer", range(8))
+def test_resnet_suite_batch64_full_size(P, layer):
+    # batch 64: other picks than at batch 32 (leftover-tile splits, the pointwise kernel, other
+    # split factors); every output against the oracle, in chunks of 16 images to bound host memory
+    s = synth.RESNET50_SUITE(64)[layer]
+    x, w, b = synth.conv_inputs(s, seed=100 + layer, dist="normal", bias=True)
+    got = run_conv(P, s, x, w, b, act="relu")
+    tile = P.get_last_tile()
+    for n0 in range(0, s.N, 16):
+        want, ab = oracle.conv2d_fwd(x[n0:n0 + 16], w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+        assert oracle.scaled_error(got[n0:n0 + 16], want, ab) <= FP32_TOL, (tile, n0)
+
+
+@pytest.mark.parametrize("layer", [0, 2, 4, 7])
+def test_leftover_tile_split_full_size(P, layer):
+    # raster 2 at full size on the layers where the picker ranks it (batch 32 and 64): the whole
+    # tiles and the tiles cut along the reduction, every output
+    for N in (32, 64):
+        s = synth.RESNET50_SUITE(N)[layer]
+        x, w, b = synth.conv_inputs(s, seed=100 + layer, dist="normal", bias=True)
+        want = None
+        for v in P.variants(0):
+            if v.algo != 0 or v.wm * v.wn > 64 * 32:
+                continue
+            v.raster, v.split_k = 2, 1
+            got = try_variant(P, v, s, x, w, b, act="relu")
+            if got is None:
+                continue
+            if want is None:
+                want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+            assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (v, N)
+        assert want is not None
+    P.set_tile_override(None)
 
 
 def test_split_k_random(P):
@@ -404,23 +434,22 @@ def test_pointwise_kernel_limits_and_fallback(P):
         with pytest.raises(P.PolydlError):
             P.model_conv2d(tuple(s)[1:], v)
     P.set_tile_override(None)
-    # a problem where the picker chooses it (64 -> 256 channels at 56 x 56, batch 64), checked on sampled
-    # outputs; with tensors that are only 4-byte aligned the call still succeeds through another kernel
+    # a problem where the picker chooses it (64 -> 256 channels at 56 x 56, batch 64), every output
+    # checked; with tensors that are only 4-byte aligned the call still succeeds through another kernel
     s = synth.ConvShape("pick", 64, 64, 56, 56, 256, 1, 1, 1, 0)
     cfg, _ = P.pick_conv2d(tuple(s)[1:])
     assert cfg.algo == 2
     x, w, b = synth.conv_inputs(s, seed=74, dist="normal", bias=True)
-    idx = sample_indices(s.N * s.K * s.H * s.W, 4096, seed=75)
-    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=0, act="relu", at=idx)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=0, act="relu")
     got = run_conv(P, s, x, w, b, act="relu")
     assert P.get_last_tile().as_dict() == cfg.as_dict()
-    assert oracle.scaled_error(got.reshape(-1)[idx], want, ab) <= FP32_TOL
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL
     xd = torch.empty(x.size + 1, dtype=torch.float32, device="cuda")[1:].view(x.shape)
     xd.copy_(torch.from_numpy(x))
     assert xd.data_ptr() % 8 == 4
     got = host(P.conv2d_fwd(xd, dev(w), dev(b), stride=1, pad=0, act="relu"))
     assert P.get_last_tile().algo != 2
-    assert oracle.scaled_error(got.reshape(-1)[idx], want, ab) <= FP32_TOL
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL
     P.set_tile_override(v)
     with pytest.raises(P.PolydlError):
         P.conv2d_fwd(xd, dev(w), dev(b), stride=1, pad=0, act="relu")

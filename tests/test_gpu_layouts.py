@@ -78,7 +78,7 @@ def test_fused_epilogue_equals_separate_kernels(P):
     s = synth.ConvShape("f", 2, 32, 14, 14, 48, 3, 3, 1, 1)
     x, w, b = synth.conv_inputs(s, 46, "normal", bias=True)
     tile, _ = P.pick_conv2d(tuple(s)[1:])
-    tile.split_k = 1   # a split reduction adds its parts with atomics in no fixed order
+    tile.split_k = 1   # whole reduction in one workgroup: the same launch with and without the tail
     P.set_tile_override(tile)
     fused = host(P.conv2d_fwd(dev(x), dev(w), dev(b), stride=1, pad=1, act="relu"))
     y = P.conv2d_fwd(dev(x), dev(w), None, stride=1, pad=1)
