@@ -18,11 +18,21 @@
  *   - tensors are dense, contiguous float32 unless stated; input and output must not overlap;
  *   - memory of its own: a convolution or matrix product whose reduction is split over
  *     several workgroups (split_k > 1, or the leftover tiles of raster 2) keeps partial tiles
- *     and arrival counters in a
- *     device buffer the library allocates with hipMalloc on first need, one per (device, stream),
- *     grows on demand and keeps until the process ends; growing it waits for the device.  Calls
- *     on ONE stream share it safely (they run in order); calls on different streams use
- *     different buffers.  An allocation failure is reported as POLYDL_ERR_LAUNCH.
+ *     and arrival counters in a device buffer the library allocates with hipMalloc on first
+ *     need, one per (device, stream), and keeps until the process ends.  When a later problem
+ *     needs more, a larger buffer is allocated (this waits for the device) and the smaller one is
+ *     kept, not freed, so launches recorded earlier stay valid.  Calls on ONE stream share the
+ *     buffer safely (they run in order); calls on different streams use different buffers.  An
+ *     allocation failure is reported as POLYDL_ERR_LAUNCH;
+ *   - HIP graphs: every entry point may be captured.  Three rules follow from the scratch memory
+ *     above.  (1) A call that would have to allocate or grow it while its stream is being
+ *     captured returns POLYDL_ERR_UNSUPPORTED and records nothing: run the same call once on
+ *     that stream before capturing.  (2) A graph keeps the
+ *     scratch addresses of its capture stream; they stay valid for the life of the process.
+ *     (3) Replaying the graph, on any stream, uses the scratch memory of the stream it was
+ *     CAPTURED on: do not let a replay overlap in time with other split-reduction work of this
+ *     library enqueued on that capture stream (or with another replay of the same graph); their
+ *     partial tiles and counters would mix.
  */
 #ifndef POLYDL_H
 #define POLYDL_H
@@ -40,7 +50,7 @@ typedef enum polydl_status {
     POLYDL_ERR_BAD_DIMENSION = -2,  /* a size <= 0, stride <= 0, pad < 0, or no output (P or Q <= 0) */
     POLYDL_ERR_UNSUPPORTED = -3,    /* valid problem outside the kernels' index range, bad override */
     POLYDL_ERR_LAUNCH = -4,         /* the HIP runtime refused the launch or an allocation */
-    POLYDL_ERR_NO_DEVICE = -5       /* no gfx950 device is current */
+    POLYDL_ERR_NO_DEVICE = -5       /* the current device is not a gfx950 GPU (or there is none) */
 } polydl_status;
 
 /* Element-wise operator applied to every output after the reduction (section "Operator
@@ -311,6 +321,16 @@ int polydl_pick_conv2d_learned(int N, int C, int H, int W, int K, int R, int S, 
  * (kind 0 = convolution, 1 = sgemm, 2 = bfloat16 convolution). */
 int polydl_set_tile_override(const polydl_tile_cfg *cfg);
 int polydl_get_last_tile(polydl_tile_cfg *cfg);
+/* The candidate lists the pickers rank, for an exhaustive sweep over exactly the same space
+ * (section "Experimental Evaluation": the picked variant against the best of all variants).
+ * polydl_conv2d_candidates: kind 0 = what polydl_pick_conv2d ranks (fp32: kernel, tile, stage depth,
+ *   split factor, leftover-tile switch), kind 2 = what polydl_pick_conv2d_bf16 ranks (C counts
+ *   channels).  polydl_sgemm_candidates: what polydl_pick_sgemm ranks.
+ * *count receives the number of candidates; the first min(*count, max_cfgs) are written to cfgs
+ * (host memory; cfgs may be NULL when max_cfgs is 0).  Errors as the matching pick function. */
+int polydl_conv2d_candidates(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int kind,
+                             int max_cfgs, polydl_tile_cfg *cfgs, int *count);
+int polydl_sgemm_candidates(int M, int N, int K, int max_cfgs, polydl_tile_cfg *cfgs, int *count);
 int polydl_num_variants(int kind);
 int polydl_get_variant(int kind, int index, polydl_tile_cfg *cfg);
 

@@ -484,66 +484,35 @@ def pick_sgemm(M, N, K):
     return cfg, rep
 
 
+lib.polydl_conv2d_candidates.argtypes = [_i] * 11 + [ctypes.POINTER(TileCfg), _ip]
+lib.polydl_sgemm_candidates.argtypes = [_i] * 4 + [ctypes.POINTER(TileCfg), _ip]
+lib.polydl_conv2d_candidates.restype = _i
+lib.polydl_sgemm_candidates.restype = _i
+
+
+def _candidates(call, where):
+    n = ctypes.c_int(0)
+    _check(call(0, None, ctypes.byref(n)), where)
+    arr = (TileCfg * max(n.value, 1))()
+    _check(call(n.value, arr, ctypes.byref(n)), where)
+    return [TileCfg(*[getattr(arr[i], f) for f, _ in TileCfg._fields_]) for i in range(n.value)]
+
+
 def conv_candidates(shape):
-    """Every (variant, cb, split_k) the picker ranks for this problem: the sweep's search space."""
-    N, C, H, W, K, R, S, stride, pad = [int(v) for v in shape]
-    splits = (1, 2, 3, 4, 6, 8, 12, 16)
-    cpad = (C + 1) & ~1
-    out = []
-    for v in variants(0):
-        if v.algo == 2:
-            out.append(v)                      # pointwise kernel: one shape, no knobs
-        elif v.algo == 1:
-            for cb in range(2, min(cpad, 64) + 1, 2):
-                if cpad % cb:
-                    continue
-                stages = -(-C // cb)
-                for sk in splits:
-                    if sk > stages:
-                        break
-                    out.append(TileCfg(v.bm, v.bn, 0, v.wm, v.wn, sk, 0, 0, 1, cb))
-        else:
-            stages = -(-(C * R * S) // v.bk)
-            for sk in splits:
-                if sk > stages:
-                    break
-                out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0))
-                if sk == 1 and v.wm * v.wn <= 64 * 32:
-                    out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, 1, 0, 2, 0, 0))   # leftover tiles split
-    return out
+    """polydl_conv2d_candidates, kind 0: every variant polydl_pick_conv2d ranks for this problem."""
+    dims = [int(v) for v in shape]
+    return _candidates(lambda m, a, n: lib.polydl_conv2d_candidates(*dims, 0, m, a, n), "polydl_conv2d_candidates")
 
 
 def sgemm_candidates(M, N, K):
-    """Every (variant, split_k, raster) the picker ranks for an SGEMM: the sweep's search space."""
-    splits = (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128)
-    out = []
-    for v in variants(1):
-        stages = -(-K // v.bk)
-        for sk in splits:
-            if sk > stages:
-                break
-            for raster in (0, 1):
-                out.append(TileCfg(v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, raster, 0, 0))
-    return out
+    """polydl_sgemm_candidates: every variant polydl_pick_sgemm ranks."""
+    return _candidates(lambda m, a, n: lib.polydl_sgemm_candidates(M, N, K, m, a, n), "polydl_sgemm_candidates")
 
 
 def conv_candidates_bf16(shape):
-    """The (variant, cb, split_k) space of the bfloat16 convolution the sweep times: every compiled
-    tile, stage depths of 2 .. 32 eight-channel blocks, the split factors the picker ranks."""
-    N, C, H, W, K, R, S, stride, pad = [int(v) for v in shape]
-    units = -(-C // 8)
-    stage_rows = 1 if R >= 5 else R
-    out = []
-    for v in variants(2):
-        for cb in (2, 4, 6, 8, 12, 16, 24, 32):
-            if cb > ((units + 1) & ~1):
-                break
-            stages = -(-units // cb) * (R // stage_rows)
-            for sk in (1, 2, 3, 4, 6, 8, 12, 16):
-                if sk > stages:
-                    break
-                out.append(TileCfg(v.bm, v.bn, 0, v.wm, v.wn, sk, 1, 0, 1, cb))
-    return out
+    """polydl_conv2d_candidates, kind 2: every variant polydl_pick_conv2d_bf16 ranks."""
+    dims = [int(v) for v in shape]
+    return _candidates(lambda m, a, n: lib.polydl_conv2d_candidates(*dims, 2, m, a, n), "polydl_conv2d_candidates")
 
 
 def set_tile_override(cfg=None, **kw):

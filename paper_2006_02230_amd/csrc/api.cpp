@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 #include <atomic>
 #include <algorithm>
+#include <cstring>
 #include <array>
 #include <map>
 #include <mutex>
@@ -36,8 +37,34 @@ static std::mutex g_mu;
 static std::atomic<int> g_last_hip_error{0};
 static int launch_failed(hipError_t e)
 {
+    // a launch that needed scratch memory it may not have: not the runtime's refusal
+    const int why = scratch_refusal();
+    if (e == hipErrorOutOfMemory && why == SCRATCH_TOO_SMALL) return POLYDL_ERR_UNSUPPORTED;
+    if (e == hipErrorStreamCaptureUnsupported && why == SCRATCH_CAPTURING) return POLYDL_ERR_UNSUPPORTED;
     g_last_hip_error = (int)e;
     return POLYDL_ERR_LAUNCH;
+}
+static int launched(hipError_t e) { return e == hipSuccess ? POLYDL_OK : launch_failed(e); }
+
+// The kernels are gfx950 code: any other current device (or none) is refused.  Asked once per device.
+static bool on_gfx950()
+{
+    static std::mutex mu;
+    static std::map<int, bool> known;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = known.find(dev);
+    if (it != known.end()) return it->second;
+    hipDeviceProp_t prop;
+    bool ok = false;
+    if (hipGetDeviceProperties(&prop, dev) == hipSuccess) ok = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+    else (void)hipGetLastError();
+    known[dev] = ok;
+    return ok;
 }
 static bool g_have_override = false;
 static polydl_tile_cfg g_override;
@@ -45,6 +72,7 @@ static polydl_tile_cfg g_last = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 // picks already made, keyed by the problem's dimensions (the ranking depends on nothing else)
 static std::map<std::array<int, 10>, polydl_tile_cfg> g_conv_plans;   // shape, and whether the input is activated on the way in
 static std::map<std::array<int, 3>, polydl_tile_cfg> g_sgemm_plans;
+static std::map<std::array<int, 9>, polydl_tile_cfg> g_bf16_plans;
 
 static const Variant *find_variant(const polydl_tile_cfg &c)
 {
@@ -119,6 +147,7 @@ static int sgemm_impl(int M, int N, int K, float alpha, const float *A, const fl
     if (M <= 0 || N <= 0 || K < 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!C || (K > 0 && (!A || !B))) return POLYDL_ERR_NULL_POINTER;
     if (K == 0 && beta == 1.f) return POLYDL_OK;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
     polydl_tile_cfg cfg;
     if (K == 0) {
         // an empty product: only C = beta*C is left, any variant's epilogue does it
@@ -157,7 +186,7 @@ static int sgemm_impl(int M, int N, int K, float alpha, const float *A, const fl
 
 static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                      const float *in, const float *wt, const float *bias, float *out, int pre_act, int act,
-                     void *stream)
+                     void *stream, const ScratchArena *arena = nullptr)
 {
     if (pre_act != POLYDL_ACT_NONE && pre_act != POLYDL_ACT_RELU && pre_act != POLYDL_ACT_RELU6)
         return POLYDL_ERR_UNSUPPORTED;
@@ -167,8 +196,9 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     if (act != POLYDL_ACT_NONE && act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6)
         return POLYDL_ERR_UNSUPPORTED;
     if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
     const int64_t Kg = (int64_t)C * R * S, CHW = (int64_t)C * H * W;
-    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act, pre_act};
+    ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act, pre_act, arena};
     polydl_tile_cfg cfg;
     bool forced;
     {
@@ -282,7 +312,8 @@ int polydl_nchw_to_nchwc(int N, int C, int H, int W, int b, const float *in, flo
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!in || !out) return POLYDL_ERR_NULL_POINTER;
     if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_nchwc(in, out, N, C, H * W, b, true, 4, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_nchwc(in, out, N, C, H * W, b, true, 4, (hipStream_t)stream));
 }
 
 int polydl_nchwc_to_nchw(int N, int C, int H, int W, int b, const float *in, float *out, void *stream)
@@ -290,7 +321,8 @@ int polydl_nchwc_to_nchw(int N, int C, int H, int W, int b, const float *in, flo
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!in || !out) return POLYDL_ERR_NULL_POINTER;
     if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_nchwc(in, out, N, C, H * W, b, false, 4, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_nchwc(in, out, N, C, H * W, b, false, 4, (hipStream_t)stream));
 }
 
 int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const float *wt, float *out, void *stream)
@@ -299,7 +331,8 @@ int polydl_kcrs_to_kcrsck(int K, int C, int R, int S, int bc, int bk, const floa
     if (!wt || !out) return POLYDL_ERR_NULL_POINTER;
     const int64_t total = (int64_t)((K + bk - 1) / bk) * bk * ((C + bc - 1) / bc) * bc * R * S;
     if (total >= (1ll << 39) || (int64_t)R * S >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_kcrsck(wt, out, K, C, R * S, bc, bk, 4, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_kcrsck(wt, out, K, C, R * S, bc, bk, 4, (hipStream_t)stream));
 }
 
 int polydl_nchw_to_nchwc_bf16(int N, int C, int H, int W, int b, const uint16_t *in, uint16_t *out, void *stream)
@@ -307,7 +340,8 @@ int polydl_nchw_to_nchwc_bf16(int N, int C, int H, int W, int b, const uint16_t 
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || b <= 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!in || !out) return POLYDL_ERR_NULL_POINTER;
     if (b > 32 || N > 65535 || (C + b - 1) / b > 65535 || (int64_t)H * W >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_nchwc(in, out, N, C, H * W, b, true, 2, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_nchwc(in, out, N, C, H * W, b, true, 2, (hipStream_t)stream));
 }
 
 int polydl_kcrs_to_kcrsck_bf16(int K, int C, int R, int S, int bc, int bk, const uint16_t *wt, uint16_t *out,
@@ -317,29 +351,45 @@ int polydl_kcrs_to_kcrsck_bf16(int K, int C, int R, int S, int bc, int bk, const
     if (!wt || !out) return POLYDL_ERR_NULL_POINTER;
     const int64_t total = (int64_t)((K + bk - 1) / bk) * bk * ((C + bc - 1) / bc) * bc * R * S;
     if (total >= (1ll << 39) || (int64_t)R * S >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_kcrsck(wt, out, K, C, R * S, bc, bk, 2, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_kcrsck(wt, out, K, C, R * S, bc, bk, 2, (hipStream_t)stream));
 }
+
+// Every (tile, stage depth in eight-channel units, split factor) the bfloat16 picker ranks; qb.C counts units.
+static const int kBf16Depths[] = {32, 24, 16, 12, 8, 6, 4, 2};
+static void bf16_candidates(const ConvProblem &qb, std::vector<polydl_tile_cfg> *out)
+{
+    out->clear();
+    const int cunits = qb.C;
+    const int rows_per_stage = qb.R >= 5 ? 1 : qb.R;
+    for (int i = 0; i < kNumPatchBf16Variants; ++i) {
+        const PatchVariant &v = kPatchBf16Variants[i];
+        // deepest stages first: on equal predictions fewer, longer stages win (fewer barriers)
+        for (int cb : kBf16Depths) {
+            if (cb > ((cunits + 1) & ~1)) continue;
+            if (v.conv(qb, cb, 1, 0, nullptr, true) != hipSuccess) continue;
+            const int nstages = (cunits + cb - 1) / cb * (qb.R / rows_per_stage);
+            const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+            for (int sk : splits) {
+                if (sk > nstages) break;
+                out->push_back(polydl_tile_cfg{v.bm, v.bn, 0, v.wm, v.wn, sk, 1, 0, 1, cb});
+            }
+        }
+    }
+}
+
+static int bf16_threads(const polydl_tile_cfg &c) { return (c.bm / c.wm) * (c.bn / c.wn) * 64; }
 
 // bf16 candidates are ranked with the round-by-round time model at the bf16 instruction's rate
 static bool pick_bf16(const ConvProblem &qb, polydl_tile_cfg *out)
 {
-    const int cunits = qb.C;
+    std::vector<polydl_tile_cfg> cands;
+    bf16_candidates(qb, &cands);
     bool have = false;
     double best = 0;
-    for (int i = 0; i < kNumPatchBf16Variants; ++i) {
-        const PatchVariant &v = kPatchBf16Variants[i];
-        // deepest stages first: on equal predictions fewer, longer stages win (fewer barriers)
-        for (int cb = std::min(32, (cunits + 1) & ~1); cb >= 2; cb -= 2) {
-            if (v.conv(qb, cb, 1, 0, nullptr, true) != hipSuccess) continue;
-            const int nstages = (cunits + cb - 1) / cb;
-            const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16};
-            for (int sk : splits) {
-                if (sk > nstages) break;
-                polydl_tile_cfg c = {v.bm, v.bn, 0, v.wm, v.wn, sk, 1, 0, 1, cb};
-                const double t = model_conv_bf16(qb, c, v.threads);
-                if (!have || t < best * 0.999) { best = t; *out = c; have = true; }
-            }
-        }
+    for (const polydl_tile_cfg &c : cands) {
+        const double t = model_conv_bf16(qb, c, bf16_threads(c));
+        if (!have || t < best * 0.999) { best = t; *out = c; have = true; }
     }
     return have;
 }
@@ -354,6 +404,7 @@ int polydl_conv2d_fwd_bf16_blocked(int N, int C, int H, int W, int K, int R, int
     if (act != POLYDL_ACT_NONE && act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6) return POLYDL_ERR_UNSUPPORTED;
     if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
     if (((uintptr_t)in8c & 15) || ((uintptr_t)wt8c & 15)) return POLYDL_ERR_UNSUPPORTED;   // 16-byte units
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
     const int cunits = (C + 7) / 8;
     ConvProblem q{N, cunits, H, W, K, R, S, stride, pad, (int)P, (int)Q, in8c, wt8c, bias, out, act};
     polydl_tile_cfg cfg;
@@ -365,8 +416,17 @@ int polydl_conv2d_fwd_bf16_blocked(int N, int C, int H, int W, int K, int R, int
     }
     if (forced) {
         if (cfg.algo != 1) return POLYDL_ERR_UNSUPPORTED;
-    } else if (!pick_bf16(q, &cfg)) {
-        return POLYDL_ERR_UNSUPPORTED;
+    } else {
+        // the pick depends on the shape alone: made once per shape
+        const std::array<int, 9> key = {N, cunits, H, W, K, R, S, stride, pad};
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = g_bf16_plans.find(key);
+        if (it != g_bf16_plans.end()) {
+            cfg = it->second;
+        } else {
+            if (!pick_bf16(q, &cfg)) return POLYDL_ERR_UNSUPPORTED;
+            g_bf16_plans[key] = cfg;
+        }
     }
     const PatchVariant *pv = nullptr;
     for (int i = 0; i < kNumPatchBf16Variants; ++i) {
@@ -422,8 +482,8 @@ int polydl_bias_add(int N, int K, int P, int Q, float *y, const float *bias, voi
     if (N <= 0 || K <= 0 || P <= 0 || Q <= 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!y || !bias) return POLYDL_ERR_NULL_POINTER;
     if ((int64_t)P * Q >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    return launch_bias_add(y, bias, K, P * Q, (size_t)N * K * P * Q, (hipStream_t)stream) == hipSuccess
-               ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_bias_add(y, bias, K, P * Q, (size_t)N * K * P * Q, (hipStream_t)stream));
 }
 
 int polydl_bnorm_fwd(int N, int K, int P, int Q, const float *x, const float *gamma, const float *beta,
@@ -434,9 +494,9 @@ int polydl_bnorm_fwd(int N, int K, int P, int Q, const float *x, const float *ga
     if (act < POLYDL_ACT_NONE || act > POLYDL_ACT_RELU6 || !(eps >= 0.f)) return POLYDL_ERR_UNSUPPORTED;
     // element indices are 31-bit in the kernel
     if ((int64_t)N * K * P * Q >= (1ll << 31)) return POLYDL_ERR_UNSUPPORTED;
-    hipError_t e = launch_bnorm_act(x, y, gamma, beta, mean, var, eps, K, P * Q, (size_t)N * K * P * Q, act,
-                                    (hipStream_t)stream);
-    return e == hipSuccess ? POLYDL_OK : launch_failed(e);
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_bnorm_act(x, y, gamma, beta, mean, var, eps, K, P * Q, (size_t)N * K * P * Q, act,
+                                     (hipStream_t)stream));
 }
 
 int polydl_activation(int64_t count, float *y, int act, void *stream)
@@ -444,7 +504,8 @@ int polydl_activation(int64_t count, float *y, int act, void *stream)
     if (count <= 0) return POLYDL_ERR_BAD_DIMENSION;
     if (!y) return POLYDL_ERR_NULL_POINTER;
     if (act != POLYDL_ACT_RELU && act != POLYDL_ACT_RELU6) return POLYDL_ERR_UNSUPPORTED;
-    return launch_act(y, (size_t)count, act, (hipStream_t)stream) == hipSuccess ? POLYDL_OK : POLYDL_ERR_LAUNCH;
+    if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
+    return launched(launch_act(y, (size_t)count, act, (hipStream_t)stream));
 }
 
 int polydl_reuse_analyse(int nloops, const int *extents, const int *parallel, int nrefs, const polydl_loop_ref *refs,
@@ -669,6 +730,44 @@ int polydl_pick_sgemm(int M, int N, int K, polydl_tile_cfg *cfg, polydl_model_re
     return POLYDL_OK;
 }
 
+int polydl_conv2d_candidates(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int kind,
+                             int max_cfgs, polydl_tile_cfg *cfgs, int *count)
+{
+    if (!count || (max_cfgs > 0 && !cfgs)) return POLYDL_ERR_NULL_POINTER;
+    if (max_cfgs < 0) return POLYDL_ERR_BAD_DIMENSION;
+    std::vector<polydl_tile_cfg> list;
+    if (kind == 0) {
+        int64_t P, Q;
+        if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
+        if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
+        ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
+        std::vector<ConvCandidate> cands;
+        conv_candidates(q, &cands);
+        for (const ConvCandidate &c : cands) list.push_back(c.cfg);
+    } else if (kind == 2) {
+        ConvProblem q;
+        int st = POLYDL_OK;
+        if (!bf16_problem(N, C, H, W, K, R, S, stride, pad, &q, &st)) return st;
+        bf16_candidates(q, &list);
+    } else {
+        return POLYDL_ERR_UNSUPPORTED;
+    }
+    *count = (int)list.size();
+    for (int i = 0; i < *count && i < max_cfgs; ++i) cfgs[i] = list[i];
+    return POLYDL_OK;
+}
+
+int polydl_sgemm_candidates(int M, int N, int K, int max_cfgs, polydl_tile_cfg *cfgs, int *count)
+{
+    if (!count || (max_cfgs > 0 && !cfgs)) return POLYDL_ERR_NULL_POINTER;
+    if (M <= 0 || N <= 0 || K <= 0 || max_cfgs < 0) return POLYDL_ERR_BAD_DIMENSION;
+    std::vector<polydl_tile_cfg> list;
+    sgemm_candidates(SgemmProblem{M, N, K, nullptr, nullptr, nullptr}, &list);
+    *count = (int)list.size();
+    for (int i = 0; i < *count && i < max_cfgs; ++i) cfgs[i] = list[i];
+    return POLYDL_OK;
+}
+
 int polydl_set_tile_override(const polydl_tile_cfg *cfg)
 {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -725,7 +824,7 @@ const char *polydl_status_string(int status)
     case POLYDL_ERR_BAD_DIMENSION: return "bad dimension";
     case POLYDL_ERR_UNSUPPORTED: return "unsupported configuration";
     case POLYDL_ERR_LAUNCH: return "HIP launch failed";
-    case POLYDL_ERR_NO_DEVICE: return "no device";
+    case POLYDL_ERR_NO_DEVICE: return "the current device is not a gfx950 GPU";
     default: return "unknown status";
     }
 }

@@ -246,7 +246,7 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
                 for (int r = 0; r < 16; ++r)
                     __hip_atomic_store(mine + ((bi * T::NB + bj) * 16 + r) * NT + tid, acc[bi][bj][r], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's device-scope stores have completed
+        wait_vmcnt0();   // vmcnt(0): this wave's device-scope stores have completed
         __syncthreads();
         if (tid == 0)
             s_arrived = __hip_atomic_fetch_add(p.counters + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -351,13 +351,13 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     a.pre_act = q.pre_act;
     a.partials = nullptr;
     a.counters = nullptr;
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     const int tiles = a.tiles_m * a.tiles_n;
     a.whole_tiles = tiles; a.tail_parts = 1; a.tail_k = a.k_per_split; a.recip_tail = 0;
     dim3 grid((unsigned)tiles, (unsigned)a.split_k), block(T::NT);
     if (a.split_k > 1) {
         const size_t bytes = (size_t)tiles * a.split_k * T::BM * T::BN * sizeof(float);
-        hipError_t e = splitk_scratch(stream, bytes, tiles, &a.partials, &a.counters);
+        hipError_t e = splitk_scratch(stream, q.arena, bytes, tiles, &a.partials, &a.counters);
         if (e != hipSuccess) return e;
     } else {
         // raster 2: an unsplit grid whose last round would leave most compute units idle has the
@@ -367,7 +367,7 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
             a.whole_tiles = tiles - ts.tiles; a.tail_parts = ts.parts; a.tail_k = ts.stages_per_part * T::BK;
             a.recip_tail = div_recip((uint32_t)ts.parts);
             const size_t bytes = (size_t)ts.tiles * ts.parts * T::BM * T::BN * sizeof(float);
-            hipError_t e = splitk_scratch(stream, bytes, ts.tiles, &a.partials, &a.counters);
+            hipError_t e = splitk_scratch(stream, q.arena, bytes, ts.tiles, &a.partials, &a.counters);
             if (e != hipSuccess) return e;
             grid = dim3((unsigned)(a.whole_tiles + ts.tiles * ts.parts), 1u);
         }
@@ -375,7 +375,7 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
     const int mode = (q.R == 1 && q.S == 1 && q.pad == 0) ? GATHER_POINT
                      : a.RS <= 31 ? GATHER_TAPS1 : a.RS <= 63 ? GATHER_TAPS2 : GATHER_ANY;
-#define POLYDL_GO(AV, MODE) hipLaunchKernelGGL((conv_kernel<T, AV, MODE>), grid, block, 0, stream, a)
+#define POLYDL_GO(AV, MODE) le = launch_kernel((conv_kernel<T, AV, MODE>), grid, block, 0, stream, a)
     if (avec) {
         if (mode == GATHER_POINT) POLYDL_GO(4, GATHER_POINT);
         else if (mode == GATHER_TAPS1) POLYDL_GO(4, GATHER_TAPS1);
@@ -388,7 +388,7 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
         else POLYDL_GO(1, GATHER_ANY);
     }
 #undef POLYDL_GO
-    return hipGetLastError();
+    return le;
 }
 
 #define POLYDL_DEFINE_CONV(BM, BN, BK, WM, WN)                                                            \

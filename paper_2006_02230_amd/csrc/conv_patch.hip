@@ -386,7 +386,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     const int t_begin = cut ? part * p.stages_per_split : 0;
     const int t_end = cut ? min(p.nstages, t_begin + p.stages_per_split) : p.nstages;
     load_stage(t_begin, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's direct-to-LDS loads have landed
+    wait_vmcnt0();   // vmcnt(0): this wave's direct-to-LDS loads have landed
     __syncthreads();
     for (int t = t_begin; t < t_end; ++t) {
         const int buf = (t - t_begin) & 1;
@@ -409,7 +409,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             for (int cp = 0; cp < npairs; ++cp)
                 patch_pair<E, T, RC, SC>(A, B, a_base, b_base, cp * 2 * p.RSp, cp * 2 * chs, p.Rp, p.S, p.Wp, acc, bmul);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        wait_vmcnt0();   // vmcnt(0)
         __syncthreads();
     }
 
@@ -440,7 +440,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
         // too, but costs a write-back of the whole L2 per workgroup.  Instead: wait until this
         // wave's stores have completed (at device scope), meet the other waves, then count the
         // arrival; whoever sees the last count knows every part's stores completed before it.
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        wait_vmcnt0();   // vmcnt(0)
         __syncthreads();
         if (tid == 0)
             s_arrived = __hip_atomic_fetch_add(p.counters + cut_tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -589,13 +589,13 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
         (imgs + 1) * (long)q.K * PQl * 4 >= 0x7FFFFFF0l)
         return hipErrorInvalidConfiguration;
     if (dry) return hipSuccess;
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     a.partials = nullptr;
     a.counters = nullptr;
     const int cut_tiles = a.split_k > 1 ? tiles : 0;
     if (cut_tiles > 0) {
         const size_t bytes = (size_t)cut_tiles * a.split_k * T::BM * T::BN * sizeof(float);
-        hipError_t e = splitk_scratch(stream, bytes, cut_tiles, &a.partials, &a.counters);
+        hipError_t e = splitk_scratch(stream, q.arena, bytes, cut_tiles, &a.partials, &a.counters);
         if (e != hipSuccess) return e;
     }
     const long nwg = (long)(tiles - cut_tiles) + (long)cut_tiles * a.split_k;
@@ -614,8 +614,8 @@ static hipError_t conv_patch_launch(const ConvProblem &q, int cb, int split_k, i
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a);
-    return hipGetLastError();
+    le = launch_kernel(kern, grid, block, lds_bytes, stream, a);
+    return le;
 }
 
 #define POLYDL_DEFINE_CONV_PATCH(BM, BN, BK, WM, WN)                                                     \

@@ -188,11 +188,11 @@ hipError_t conv_point_launch(const ConvProblem &q, hipStream_t stream)
     a.recip_groups = div_recip((uint32_t)a.groups);
     a.recip_HW = div_recip((uint32_t)a.HW);
     a.act = q.act;
-    clear_stale_hip_error();
-    if (q.C == 64) hipLaunchKernelGGL(conv_point_kernel<8>, dim3(wgs), dim3(256), 0, stream, a);
-    else if (q.C == 32) hipLaunchKernelGGL(conv_point_kernel<4>, dim3(wgs), dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(conv_point_kernel<2>, dim3(wgs), dim3(256), 0, stream, a);
-    return hipGetLastError();
+    hipError_t le = hipSuccess;
+    if (q.C == 64) le = launch_kernel(conv_point_kernel<8>, dim3(wgs), dim3(256), 0, stream, a);
+    else if (q.C == 32) le = launch_kernel(conv_point_kernel<4>, dim3(wgs), dim3(256), 0, stream, a);
+    else le = launch_kernel(conv_point_kernel<2>, dim3(wgs), dim3(256), 0, stream, a);
+    return le;
 }
 
 }  // namespace polydl

@@ -66,6 +66,18 @@ __device__ __forceinline__ void buf_store4(__amdgpu_buffer_rsrc_t r, uint32_t by
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v), r, (int)byte_off, (int)uniform_off, 0);
 }
 
+// Blocks the wave until every vector-memory operation it has issued (loads, stores, direct-to-LDS
+// loads) has completed: s_waitcnt vmcnt(0), the other counters left alone.  The immediate is the
+// gfx9-family encoding (vmcnt in bits 3:0 and 15:14, expcnt 6:4 = 7, lgkmcnt 11:8 = 15), where
+// stores count in vmcnt too; this library is built for gfx950 only.
+__device__ __forceinline__ void wait_vmcnt0()
+{
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "s_waitcnt encoding and counter semantics below are those of gfx950"
+#endif
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
 // n / d and n % d for any 32-bit n and d >= 1, given recip = floor(2^32 / d) (0xFFFFFFFF for
 // d == 1): umulhi(n, recip) is the quotient or one below it, which one comparison settles.
 __device__ __forceinline__ uint32_t div_by(uint32_t n, uint32_t d, uint32_t recip, uint32_t &rem)

@@ -2,16 +2,29 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <tuple>
+#include <utility>
 #include <vector>
 #include "../../include/polydl.h"
 
 namespace polydl {
+
+// Where a split-reduction launch takes its partial tiles and arrival counters from when not from
+// the library's own per-stream buffers.
+struct ScratchArena {
+    float *partials = nullptr;
+    size_t partial_bytes = 0;
+    unsigned *counters = nullptr;
+    int ncounters = 0;
+    bool clear_counters = false;   // zero the counters a launch will use (small kernel on its stream) first
+};
 
 struct SgemmProblem {
     int M, N, K;
     const float *A, *B;
     float *C;
     float alpha = 1.f, beta = 1.f;   // C = beta*C + alpha*A*B
+    const ScratchArena *arena = nullptr;
 };
 
 struct ConvProblem {
@@ -21,6 +34,7 @@ struct ConvProblem {
     float *out;
     int act;
     int pre_act = 0;       // polydl_act applied to every input element as it is read (gather kernel only)
+    const ScratchArena *arena = nullptr;   // split reductions: nullptr = the library's per-stream buffers
 };
 
 // One compiled variant: its tile parameters and the launchers instantiated for it.
@@ -69,9 +83,15 @@ hipError_t launch_act(float *y, size_t total, int act, hipStream_t st);
 hipError_t launch_bnorm_act(const float *x, float *y, const float *gamma, const float *beta, const float *mean,
                             const float *var, float eps, int K, int PQ, size_t total, int act, hipStream_t st);
 
-// scratch.cpp: partial-tile buffer (>= partial_bytes) and zeroed arrival counters (>= tiles) for
-// split-reduction launches on this device and stream
-hipError_t splitk_scratch(hipStream_t stream, size_t partial_bytes, int tiles, float **partials, unsigned **counters);
+// scratch.hip: partial-tile buffer (>= partial_bytes) and zeroed arrival counters (>= tiles) for a
+// split-reduction launch, from `arena` or (arena == nullptr) from the buffers the library keeps for
+// this device and stream.  On failure scratch_refusal() tells this thread why, when the reason is
+// not the runtime's: the arena is too small, or the library's buffers would have to grow while the
+// stream is being captured.
+enum { SCRATCH_OK = 0, SCRATCH_TOO_SMALL = 1, SCRATCH_CAPTURING = 2 };
+hipError_t splitk_scratch(hipStream_t stream, const ScratchArena *arena, size_t partial_bytes, int tiles,
+                          float **partials, unsigned **counters);
+int scratch_refusal();
 int compute_units();   // of the current device
 
 // Workgroups of one launch are all resident at once or run in rounds; either way a compute unit
@@ -95,10 +115,23 @@ inline TailSplit tail_split(int tiles, int stages, int cus)
     return t;
 }
 
-// hipGetLastError() reports the last error of any HIP call of this thread, including benign ones
-// left by the caller (an event query that was not ready, say).  Launchers clear that state first
-// so that what they return is about their own launch.
-inline void clear_stale_hip_error() { (void)hipGetLastError(); }
+// Launch with the runtime's verdict as the return value (hipGetLastError() would also report, and
+// clear, errors other code of this thread left behind).  Arguments are converted to the kernel's
+// parameter types.
+template <class... P, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                                     std::tuple<P...> &vals, std::index_sequence<I...>)
+{
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds, st);
+}
+template <class... P, class... A>
+inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t st, A... args)
+{
+    static_assert(sizeof...(P) == sizeof...(A), "argument count");
+    std::tuple<P...> vals{static_cast<P>(args)...};
+    return launch_kernel_impl(kernel, grid, block, lds, st, vals, std::index_sequence_for<P...>{});
+}
 
 // picker.cpp
 void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem);
@@ -111,6 +144,7 @@ bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_repor
 struct ConvCandidate { polydl_tile_cfg cfg; polydl_model_report rep; };
 // every (variant, stage depth, split factor, leftover-tile switch) pick_conv ranks, with its model report
 void conv_candidates(const ConvProblem &q, std::vector<ConvCandidate> *out);
+void sgemm_candidates(const SgemmProblem &q, std::vector<polydl_tile_cfg> *out);
 
 // conv_point.hip: pointwise convolution with the filter resident in LDS (cfg.algo == 2; one variant:
 // 32 output channels x 64 pixels per wave and unit, 256 threads)

@@ -222,24 +222,24 @@ __global__ void bnorm_act_kernel(const float *__restrict__ x, float *__restrict_
 hipError_t launch_bnorm_act(const float *x, float *y, const float *gamma, const float *beta, const float *mean,
                             const float *var, float eps, int K, int PQ, size_t total, int act, hipStream_t st)
 {
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     const bool vec = PQ % 4 == 0 && (((uintptr_t)x | (uintptr_t)y) & 15) == 0;
     const uint32_t units = (uint32_t)(vec ? total / 4 : total);
     const unsigned blocks = (unsigned)((units + 255) / 256 < 16384 ? (units + 255) / 256 : 16384);
     if (vec)
-        hipLaunchKernelGGL((bnorm_act_kernel<4>), dim3(blocks), dim3(256), 0, st, x, y, gamma, beta, mean, var, eps,
+        le = launch_kernel((bnorm_act_kernel<4>), dim3(blocks), dim3(256), 0, st, x, y, gamma, beta, mean, var, eps,
                            (uint32_t)K, (uint32_t)PQ, units, act);
     else
-        hipLaunchKernelGGL((bnorm_act_kernel<1>), dim3(blocks), dim3(256), 0, st, x, y, gamma, beta, mean, var, eps,
+        le = launch_kernel((bnorm_act_kernel<1>), dim3(blocks), dim3(256), 0, st, x, y, gamma, beta, mean, var, eps,
                            (uint32_t)K, (uint32_t)PQ, units, act);
-    return hipGetLastError();
+    return le;
 }
 
 // elem_bytes: 4 (float) or 2 (bfloat16 bit patterns; a permutation does not look at the values)
 hipError_t launch_nchwc(const void *src, void *dst, int N, int C, int HW, int b, bool to_blocked, int elem_bytes,
                         hipStream_t st)
 {
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     int Cb = (C + b - 1) / b;
     dim3 grid((unsigned)((HW + 255) / 256), (unsigned)Cb, (unsigned)N);
     size_t lds = (size_t)b * 257 * elem_bytes;
@@ -248,57 +248,57 @@ hipError_t launch_nchwc(const void *src, void *dst, int N, int C, int HW, int b,
         float *d = static_cast<float *>(dst);
         if (b % 4 == 0 && HW % 4 == 0 && ((uintptr_t)src & 15) == 0 && ((uintptr_t)dst & 15) == 0) {
             const size_t wide_lds = (size_t)b * 260 * sizeof(float);
-            if (to_blocked) hipLaunchKernelGGL((nchwc_wide_kernel<true>), grid, dim3(256), wide_lds, st, s, d, C, HW, b, Cb);
-            else hipLaunchKernelGGL((nchwc_wide_kernel<false>), grid, dim3(256), wide_lds, st, s, d, C, HW, b, Cb);
-            return hipGetLastError();
+            if (to_blocked) le = launch_kernel((nchwc_wide_kernel<true>), grid, dim3(256), wide_lds, st, s, d, C, HW, b, Cb);
+            else le = launch_kernel((nchwc_wide_kernel<false>), grid, dim3(256), wide_lds, st, s, d, C, HW, b, Cb);
+            return le;
         }
-        if (to_blocked) hipLaunchKernelGGL((nchwc_kernel<float, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
-        else hipLaunchKernelGGL((nchwc_kernel<float, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+        if (to_blocked) le = launch_kernel((nchwc_kernel<float, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+        else le = launch_kernel((nchwc_kernel<float, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
     } else {
         const uint16_t *s = static_cast<const uint16_t *>(src);
         uint16_t *d = static_cast<uint16_t *>(dst);
         if (to_blocked && b == 8 && HW % 8 == 0 && ((uintptr_t)src & 15) == 0 && ((uintptr_t)dst & 15) == 0) {
             dim3 g8((unsigned)((HW + 511) / 512), (unsigned)Cb, (unsigned)N);
-            hipLaunchKernelGGL(nchw8c_16bit_kernel, g8, dim3(256), 0, st, s, d, C, HW, Cb);
-            return hipGetLastError();
+            le = launch_kernel(nchw8c_16bit_kernel, g8, dim3(256), 0, st, s, d, C, HW, Cb);
+            return le;
         }
-        if (to_blocked) hipLaunchKernelGGL((nchwc_kernel<uint16_t, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
-        else hipLaunchKernelGGL((nchwc_kernel<uint16_t, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+        if (to_blocked) le = launch_kernel((nchwc_kernel<uint16_t, true>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
+        else le = launch_kernel((nchwc_kernel<uint16_t, false>), grid, dim3(256), lds, st, s, d, C, HW, b, Cb);
     }
-    return hipGetLastError();
+    return le;
 }
 
 hipError_t launch_kcrsck(const void *wt, void *dst, int K, int C, int RS, int bc, int bk, int elem_bytes,
                          hipStream_t st)
 {
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     int Kb = (K + bk - 1) / bk, Cb = (C + bc - 1) / bc;
     size_t total = (size_t)Kb * Cb * RS * bc * bk;
     dim3 grid((unsigned)((total + 255) / 256));
     if (elem_bytes == 4)
-        hipLaunchKernelGGL(kcrsck_kernel<float>, grid, dim3(256), 0, st, static_cast<const float *>(wt),
+        le = launch_kernel(kcrsck_kernel<float>, grid, dim3(256), 0, st, static_cast<const float *>(wt),
                            static_cast<float *>(dst), K, C, RS, bc, bk, Cb, total);
     else
-        hipLaunchKernelGGL(kcrsck_kernel<uint16_t>, grid, dim3(256), 0, st, static_cast<const uint16_t *>(wt),
+        le = launch_kernel(kcrsck_kernel<uint16_t>, grid, dim3(256), 0, st, static_cast<const uint16_t *>(wt),
                            static_cast<uint16_t *>(dst), K, C, RS, bc, bk, Cb, total);
-    return hipGetLastError();
+    return le;
 }
 
 hipError_t launch_bias_add(float *y, const float *bias, int K, int PQ, size_t total, hipStream_t st)
 {
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     unsigned blocks = (unsigned)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-    hipLaunchKernelGGL(bias_add_kernel, dim3(blocks), dim3(256), 0, st, y, bias, K, PQ, total);
-    return hipGetLastError();
+    le = launch_kernel(bias_add_kernel, dim3(blocks), dim3(256), 0, st, y, bias, K, PQ, total);
+    return le;
 }
 
 hipError_t launch_act(float *y, size_t total, int act, hipStream_t st)
 {
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     size_t work = (total + 3) / 4;
     unsigned blocks = (unsigned)((work + 255) / 256 < 8192 ? (work + 255) / 256 : 8192);
-    hipLaunchKernelGGL(act_kernel, dim3(blocks), dim3(256), 0, st, y, total, act);
-    return hipGetLastError();
+    le = launch_kernel(act_kernel, dim3(blocks), dim3(256), 0, st, y, total, act);
+    return le;
 }
 
 }  // namespace polydl

@@ -41,7 +41,9 @@ static const Level kLevels[4] = {
 };
 static const double kHbmGBs = 4500.0;       // sustained mixed read/write HBM rate
 static const double kClockHz = 2.4e9;
-static const int kCUs = 256, kSimdsPerCU = 4, kXcds = 8;
+static const int kSimdsPerCU = 4, kXcds = 8;
+// compute units of the current device (256 on an MI355X; also the answer when no device is visible)
+#define kCUs (compute_units())
 
 void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem)
 {
@@ -486,10 +488,10 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
     return true;
 }
 
-bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *best_rep)
+// every (variant, split factor, workgroup order) pick_sgemm ranks
+void sgemm_candidates(const SgemmProblem &q, std::vector<polydl_tile_cfg> *out)
 {
-    bool have = false;
-    polydl_model_report rep;
+    out->clear();
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         const long stages = ((long)q.K + v.bk - 1) / v.bk;
@@ -497,13 +499,22 @@ bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_repor
         static const int kSgemmSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128};
         for (int sk : kSgemmSplits) {
             if (sk > stages) break;
-            for (int raster = 0; raster < 2; ++raster) {
-                polydl_tile_cfg c = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, raster, 0, 0};
-                model_sgemm(q, c, v.threads, &rep);
-                if (raster == 1) rep.predicted_us *= 0.999;   // ties go to the XCD-aware order
-                if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
-            }
+            for (int raster = 0; raster < 2; ++raster)
+                out->push_back(polydl_tile_cfg{v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, raster, 0, 0});
         }
+    }
+}
+
+bool pick_sgemm(const SgemmProblem &q, polydl_tile_cfg *best, polydl_model_report *best_rep)
+{
+    bool have = false;
+    polydl_model_report rep;
+    std::vector<polydl_tile_cfg> cands;
+    sgemm_candidates(q, &cands);
+    for (const polydl_tile_cfg &c : cands) {
+        model_sgemm(q, c, (c.bm / c.wm) * (c.bn / c.wn) * 64, &rep);
+        if (c.raster == 1) rep.predicted_us *= 0.999;   // ties go to the XCD-aware order
+        if (!have || rep.predicted_us < best_rep->predicted_us) { *best = c; *best_rep = rep; have = true; }
     }
     return have;
 }

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
                 for (int r = 0; r < 16; ++r)
                     __hip_atomic_store(mine + ((bi * T::NB + bj) * 16 + r) * NT + tid, acc[bi][bj][r], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's device-scope stores have completed
+        wait_vmcnt0();   // vmcnt(0): this wave's device-scope stores have completed
         __syncthreads();
         if (tid == 0)
             s_arrived = __hip_atomic_fetch_add(p.counters + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -159,17 +159,17 @@ static hipError_t sgemm_launch(const SgemmProblem &q, int split_k, int raster, h
     a.alpha = q.alpha; a.beta = q.beta;
     a.partials = nullptr;
     a.counters = nullptr;
-    clear_stale_hip_error();
+    hipError_t le = hipSuccess;
     if (split_k > 1) {
         const size_t bytes = (size_t)a.tiles_m * a.tiles_n * split_k * T::BM * T::BN * sizeof(float);
-        hipError_t e = splitk_scratch(stream, bytes, a.tiles_m * a.tiles_n, &a.partials, &a.counters);
+        hipError_t e = splitk_scratch(stream, q.arena, bytes, a.tiles_m * a.tiles_n, &a.partials, &a.counters);
         if (e != hipSuccess) return e;
     }
     dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k), block(T::NT);
     const bool avec = (q.K % 4 == 0) && ((uintptr_t)q.A % 16 == 0);
     const bool bvec = (q.N % 4 == 0) && ((uintptr_t)q.B % 16 == 0);
     const bool cvec = (q.N % T::NB == 0) && ((uintptr_t)q.C % 16 == 0);
-#define POLYDL_GO(AV, BV, CV) hipLaunchKernelGGL((sgemm_kernel<T, AV, BV, CV>), grid, block, 0, stream, a)
+#define POLYDL_GO(AV, BV, CV) le = launch_kernel((sgemm_kernel<T, AV, BV, CV>), grid, block, 0, stream, a)
     if (avec && bvec && cvec) POLYDL_GO(4, 4, true);
     else if (avec && bvec) POLYDL_GO(4, 4, false);
     else if (avec && cvec) POLYDL_GO(4, 1, true);
@@ -179,7 +179,7 @@ static hipError_t sgemm_launch(const SgemmProblem &q, int split_k, int raster, h
     else if (cvec) POLYDL_GO(1, 1, true);
     else POLYDL_GO(1, 1, false);
 #undef POLYDL_GO
-    return hipGetLastError();
+    return le;
 }
 
 #define POLYDL_DEFINE_SGEMM(BM, BN, BK, WM, WN)                                                            \
