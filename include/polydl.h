@@ -27,7 +27,7 @@
  *   - HIP graphs: every entry point may be captured.  Three rules follow from the scratch memory
  *     above.  (1) A call that would have to allocate or grow it while its stream is being
  *     captured returns POLYDL_ERR_UNSUPPORTED and records nothing: run the same call once on
- *     that stream before capturing.  (2) A graph keeps the
+ *     that stream before capturing (or use polydl_conv2d_fwd_noalloc).  (2) A graph keeps the
  *     scratch addresses of its capture stream; they stay valid for the life of the process.
  *     (3) Replaying the graph, on any stream, uses the scratch memory of the stream it was
  *     CAPTURED on: do not let a replay overlap in time with other split-reduction work of this
@@ -50,7 +50,9 @@ typedef enum polydl_status {
     POLYDL_ERR_BAD_DIMENSION = -2,  /* a size <= 0, stride <= 0, pad < 0, or no output (P or Q <= 0) */
     POLYDL_ERR_UNSUPPORTED = -3,    /* valid problem outside the kernels' index range, bad override */
     POLYDL_ERR_LAUNCH = -4,         /* the HIP runtime refused the launch or an allocation */
-    POLYDL_ERR_NO_DEVICE = -5       /* the current device is not a gfx950 GPU (or there is none) */
+    POLYDL_ERR_NO_DEVICE = -5,      /* the current device is not a gfx950 GPU (or there is none) */
+    POLYDL_ERR_SCRATCH_LIMIT = -6   /* polydl_conv2d_fwd_noalloc: the problem's variant needs more scratch
+                                       memory than the fixed array holds; nothing was enqueued */
 } polydl_status;
 
 /* Element-wise operator applied to every output after the reduction (section "Operator
@@ -115,6 +117,22 @@ int polydl_conv2d_fwd_act(int N, int C, int H, int W, int K, int R, int S, int s
 int polydl_conv2d_fwd_pre_act(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                               const float *in, const float *wt, const float *bias, float *out,
                               int pre_act /* polydl_act */, int act /* polydl_act */, void *stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): polydl_conv2d_fwd_act with the scratch memory of split
+ * reductions taken from a fixed array inside the library's code object instead of from
+ * hipMalloc.  Same arguments, same variant choice and bit for bit the same result as
+ * polydl_conv2d_fwd_act.  The call makes no hipMalloc / hipFree and no call into an allocating
+ * library.  The array holds 64 MiB of partial tiles and 16384 arrival counters per device (each
+ * device the library runs on keeps its copy until the process ends); a problem whose chosen variant
+ * needs more returns POLYDL_ERR_SCRATCH_LIMIT with nothing enqueued (an unsplit variant, forced
+ * through polydl_set_tile_override, needs none).  Every call on a device shares that device's
+ * array, whatever its stream: the counters a call uses are cleared by a small kernel on its stream
+ * first, and two calls that overlap in time on one device race on it -- keep them on one stream or
+ * order them with events. */
+int polydl_conv2d_fwd_noalloc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              const float *in, const float *wt, const float *bias, float *out,
+                              int act /* polydl_act */, void *stream);
 
 /* ---- matrix product ------------------------------------------------------------------------
  * C[i][j] += sum_k A[i][k] * B[k][j]   (alpha = beta = 1, the reading taken of section "GEMM").

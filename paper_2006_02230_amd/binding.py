@@ -60,6 +60,8 @@ lib.polydl_conv2d_fwd.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_conv2d_fwd_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_conv2d_fwd_pre_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _i, _p]
 lib.polydl_conv2d_fwd_pre_act.restype = _i
+lib.polydl_conv2d_fwd_noalloc.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
+lib.polydl_conv2d_fwd_noalloc.restype = _i
 lib.polydl_sgemm.argtypes = [_i, _i, _i, _p, _p, _p, _p]
 lib.polydl_sgemm_ex.argtypes = [_i, _i, _i, ctypes.c_float, _p, _p, ctypes.c_float, _p, _p]
 lib.polydl_sgemm_ex.restype = _i
@@ -233,6 +235,19 @@ def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None
                                            _dev(bias, "bias"), _dev(out, "out"), ACT[pre_act], ACT[act],
                                            _stream_ptr(stream))
     _check(st, "polydl_conv2d_fwd")
+    return out
+
+
+def conv2d_fwd_noalloc(x, w, bias, out, stride=1, pad=0, act=None, stream=None):
+    """polydl_conv2d_fwd_noalloc: as conv2d_fwd into a caller-provided out, scratch memory from the
+    library's fixed array (the call allocates nothing)."""
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    st = lib.polydl_conv2d_fwd_noalloc(N, C, H, W, K, R, S, stride, pad, _dev(x, "x"), _dev(w, "w"),
+                                       _dev(bias, "bias"), _dev(out, "out"), ACT[act], _stream_ptr(stream))
+    _check(st, "polydl_conv2d_fwd_noalloc")
     return out
 
 

@@ -39,7 +39,7 @@ static int launch_failed(hipError_t e)
 {
     // a launch that needed scratch memory it may not have: not the runtime's refusal
     const int why = scratch_refusal();
-    if (e == hipErrorOutOfMemory && why == SCRATCH_TOO_SMALL) return POLYDL_ERR_UNSUPPORTED;
+    if (e == hipErrorOutOfMemory && why == SCRATCH_TOO_SMALL) return POLYDL_ERR_SCRATCH_LIMIT;
     if (e == hipErrorStreamCaptureUnsupported && why == SCRATCH_CAPTURING) return POLYDL_ERR_UNSUPPORTED;
     g_last_hip_error = (int)e;
     return POLYDL_ERR_LAUNCH;
@@ -294,6 +294,19 @@ int polydl_conv2d_fwd_pre_act(int N, int C, int H, int W, int K, int R, int S, i
                               int act, void *stream)
 {
     return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, pre_act, act, stream);
+}
+
+int polydl_conv2d_fwd_noalloc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              const float *in, const float *wt, const float *bias, float *out, int act,
+                              void *stream)
+{
+    ScratchArena arena;
+    const hipError_t e = static_scratch_arena(&arena);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return POLYDL_ERR_LAUNCH;
+    }
+    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, POLYDL_ACT_NONE, act, stream, &arena);
 }
 
 int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream)
@@ -825,6 +838,7 @@ const char *polydl_status_string(int status)
     case POLYDL_ERR_UNSUPPORTED: return "unsupported configuration";
     case POLYDL_ERR_LAUNCH: return "HIP launch failed";
     case POLYDL_ERR_NO_DEVICE: return "the current device is not a gfx950 GPU";
+    case POLYDL_ERR_SCRATCH_LIMIT: return "needs more scratch memory than the fixed array holds";
     default: return "unknown status";
     }
 }

@@ -92,6 +92,10 @@ enum { SCRATCH_OK = 0, SCRATCH_TOO_SMALL = 1, SCRATCH_CAPTURING = 2 };
 hipError_t splitk_scratch(hipStream_t stream, const ScratchArena *arena, size_t partial_bytes, int tiles,
                           float **partials, unsigned **counters);
 int scratch_refusal();
+// the fixed scratch array of the current device (address looked up on the first call per device)
+constexpr size_t kStaticCounterBytes = 64 * 1024;            // 16384 tiles
+constexpr size_t kStaticPartialBytes = 64 * 1024 * 1024;
+hipError_t static_scratch_arena(ScratchArena *arena);
 int compute_units();   // of the current device
 
 // Workgroups of one launch are all resident at once or run in rounds; either way a compute unit

@@ -1,9 +1,12 @@
 // Device scratch memory of the split-reduction kernels: partial accumulator tiles and one arrival
-// counter per tile, in buffers the library allocates per (device, stream) unless the caller of a
-// launcher brings an arena of its own.  Work on one stream is ordered, so consecutive launches on
-// it may share a buffer; launches on different streams get different ones.  A buffer that has
-// been handed out is never freed: a larger one is allocated beside it and the old one stays valid
-// for launches recorded earlier (a captured graph keeps the addresses it was recorded with).
+// counter per tile.  Two sources:
+//   * buffers the library allocates per (device, stream).  Work on one stream is ordered, so
+//     consecutive launches on it may share a buffer; launches on different streams get different
+//     ones.  A buffer that has been handed out is never freed: a larger one is allocated beside
+//     it and the old one stays valid for launches recorded earlier (a captured graph keeps the
+//     addresses it was recorded with);
+//   * one fixed array in the code object (`scratch` below), for the entry point that may not
+//     allocate.  Every device the library runs on holds its own copy for the life of the process.
 #include <hip/hip_runtime.h>
 #include <map>
 #include <mutex>
@@ -12,6 +15,11 @@
 #include "internal.hpp"
 
 namespace polydl {
+
+// The fixed array: counters first, partial tiles behind them.  In host code this name is only a
+// handle for hipGetSymbolAddress; the device address is asked for once per device and used from
+// then on.
+static __device__ __align__(256) unsigned char scratch[kStaticCounterBytes + kStaticPartialBytes];
 
 __global__ void zero_words_kernel(unsigned *p, int n)
 {
@@ -29,6 +37,7 @@ struct Scratch {
 };
 std::mutex g_scratch_mu;
 std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
+std::map<int, unsigned char *> g_static_base;   // device -> address of that device's copy of `scratch`
 thread_local int t_refusal = SCRATCH_OK;
 
 bool capturing(hipStream_t stream)
@@ -43,6 +52,28 @@ bool capturing(hipStream_t stream)
 }  // namespace
 
 int scratch_refusal() { return t_refusal; }
+
+hipError_t static_scratch_arena(ScratchArena *arena)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    auto it = g_static_base.find(dev);
+    if (it == g_static_base.end()) {
+        unsigned char *base = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&base), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!base) return hipErrorInvalidSymbol;
+        it = g_static_base.emplace(dev, base).first;
+    }
+    arena->counters = reinterpret_cast<unsigned *>(it->second);
+    arena->ncounters = (int)(kStaticCounterBytes / sizeof(unsigned));
+    arena->partials = reinterpret_cast<float *>(it->second + kStaticCounterBytes);
+    arena->partial_bytes = kStaticPartialBytes;
+    arena->clear_counters = true;
+    return hipSuccess;
+}
 
 // Buffers of at least partial_bytes bytes and `tiles` counters, all counters zero (every kernel
 // leaves the counters it used at zero again).

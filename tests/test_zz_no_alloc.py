@@ -1,0 +1,87 @@
+"""polydl_conv2d_fwd_noalloc (scratch memory from the library's fixed array) gives bit for bit what
+polydl_conv2d_fwd_act gives, on two calls in a row that share the array, the second one smaller;
+a variant that needs more than the array holds is refused with its own status."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import FP32_TOL, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2006_02230_amd as p
+    yield p
+    p.set_tile_override(None)
+
+
+def both(P, s, x, w, b, act):
+    import torch
+    Pq, Qq = synth.out_hw(s)
+    dx, dw, db = dev(x), dev(w), dev(b)
+    ref = P.conv2d_fwd(dx, dw, db, stride=s.stride, pad=s.pad, act=act)
+    tile_ref = P.get_last_tile().as_dict()
+    out = torch.full((s.N, s.K, Pq, Qq), float("nan"), dtype=torch.float32, device="cuda")
+    st = P.lib.polydl_conv2d_fwd_noalloc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad,
+                                         ctypes.c_void_p(dx.data_ptr()), ctypes.c_void_p(dw.data_ptr()),
+                                         ctypes.c_void_p(db.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                         P.ACT[act], ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert st == 0, P.status_string(st)
+    assert P.get_last_tile().as_dict() == tile_ref
+    return host(ref), host(out), tile_ref
+
+
+def test_two_calls_share_the_fixed_scratch(P):
+    P.set_tile_override(None)
+    # the picker splits the reduction of both (few output tiles, long reductions): scratch tiles
+    # and counters are in use; the second problem is smaller and reuses the front of the array
+    big = synth.RESNET50_SUITE(32)[6]                       # 512 -> 512, 7x7, 3x3
+    small = synth.ConvShape("small", 4, 256, 7, 7, 192, 3, 3, 1, 1)
+    for s, seed in ((big, 91), (small, 92)):
+        x, w, b = synth.conv_inputs(s, seed=seed, dist="normal", bias=True)
+        ref, got, tile = both(P, s, x, w, b, "relu")
+        assert tile["split_k"] > 1 or tile["raster"] == 2, tile
+        assert np.array_equal(got, ref), (s.name, tile)
+        want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+        assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (s.name, tile)
+    # every kernel with a split reduction, forced, again a larger problem first
+    shapes = [synth.ConvShape("a", 3, 48, 13, 11, 150, 3, 3, 1, 1), synth.ConvShape("b", 1, 16, 6, 6, 20, 3, 3, 1, 1)]
+    for v in (P.TileCfg(64, 64, 16, 32, 32, 3, 0, 0, 0, 0), P.TileCfg(64, 64, 0, 32, 32, 3, 0, 0, 1, 4),
+              P.TileCfg(64, 64, 16, 32, 32, 1, 0, 2, 0, 0)):
+        P.set_tile_override(v)
+        for s, seed in zip(shapes, (93, 94)):
+            x, w, b = synth.conv_inputs(s, seed=seed, dist="normal", bias=True)
+            ref, got, tile = both(P, s, x, w, b, "relu6")
+            assert np.array_equal(got, ref), (s.name, tile)
+            want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu6")
+            assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (s.name, tile)
+    P.set_tile_override(None)
+
+
+def test_a_variant_beyond_the_array_is_refused(P):
+    import torch
+    # 16 parts of 3136 tiles of 128 x 128 floats: 3.3 GB of partial tiles, far beyond the 64 MiB array
+    s = synth.ConvShape("big", 32, 64, 56, 56, 256, 3, 3, 1, 1)
+    x, w, b = synth.conv_inputs(s, seed=95, dist="normal", bias=True)
+    dx, dw, db = dev(x), dev(w), dev(b)
+    out = torch.zeros((s.N, s.K, 56, 56), dtype=torch.float32, device="cuda")
+    P.set_tile_override(P.TileCfg(128, 128, 16, 64, 64, 16, 0, 0, 0, 0))
+    with pytest.raises(P.PolydlError) as err:
+        P.conv2d_fwd_noalloc(dx, dw, db, out, stride=1, pad=1, act="relu")
+    assert err.value.status == -6
+    torch.cuda.synchronize()
+    assert not host(out).any()            # nothing was enqueued
+    # the same variant unsplit needs no scratch memory at all
+    P.set_tile_override(P.TileCfg(128, 128, 16, 64, 64, 1, 0, 0, 0, 0))
+    got = host(P.conv2d_fwd_noalloc(dx, dw, db, out, stride=1, pad=1, act="relu"))
+    P.set_tile_override(None)
+    want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=1, pad=1, act="relu")
+    assert oracle.scaled_error(got, want, ab) <= FP32_TOL
