@@ -28,6 +28,10 @@ HBM_PEAK_GBS = 8000.0
 HBM_TRAFFIC = {"csrc_sha256": "fa779a9ab7e660bf3b3aca7189b4eb0e6964271e0bc8260af9aa7332ec5db9d2", "batch": 32, "fetch_bytes": 733920506, "write_bytes": 457864632}
 
 
+# L2 fetch + write-back bytes of config 4 from two rocprofv3 --pmc runs of `bench.py --copy-probe --counter-pass
+# fusion` (same scaling as above): the fused launch, and the convolution + bias + activation launches it replaces.
+FUSION_TRAFFIC = {"csrc_sha256": "", "fused_bytes": 0, "separate_bytes": 0}
+
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
 
 
@@ -78,6 +82,11 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps first; about 50 ms of them bring the clocks to their steady state")
+    ap.add_argument("--clock-warm-ms", type=float, default=150.0,
+                    help="untimed load before the warm-up steps that brings the clocks to their steady state")
+    ap.add_argument("--counter-pass", default="", choices=["", "fusion", "bf16"],
+                    help="run only a few launches of one row, for a rocprofv3 --pmc pass: 'fusion' = the "
+                         "fused call and the three separate kernels of config 4, 'bf16' = the bf16 suite")
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--sweep", action="store_true", help="also time every compiled variant per layer")
     ap.add_argument("--sweep-out", default="", help="with --sweep: write every candidate's time to this JSON file")
@@ -89,6 +98,7 @@ def main():
                     "(an elementwise kernel of known traffic that calibrates the HBM byte counters)")
     ap.add_argument("--no-layer-rows", action="store_true", help="skip the per-layer timing loops (counter runs)")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache per-layer timings")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--layers", default="", help="comma list of suite layers to run (default: all eight); "
                     "a subset is for profiling one kernel and changes the workload the line reports")
     ap.add_argument("--tile", default="", help="force a variant bm,bn,bk,wm,wn[,split_k[,layout[,raster]]] (profiling)")
@@ -113,6 +123,35 @@ def main():
             torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.counter_pass == "fusion":
+        # dispatch order per repetition: fused convolution; then convolution, bias_add, activation
+        s = synth.CONFIG4
+        x, w, b = synth.conv_inputs(s, seed=300, dist="normal", bias=True)
+        Pq, Qq = synth.out_hw(s)
+        dx, dw, db = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
+        out = torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda")
+        for _ in range(4):
+            P.conv2d_fwd(dx, dw, db, out=out, stride=s.stride, pad=s.pad, act="relu")
+            torch.cuda.synchronize()
+            P.conv2d_fwd(dx, dw, None, out=out, stride=s.stride, pad=s.pad, act=None)
+            P.bias_add(out, db)
+            P.activation(out, "relu")
+            torch.cuda.synchronize()
+        print(json.dumps({"counter_pass": "fusion", "tile": P.get_last_tile().as_dict()}))
+        return
+    if args.counter_pass == "bf16":
+        for i, s in enumerate(synth.RESNET50_SUITE(64)):
+            x, w, b = synth.conv_inputs(s, seed=200 + i, dist="normal", bias=True)
+            xb = torch.from_numpy(synth.to_bf16_bits(x).view(np.int16)).cuda()
+            wb = torch.from_numpy(synth.to_bf16_bits(w).view(np.int16)).cuda()
+            x8, w8 = P.nchw_to_nchwc_bf16(xb, 8), P.kcrs_to_kcrsck_bf16(wb, 8, 1)
+            db = torch.from_numpy(b).cuda()
+            for _ in range(3):
+                P.conv2d_fwd_bf16_blocked(x8, w8, s.C, db, stride=s.stride, pad=s.pad, act="relu")
+            torch.cuda.synchronize()
+        print(json.dumps({"counter_pass": "bf16"}))
+        return
 
     suite = synth.RESNET50_SUITE(args.batch)
     chosen = [int(t) for t in args.layers.split(",") if t != ""] or list(range(len(suite)))
@@ -141,6 +180,13 @@ def main():
             run_layer(L)
 
     P.set_tile_override(forced)
+    # the GPU's clocks take tens of milliseconds of load to reach their steady state; a short --warmup
+    # would otherwise put the ramp inside the timed steps.  Untimed, before the W warm-up steps.
+    t_warm = time.perf_counter()
+    while (time.perf_counter() - t_warm) * 1e3 < args.clock_warm_ms:
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -154,6 +200,30 @@ def main():
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = wall_ms / args.steps
     total_flops = sum(L["flops"] for L in layers)
+
+    # the same step recorded once into a HIP graph and replayed: what a caller that keeps the launch
+    # sequence pays per step (no per-call argument marshalling, launches already formed)
+    graph_ms = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            step()                      # scratch memory of this stream exists before the capture
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+            for _ in range(min(args.warmup, 20)):
+                graph.replay()
+            torch.cuda.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            tg = time.perf_counter()
+            g0.record()
+            for _ in range(args.steps):
+                graph.replay()
+            g1.record()
+            torch.cuda.synchronize()
+            graph_ms = (time.perf_counter() - tg) * 1e3 / args.steps
+        del graph
     total_bytes = sum(L["bytes"] for L in layers)
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
@@ -293,7 +363,7 @@ def main():
     if not args.no_bf16 and len(chosen) == 8 and forced is None:
         bf_rows, bf_ms, bf_flops, tr_ms = [], 0.0, 0.0, 0.0
         for i, s in enumerate(synth.RESNET50_SUITE(64)):
-            x, w, b = synth.conv_inputs(s, seed=300 + i, dist="normal", bias=True)
+            x, w, b = synth.conv_inputs(s, seed=200 + i, dist="normal", bias=True)
             Pq, Qq = synth.out_hw(s)
             xb = torch.from_numpy(synth.to_bf16_bits(x).view(np.int16)).cuda()
             wb = torch.from_numpy(synth.to_bf16_bits(w).view(np.int16)).cuda()
@@ -306,7 +376,16 @@ def main():
             fn()
             ms = time_calls(torch, fn, 20)
             fl = conv_flops(s, Pq, Qq)
-            bf_rows.append(dict(layer=i, us=round(ms * 1e3, 2), tflops=round(fl / (ms * 1e-3) / 1e12, 2),
+            # compulsory traffic with 2-byte operands (blocked tensors as they lie: channels padded to
+            # eight) and the fp32 output; the layer's ceiling is the lower of the two rooflines
+            by = 2.0 * (x8.numel() + w8.numel()) + 4.0 * (s.N * s.K * Pq * Qq + s.K)
+            tfl = fl / (ms * 1e-3) / 1e12
+            ceil_tf = min(BF16_MFMA_PEAK_TFLOPS, fl / by * HBM_PEAK_GBS / 1e3)
+            bf_rows.append(dict(layer=i, us=round(ms * 1e3, 2), tflops=round(tfl, 2),
+                                frac_mfma=round(tfl / BF16_MFMA_PEAK_TFLOPS, 4),
+                                gbs=round(by / (ms * 1e-3) / 1e9, 1), ceiling_tflops=round(ceil_tf, 1),
+                                bound="mfma" if ceil_tf >= BF16_MFMA_PEAK_TFLOPS else "hbm",
+                                frac_roofline=round(tfl / ceil_tf, 4),
                                 layout_us=round(t_tr * 1e3, 2), tile=P.get_last_tile().as_dict()))
             if args.sweep:
                 shape = tuple(s)[1:]
@@ -336,7 +415,13 @@ def main():
             bf_flops += fl
             del xb, wb, x8, w8, out
         tf = bf_flops / (bf_ms * 1e-3) / 1e12
-        bf = dict(workload="configs[4]: the same eight layers, bf16 inputs in NCHW8c / KCRS8c, fp32 accumulate "
+        ideal_ms = sum(conv_flops(s, *synth.out_hw(s)) / (r["ceiling_tflops"] * 1e12) * 1e3
+                       for s, r in zip(synth.RESNET50_SUITE(64), bf_rows))
+        bf = dict(roofline={"bound": "min(bf16 mfma, hbm) per layer", "achieved": round(tf, 2),
+                            "peak": round(bf_flops / (ideal_ms * 1e-3) / 1e12, 1), "unit": "TFLOP/s",
+                            "frac": round(ideal_ms / bf_ms, 4),
+                            "note": "peak = suite flops / sum over layers of flops / min(2500 TFLOP/s, AI * 8 TB/s)"},
+                  workload="configs[4]: the same eight layers, bf16 inputs in NCHW8c / KCRS8c, fp32 accumulate "
                            "and output, N=64, bias+ReLU fused",
                   tflops=round(tf, 2), frac_of_bf16_mfma_peak=round(tf / BF16_MFMA_PEAK_TFLOPS, 4),
                   us_per_pass=round(bf_ms * 1e3, 1), layout_transform_us_per_pass=round(tr_ms * 1e3, 1),
@@ -347,7 +432,7 @@ def main():
     fusion = None
     if not args.no_fusion and forced is None:
         s = synth.CONFIG4
-        x, w, b = synth.conv_inputs(s, seed=400, dist="normal", bias=True)
+        x, w, b = synth.conv_inputs(s, seed=300, dist="normal", bias=True)
         Pq, Qq = synth.out_hw(s)
         dx, dw, db = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
         out = torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda")
@@ -371,6 +456,11 @@ def main():
                       fused_us=round(t_f * 1e3, 2), separate_us=round(t_s * 1e3, 2), conv_only_us=round(t_c * 1e3, 2),
                       speedup=round(t_s / t_f, 3),
                       output_bytes=ob, algorithmic_bytes_saved=4 * ob,
+                      measured_bytes_saved=(FUSION_TRAFFIC["separate_bytes"] - FUSION_TRAFFIC["fused_bytes"]
+                                            if FUSION_TRAFFIC["csrc_sha256"] == csrc_digest() else None),
+                      measured_bytes=({"fused": FUSION_TRAFFIC["fused_bytes"], "separate": FUSION_TRAFFIC["separate_bytes"],
+                                       "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/config4_fusion_bytes.md"}
+                                      if FUSION_TRAFFIC["csrc_sha256"] == csrc_digest() else None),
                       note="the two extra kernels each read and write the whole output once: four passes "
                            "over it that the fused epilogue never makes")
         # the element-wise operator BEFORE the convolution: fused into the operand staging against a
@@ -476,6 +566,41 @@ def main():
                    layers=lay_rows)
         del big, big_b, big_r
 
+    # config 1: one small convolution (N = 1): a latency case (1.5 us of matrix-core work), with the oracle
+    # beside it on one thread and on all of them
+    cfg1 = None
+    if not args.no_fusion and forced is None:
+        s = synth.CONFIG1
+        x, w, _ = synth.conv_inputs(s, seed=0, dist="uniform")
+        Pq, Qq = synth.out_hw(s)
+        dx, dw = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        out = torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda")
+        fn = lambda: P.conv2d_fwd(dx, dw, None, out=out, stride=s.stride, pad=s.pad, act=None)
+        fn()
+        ms = time_calls(torch, fn, 200)
+        fl = conv_flops(s, Pq, Qq)
+        cfg1 = dict(workload="configs[0]: N=1 C=K=64 56x56 3x3 s1 p1, no bias, U[-1,1), seed 0",
+                    us=round(ms * 1e3, 2), tflops=round(fl / (ms * 1e-3) / 1e12, 2),
+                    frac_mfma=round(fl / (ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS, 4),
+                    mfma_time_at_peak_us=round(fl / (FP32_MFMA_PEAK_TFLOPS * 1e12) * 1e6, 2),
+                    tile=P.get_last_tile().as_dict())
+        if not args.no_cpu:
+            import ctypes
+            import oracle
+            omp = ctypes.CDLL("libgomp.so.1")
+            all_threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+            for label, nt in (("oracle_1_thread_ms", 1), ("oracle_all_threads_ms", all_threads)):
+                omp.omp_set_num_threads(nt)
+                oracle.conv2d_fwd(x, w, stride=s.stride, pad=s.pad)
+                t = time.perf_counter()
+                reps = 3 if nt == 1 else 20
+                for _ in range(reps):
+                    oracle.conv2d_fwd(x, w, stride=s.stride, pad=s.pad)
+                cfg1[label] = round((time.perf_counter() - t) / reps * 1e3, 3)
+            omp.omp_set_num_threads(all_threads)
+            cfg1["oracle_threads"] = all_threads
+        del dx, dw, out
+
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -507,10 +632,13 @@ def main():
         "config": {"workload": "configs[2]: ResNet-50-shaped conv suite, fp32 NCHW, N=%d, layers %s, "
                                "in N(0,1), wt N(0,2/(CRS)), bias U[-0.1,0.1), ReLU"
                                % (args.batch, "0-7 (all eight)" if len(chosen) == 8 else str(chosen)),
-                   "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4)},
+                   "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4),
+                   "clock_warm_ms": args.clock_warm_ms},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
                      "traffic_unit": "bytes per suite pass (L2 fetch + write-back); algorithmic: %d" % total_bytes,
+                     "traffic_source": "not measured in this run: counters of an earlier rocprofv3 --pmc run of the "
+                                       "same kernel sources (digest checked), null when the sources have changed",
                      "kernel": "polydl::conv_kernel / polydl::conv_patch_kernel as picked per layer (all 8 "
                                "layers, nominal 2*N*K*P*Q*C*R*S flops / sum of per-layer mean launch durations)"},
         "cpu_baseline": cpu,
@@ -518,9 +646,12 @@ def main():
         "sgemm": sg,
         "bf16": bf,
         "fusion": fusion,
+        "config1": cfg1,
         "bnorm_relu": bn,
         "layouts": lay,
         "event_ms_per_step": round(e0.elapsed_time(e1) / args.steps, 4),
+        "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 4),
+        "value_graph": None if graph_ms is None else round(total_flops / (graph_ms * 1e-3) / 1e12, 3),
     }
     if args.sweep and args.sweep_out:
         with open(args.sweep_out, "w") as f:
