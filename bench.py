@@ -89,6 +89,9 @@ def main():
                          "fused call and the three separate kernels of config 4, 'bf16' = the bf16 suite")
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--sweep", action="store_true", help="also time every compiled variant per layer")
+    ap.add_argument("--suite", default="resnet", choices=["resnet", "heldout", "heldout2"],
+                    help="'heldout', 'heldout2': two sets of fourteen other CNN layer shapes (pick quality off the "
+                         "fitting set; not the headline workload)")
     ap.add_argument("--sweep-out", default="", help="with --sweep: write every candidate's time to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-sgemm", action="store_true")
@@ -153,7 +156,10 @@ def main():
         print(json.dumps({"counter_pass": "bf16"}))
         return
 
-    suite = synth.RESNET50_SUITE(args.batch)
+    suite = (synth.RESNET50_SUITE(args.batch) if args.suite == "resnet"
+             else synth.HELDOUT_SUITE(args.batch, 1 if args.suite == "heldout" else 2))
+    if args.suite != "resnet":
+        args.no_bf16 = args.no_fusion = args.no_sgemm = True
     chosen = [int(t) for t in args.layers.split(",") if t != ""] or list(range(len(suite)))
     forced = None
     if args.tile:
@@ -273,8 +279,10 @@ def main():
                     vms = time_calls(torch, lambda L=L: run_layer(L), 8, batches=3)
                 except P.PolydlError:
                     continue
-                pred = P.model_conv2d(shape, v).predicted_us
-                cands.append(dict(us=round(vms * 1e3, 2), pred_us=round(pred, 2), cfg=v.as_dict()))
+                rep = P.model_conv2d(shape, v)
+                cands.append(dict(us=round(vms * 1e3, 2), pred_us=round(rep.predicted_us, 2),
+                                  data_us=round(rep.mem_us, 3), mfma_us=round(rep.mfma_us, 3),
+                                  eq1_cost=rep.eq1_cost, cfg=v.as_dict()))
             t_sweep = time.perf_counter() - t_sweep
             P.set_tile_override(forced)
             cands.sort(key=lambda c: c["us"])
@@ -282,6 +290,14 @@ def main():
             t_pick = time.perf_counter()
             pcfg, prep = P.pick_conv2d(shape)
             t_pick = time.perf_counter() - t_pick
+            # ablation: what each part of the model would have picked alone, on the same timings --
+            # equation (1) over the placed working sets; the data term (equation (1) weighted by the
+            # bytes that move); the matrix-core term
+            alone = {}
+            for key in ("eq1_cost", "data_us", "mfma_us"):
+                c0 = min(cands, key=lambda c: (c[key], c["pred_us"]))
+                alone[key + "_alone_over_best"] = round(best["us"] / c0["us"], 4)
+            rows[-1].update(alone)
             rows[-1].update(sweep_best_us=best["us"], sweep_best_tile=best["cfg"],
                             pick_over_best=round(best["us"] / (ms * 1e3), 4), candidates=len(cands),
                             predicted_us=round(prep.predicted_us, 2), pick_seconds=round(t_pick, 5),
@@ -622,6 +638,7 @@ def main():
 
     traffic = None
     if (HBM_TRAFFIC["csrc_sha256"] == csrc_digest() and args.batch == HBM_TRAFFIC["batch"] and len(chosen) == 8
+            and args.suite == "resnet"
             and forced is None):
         traffic = HBM_TRAFFIC["fetch_bytes"] + HBM_TRAFFIC["write_bytes"]
     result = {
@@ -629,9 +646,12 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "configs[2]: ResNet-50-shaped conv suite, fp32 NCHW, N=%d, layers %s, "
-                               "in N(0,1), wt N(0,2/(CRS)), bias U[-0.1,0.1), ReLU"
-                               % (args.batch, "0-7 (all eight)" if len(chosen) == 8 else str(chosen)),
+        "config": {"workload": ("configs[2]: ResNet-50-shaped conv suite, fp32 NCHW, N=%d, layers %s, "
+                                "in N(0,1), wt N(0,2/(CRS)), bias U[-0.1,0.1), ReLU"
+                                % (args.batch, "0-7 (all eight)" if len(chosen) == 8 else str(chosen)))
+                               if args.suite == "resnet" else
+                               ("held-out CNN layer shapes (not the headline workload), fp32 NCHW, N=%d, layers %s"
+                                % (args.batch, str(chosen))),
                    "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4),
                    "clock_warm_ms": args.clock_warm_ms},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,

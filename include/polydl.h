@@ -216,10 +216,12 @@ int polydl_activation(int64_t count, float *y, int act, void *stream);
  * polydl_model_conv2d / polydl_model_sgemm: the model's report for one variant of one problem.
  * polydl_pick_conv2d / polydl_pick_sgemm: the variant with the lowest predicted time over the
  *   compiled family (what polydl_conv2d_fwd / polydl_sgemm use when no override is set).
- * The report holds the working sets of the variant in bytes (accumulator tile, LDS stage, one
- * column-tile step, the workgroups resident on one XCD, the whole problem), their placement in
- * (accumulator registers, LDS, L2, Infinity Cache) + memory, equation (1) over that placement,
- * and the predicted time split into its matrix-core, data and fixed parts. */
+ * The report holds the working sets of the variant's reuses in bytes (accumulator tile, LDS stage,
+ * one column-tile step, the workgroups resident on one XCD, the whole problem), the level each was
+ * placed in by algorithm "Compute working set sizes w.r.t cache sizes" over (accumulator registers,
+ * LDS, L2, Infinity Cache) + memory, the per-level sums, equation (1) over them, the bytes each
+ * reuse moves, and the predicted time split into its matrix-core, data and fixed parts.  The data
+ * part charges every reuse's bytes at the rate of the level its working set was placed in. */
 typedef struct polydl_model_report {
     double predicted_us, mfma_us, mem_us, fixed_us;
     double ws[8];
@@ -229,7 +231,18 @@ typedef struct polydl_model_report {
     double eq1_cost;
     int workgroups;
     double simd_load;   /* waves the busiest SIMD has to run one after another */
+    int ws_level[8];    /* per working set: the level algorithm 2 placed it in (0 .. 3, 4 = memory) */
+    double ws_traffic[8]; /* per working set: bytes that move because of that reuse over the whole launch */
 } polydl_model_report;
+
+/* The memory hierarchy the model places working sets in: four levels, fastest first (accumulator
+ * registers of a wave, LDS share of a workgroup, one XCD's L2, Infinity Cache), each with a capacity
+ * in bytes and the rate in GB/s the whole chip sustains from it (1 / rate is the level's weight in
+ * equation (1)), then memory's rate.  polydl_model_get_levels reads the table; polydl_model_set_levels
+ * replaces it for every later model and pick of the process (capacities > 0 and ascending, rates > 0;
+ * POLYDL_ERR_BAD_DIMENSION otherwise) and drops the picks cached so far.  Host pointers, 4 doubles each. */
+int polydl_model_get_levels(double *capacity_bytes, double *gbytes_per_s, double *mem_gbytes_per_s);
+int polydl_model_set_levels(const double *capacity_bytes, const double *gbytes_per_s, double mem_gbytes_per_s);
 
 /* polydl_reuse_analyse: algorithm "Compute working set sizes" (section "Working set size
  * computation") on a small perfect loop nest, by enumerating its iterations (no polyhedral

@@ -7,7 +7,7 @@ library has not been built, importing this package raises.
 from .binding import (lib, PolydlError, TileCfg, ACT, conv2d_fwd, conv2d_fwd_noalloc, sgemm, set_tile_override,
                       get_last_tile, variants, status_string, LIB_PATH, nchw_to_nchwc,
                       nchwc_to_nchw, kcrs_to_kcrsck, bias_add, activation, ModelReport,
-                      reuse_bucket, reuse_cost, model_conv2d, model_sgemm, pick_conv2d, pick_sgemm,
+                      reuse_bucket, reuse_cost, model_get_levels, model_set_levels, model_conv2d, model_sgemm, pick_conv2d, pick_sgemm,
                       conv_candidates, nchw_to_nchwc_bf16, kcrs_to_kcrsck_bf16, conv2d_fwd_bf16_blocked,
                       conv2d_fwd_bf16, bnorm_fwd, model_conv2d_bf16, pick_conv2d_bf16,
                       conv_candidates_bf16, sgemm_candidates, ranker_num_params, ranker_set_params,
@@ -17,7 +17,7 @@ from .binding import (lib, PolydlError, TileCfg, ACT, conv2d_fwd, conv2d_fwd_noa
 __all__ = ["lib", "PolydlError", "TileCfg", "ACT", "conv2d_fwd", "conv2d_fwd_noalloc", "sgemm", "set_tile_override",
            "get_last_tile", "variants", "status_string", "LIB_PATH", "nchw_to_nchwc", "nchwc_to_nchw",
            "kcrs_to_kcrsck", "bias_add", "activation", "ModelReport", "reuse_bucket", "reuse_cost",
-           "model_conv2d", "model_sgemm", "pick_conv2d", "pick_sgemm", "conv_candidates",
+           "model_get_levels", "model_set_levels", "model_conv2d", "model_sgemm", "pick_conv2d", "pick_sgemm", "conv_candidates",
            "nchw_to_nchwc_bf16", "kcrs_to_kcrsck_bf16", "conv2d_fwd_bf16_blocked", "conv2d_fwd_bf16", "bnorm_fwd",
            "model_conv2d_bf16", "pick_conv2d_bf16", "conv_candidates_bf16", "sgemm_candidates",
            "ranker_num_params", "ranker_set_params", "ranker_load", "ranker_stats_conv2d", "ranker_play",

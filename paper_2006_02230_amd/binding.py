@@ -46,13 +46,15 @@ class ModelReport(ctypes.Structure):
     _fields_ = [("predicted_us", ctypes.c_double), ("mfma_us", ctypes.c_double), ("mem_us", ctypes.c_double),
                 ("fixed_us", ctypes.c_double), ("ws", ctypes.c_double * 8), ("n_ws", ctypes.c_int),
                 ("level_bytes", ctypes.c_double * 4), ("mem_bytes", ctypes.c_double),
-                ("eq1_cost", ctypes.c_double), ("workgroups", ctypes.c_int), ("simd_load", ctypes.c_double)]
+                ("eq1_cost", ctypes.c_double), ("workgroups", ctypes.c_int), ("simd_load", ctypes.c_double),
+                ("ws_level", ctypes.c_int * 8), ("ws_traffic", ctypes.c_double * 8)]
 
     def as_dict(self):
         return {"predicted_us": self.predicted_us, "mfma_us": self.mfma_us, "mem_us": self.mem_us,
                 "fixed_us": self.fixed_us, "ws": list(self.ws)[:self.n_ws], "level_bytes": list(self.level_bytes),
                 "mem_bytes": self.mem_bytes, "eq1_cost": self.eq1_cost, "workgroups": self.workgroups,
-                "simd_load": self.simd_load}
+                "simd_load": self.simd_load, "ws_level": list(self.ws_level)[:self.n_ws],
+                "ws_traffic": list(self.ws_traffic)[:self.n_ws]}
 
 
 _i, _p = ctypes.c_int, ctypes.c_void_p
@@ -342,6 +344,25 @@ def reuse_cost(levels, mem, weights, mem_weight):
     m = len(levels)
     return lib.polydl_reuse_cost(m, (ctypes.c_double * max(m, 1))(*levels), mem,
                                  (ctypes.c_double * max(m, 1))(*weights), mem_weight)
+
+
+lib.polydl_model_get_levels.argtypes = [_pd, _pd, _pd]
+lib.polydl_model_set_levels.argtypes = [_pd, _pd, _d]
+lib.polydl_model_get_levels.restype = _i
+lib.polydl_model_set_levels.restype = _i
+
+
+def model_get_levels():
+    """polydl_model_get_levels: (capacities in bytes, rates in GB/s, memory rate in GB/s)."""
+    cap, rate, mem = (ctypes.c_double * 4)(), (ctypes.c_double * 4)(), ctypes.c_double()
+    _check(lib.polydl_model_get_levels(cap, rate, ctypes.byref(mem)), "polydl_model_get_levels")
+    return list(cap), list(rate), mem.value
+
+
+def model_set_levels(capacity, rate, mem_rate):
+    """polydl_model_set_levels: replace the model's memory-hierarchy table (process-wide)."""
+    _check(lib.polydl_model_set_levels((ctypes.c_double * 4)(*capacity), (ctypes.c_double * 4)(*rate), mem_rate),
+           "polydl_model_set_levels")
 
 
 def model_conv2d(shape, cfg):

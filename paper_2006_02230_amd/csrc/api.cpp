@@ -83,6 +83,15 @@ static const Variant *find_variant(const polydl_tile_cfg &c)
     return nullptr;
 }
 
+static const PatchVariant *find_patch_bf16_variant(const polydl_tile_cfg &c)
+{
+    for (int i = 0; i < kNumPatchBf16Variants; ++i) {
+        const PatchVariant &v = kPatchBf16Variants[i];
+        if (v.bm == c.bm && v.bn == c.bn && v.wm == c.wm && v.wn == c.wn) return &v;
+    }
+    return nullptr;
+}
+
 static const PatchVariant *find_patch_variant(const polydl_tile_cfg &c)
 {
     for (int i = 0; i < kNumPatchVariants; ++i) {
@@ -441,11 +450,7 @@ int polydl_conv2d_fwd_bf16_blocked(int N, int C, int H, int W, int K, int R, int
             g_bf16_plans[key] = cfg;
         }
     }
-    const PatchVariant *pv = nullptr;
-    for (int i = 0; i < kNumPatchBf16Variants; ++i) {
-        const PatchVariant &v = kPatchBf16Variants[i];
-        if (v.bm == cfg.bm && v.bn == cfg.bn && v.wm == cfg.wm && v.wn == cfg.wn) pv = &v;
-    }
+    const PatchVariant *pv = find_patch_bf16_variant(cfg);
     if (!pv) return POLYDL_ERR_UNSUPPORTED;
     if (cfg.cb == 0) {
         for (int cb = 2; cb <= ((cunits + 1) & ~1) && cb <= 32; cb += 2)
@@ -566,6 +571,28 @@ static int threads_of(const polydl_tile_cfg &c)
 {
     if (c.wm <= 0 || c.wn <= 0 || c.bm % c.wm || c.bn % c.wn) return 0;
     return (c.bm / c.wm) * (c.bn / c.wn) * 64;
+}
+
+int polydl_model_get_levels(double *capacity_bytes, double *gbytes_per_s, double *mem_gbytes_per_s)
+{
+    if (!capacity_bytes || !gbytes_per_s || !mem_gbytes_per_s) return POLYDL_ERR_NULL_POINTER;
+    model_get_levels(capacity_bytes, gbytes_per_s, mem_gbytes_per_s);
+    return POLYDL_OK;
+}
+
+int polydl_model_set_levels(const double *capacity_bytes, const double *gbytes_per_s, double mem_gbytes_per_s)
+{
+    if (!capacity_bytes || !gbytes_per_s) return POLYDL_ERR_NULL_POINTER;
+    if (!(mem_gbytes_per_s > 0)) return POLYDL_ERR_BAD_DIMENSION;
+    for (int i = 0; i < 4; ++i)
+        if (!(capacity_bytes[i] > 0) || !(gbytes_per_s[i] > 0) || (i > 0 && !(capacity_bytes[i] >= capacity_bytes[i - 1])))
+            return POLYDL_ERR_BAD_DIMENSION;
+    std::lock_guard<std::mutex> lk(g_mu);
+    model_set_levels(capacity_bytes, gbytes_per_s, mem_gbytes_per_s);
+    g_conv_plans.clear();      // picks made with the old table
+    g_sgemm_plans.clear();
+    g_bf16_plans.clear();
+    return POLYDL_OK;
 }
 
 int polydl_model_conv2d(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -789,7 +816,8 @@ int polydl_set_tile_override(const polydl_tile_cfg *cfg)
         return POLYDL_OK;
     }
     const bool known = cfg->algo == 2 ? is_conv_point_cfg(*cfg)
-                                      : (cfg->algo == 1 ? find_patch_variant(*cfg) != nullptr
+                                      : (cfg->algo == 1 ? (find_patch_variant(*cfg) != nullptr ||
+                                                           find_patch_bf16_variant(*cfg) != nullptr)
                                                         : (cfg->algo == 0 && find_variant(*cfg) != nullptr));
     if (!known || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
         cfg->raster > 2 || (cfg->raster == 2 && cfg->algo != 0) || cfg->cb < 0 || (cfg->cb & 1))

@@ -140,6 +140,8 @@ inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, siz
 // picker.cpp
 void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem);
 double reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight);
+void model_get_levels(double *capacity, double *gbytes_per_s, double *mem_gbytes_per_s);   // 4 levels + memory
+void model_set_levels(const double *capacity, const double *gbytes_per_s, double mem_gbytes_per_s);
 void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, int reg_class, polydl_model_report *r);
 void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads, polydl_model_report *r);
 double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads);   // predicted microseconds

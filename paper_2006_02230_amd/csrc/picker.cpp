@@ -33,33 +33,52 @@ struct Level {
     double capacity;      // bytes available to one reuse scope at this level
     double gbytes_per_s;  // aggregate rate the whole chip sustains from this level
 };
-static const Level kLevels[4] = {
+static Level kLevels[4] = {
     {"acc", 64.0 * 1024, 1e9},              // accumulator registers of one wave (256 regs x 64 lanes)
     {"lds", 80.0 * 1024, 60000.0},          // half of a CU's 160 KB: two workgroups share a CU
     {"l2", 4.0 * 1024 * 1024, 16000.0},     // one XCD's L2
     {"mall", 256.0 * 1024 * 1024, 8000.0},  // Infinity Cache
 };
-static const double kHbmGBs = 4500.0;       // sustained mixed read/write HBM rate
+static double kHbmGBs = 4500.0;             // sustained mixed read/write HBM rate
+
+void model_get_levels(double *capacity, double *gbytes_per_s, double *mem_gbytes_per_s)
+{
+    for (int i = 0; i < 4; ++i) { capacity[i] = kLevels[i].capacity; gbytes_per_s[i] = kLevels[i].gbytes_per_s; }
+    *mem_gbytes_per_s = kHbmGBs;
+}
+void model_set_levels(const double *capacity, const double *gbytes_per_s, double mem_gbytes_per_s)
+{
+    for (int i = 0; i < 4; ++i) { kLevels[i].capacity = capacity[i]; kLevels[i].gbytes_per_s = gbytes_per_s[i]; }
+    kHbmGBs = mem_gbytes_per_s;
+}
 static const double kClockHz = 2.4e9;
 static const int kSimdsPerCU = 4, kXcds = 8;
 // compute units of the current device (256 on an MI355X; also the answer when no device is visible)
 #define kCUs (compute_units())
 
-void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem)
+// Algorithm "Compute working set sizes w.r.t cache sizes".  placed (may be null) receives, per
+// working set in the caller's order, the level it went to (nlevels = memory).
+static void bucket_placed(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem,
+                          int *placed)
 {
-    std::vector<double> sorted(ws, ws + n);
-    std::sort(sorted.begin(), sorted.end());
+    std::vector<int> order(n);
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ws[a] < ws[b]; });
     for (int i = 0; i < nlevels; ++i) levels[i] = 0;
     *mem = 0;
-    for (double w : sorted) {
-        bool placed = false;
-        for (int i = 0; i < nlevels && !placed; ++i)
-            if (w + levels[i] <= sizes[i]) {
-                levels[i] += w;
-                placed = true;
-            }
-        if (!placed) *mem += w;
+    for (int idx : order) {
+        int at = nlevels;
+        for (int i = 0; i < nlevels && at == nlevels; ++i)
+            if (ws[idx] + levels[i] <= sizes[i]) at = i;
+        if (at < nlevels) levels[at] += ws[idx];
+        else *mem += ws[idx];
+        if (placed) placed[idx] = at;
     }
+}
+
+void reuse_bucket(int n, const double *ws, int nlevels, const double *sizes, double *levels, double *mem)
+{
+    bucket_placed(n, ws, nlevels, sizes, levels, mem, nullptr);
 }
 
 double reuse_cost(int nlevels, const double *levels, double mem, const double *weights, double mem_weight)
@@ -69,13 +88,6 @@ double reuse_cost(int nlevels, const double *levels, double mem, const double *w
     return c;
 }
 
-// level index (0..3) a working set of `bytes` is served from when placed alone, 4 = memory
-static int level_of(double bytes)
-{
-    for (int i = 0; i < 4; ++i)
-        if (bytes <= kLevels[i].capacity) return i;
-    return 4;
-}
 static double rate_of(int level) { return level < 4 ? kLevels[level].gbytes_per_s : kHbmGBs; }
 
 struct Shape {   // the GEMM a candidate works on
@@ -169,39 +181,50 @@ static void model(const Shape &s, const Cand &c, polydl_model_report *r)
         auto round_us = [&](double n) { return c.t_round_us + stages * std::max(n * t_stage, c.t_lat_us); };
         mfma_us = full_rounds * round_us(occ) + (rest > 1e-9 ? round_us(std::ceil(rest - 1e-9)) : 0.0) + tail_us;
     }
-    // ---- working sets (bytes) and where algorithm 2 places them -------------------------------
-    const double ws_acc = (double)c.wm * c.wn * 4;                         // accumulators over the reduction
-    const double ws_stage = c.lds_bytes;                                   // staged operands, shared by the waves
+    // ---- the reuses of the nest: working set (bytes) and the bytes that travel because of it ----
+    // Algorithm 2 places the working sets, smallest first, each in the fastest level that still
+    // has room beside those already there; a reuse whose working set was placed in level L is
+    // served from L, so its traffic is charged at L's rate: equation (1) with each level's term
+    // weighted by the bytes that actually move instead of by the working-set size alone.
+    enum { R_ACC = 0, R_STAGE, R_COL_STEP, R_PAR, R_ALL, N_REUSE };
     const double a_panel = c.bm * s.Kg * 4;                                // A row panel between two column tiles
-    const double ws_col_step = a_panel + s.b_tile_bytes + (double)c.bm * c.bn * 4;
     // reuse across workgroups that run together on one XCD (the dependence spans the parallel
     // loop): the footprint of everything resident there
     const double res_wgs = std::min(wgs, (double)kCUs / kXcds * std::max(1.0, resident * kSimdsPerCU / waves_per_wg));
     const double dm = std::min(tiles_m, res_wgs), dn = std::max(1.0, std::ceil(res_wgs / tiles_m));
-    const double ws_par = dm * a_panel + dn * s.b_tile_bytes;
-    const double ws_all = s.a_bytes + s.b_bytes + s.d_bytes;
-    const double ws[5] = {ws_acc, ws_stage, ws_col_step, ws_par, ws_all};
-    double sizes[4];
-    for (int i = 0; i < 4; ++i) sizes[i] = kLevels[i].capacity;
-    reuse_bucket(5, ws, 4, sizes, r->level_bytes, &r->mem_bytes);
-    double weights[4];
-    for (int i = 0; i < 4; ++i) weights[i] = 1.0 / kLevels[i].gbytes_per_s;
-    r->eq1_cost = reuse_cost(4, r->level_bytes, r->mem_bytes, weights, 1.0 / kHbmGBs);
-    r->n_ws = 5;
-    for (int i = 0; i < 5; ++i) r->ws[i] = ws[i];
-    // ---- data term: bytes that travel, charged at the level their reuse is served from -------
-    // A is fetched once per column tile, B once per row tile; each from the level that holds the
-    // footprint of the workgroups running together, else from where the whole tensor fits
+    double ws[N_REUSE], traffic[N_REUSE];
+    ws[R_ACC] = (double)c.wm * c.wn * 4;                                   // accumulators over the reduction
+    ws[R_STAGE] = c.lds_bytes;                                             // staged operands, shared by the waves
+    ws[R_COL_STEP] = a_panel + s.b_tile_bytes + (double)c.bm * c.bn * 4;   // one column-tile step: A panel reused by the next
+    ws[R_PAR] = dm * a_panel + dn * s.b_tile_bytes;                        // B tile (and A panels) shared by concurrent tiles
+    ws[R_ALL] = s.a_bytes + s.b_bytes + s.d_bytes;                         // the tensors themselves
+    // A is fetched once per column tile, B once per row tile; the accumulators never leave the
+    // registers; every staged element is read from LDS once per wave that multiplies it
     const double a_traffic = tiles_n * s.a_bytes, b_traffic = tiles_m * tiles_n * s.b_tile_bytes;
-    const int shared_level = std::max(2, level_of(ws_par));
-    const int a_level = std::min(shared_level, std::max(2, level_of(s.a_bytes)));
-    const int b_level = std::min(shared_level, std::max(2, level_of(s.b_bytes)));
-    double mem_us = 0;
-    double refetch_us = (a_traffic - s.a_bytes) / rate_of(a_level) * 1e-3;           // re-fetches
-    refetch_us += (b_traffic > s.b_bytes ? b_traffic - s.b_bytes : 0) / rate_of(b_level) * 1e-3;
-    mem_us += (s.a_bytes + s.b_bytes + s.d_bytes) / kHbmGBs * 1e-3;        // compulsory
+    traffic[R_ACC] = 0;
+    traffic[R_STAGE] = tiles_m * tiles_n * s.Kg * ((double)c.bm * (c.bn / c.wn) + (double)c.bn * (c.bm / c.wm)) * 4;
+    traffic[R_COL_STEP] = a_traffic - s.a_bytes;
+    traffic[R_PAR] = b_traffic > s.b_bytes ? b_traffic - s.b_bytes : 0;
+    traffic[R_ALL] = s.a_bytes + s.b_bytes + s.d_bytes;
+    double sizes[4], weights[4];
+    for (int i = 0; i < 4; ++i) { sizes[i] = kLevels[i].capacity; weights[i] = 1.0 / kLevels[i].gbytes_per_s; }
+    int placed[N_REUSE];
+    bucket_placed(N_REUSE, ws, 4, sizes, r->level_bytes, &r->mem_bytes, placed);
+    r->eq1_cost = reuse_cost(4, r->level_bytes, r->mem_bytes, weights, 1.0 / kHbmGBs);
+    r->n_ws = N_REUSE;
+    for (int i = 0; i < N_REUSE; ++i) { r->ws[i] = ws[i]; r->ws_level[i] = placed[i]; r->ws_traffic[i] = traffic[i]; }
+    // ---- data term ------------------------------------------------------------------------------
+    // Nothing faster than L2 is shared between workgroups, and nothing faster than the Infinity
+    // Cache holds a tensor from one launch to the next: reuses across workgroups are served from
+    // their placed level or L2, whichever is slower; the tensors from theirs or the Infinity Cache.
+    const int a_level = std::max(2, placed[R_COL_STEP]), b_level = std::max(2, placed[R_PAR]);
+    const int all_level = std::max(3, placed[R_ALL]);
+    const double refetch_us = traffic[R_COL_STEP] / rate_of(a_level) * 1e-3 + traffic[R_PAR] / rate_of(b_level) * 1e-3;
+    const double lds_us = traffic[R_STAGE] / rate_of(std::max(1, placed[R_STAGE])) * 1e-3;
+    double mem_us = traffic[R_ALL] / rate_of(all_level) * 1e-3;            // compulsory
     if (c.rounds) mem_us = std::max(mem_us, refetch_us);                   // caches and memory work side by side
     else mem_us += refetch_us;
+    mem_us = std::max(mem_us, lds_us);
     double fixed = c.kernel_fixed_us;
     if (c.rounds) {
         // nothing streams the tensors faster than this, with the first and last touches exposed
@@ -307,7 +330,7 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         c.kernel_fixed_us = 5.0;
         c.gather_elems = (double)cfg.bk * cfg.bn / threads;
         switch (mbn) {
-        case 11: c.regs = 62;  c.eff_sat = 0.70; c.t_lat_us = 0.6; c.t_round_us = 2; c.gather_cycles = 0;  break;
+        case 11: c.regs = 62;  c.eff_sat = 0.85; c.t_lat_us = 0.6; c.t_round_us = 2; c.gather_cycles = 32; break;
         case 12: c.regs = 90;  c.eff_sat = 0.80; c.t_lat_us = 1.0; c.t_round_us = 4; c.gather_cycles = 20; c.split_c0 = 2; break;
         case 21: c.regs = 88;  c.eff_sat = 0.90; c.t_lat_us = 0.8; c.t_round_us = 4; c.gather_cycles = 40; break;
         case 22: c.regs = cfg.bk == 16 ? 136 : 104; c.eff_sat = 0.80; c.t_lat_us = 0.8; c.t_round_us = 2; c.gather_cycles = 40;
@@ -316,7 +339,10 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         default: c.regs = 228; c.eff_sat = 0.80; c.t_lat_us = 0.4; c.t_round_us = 4; c.gather_cycles = 20; c.split_c0 = 15; c.split_c1 = 1.0; break;
         }
         c.tail_split = cfg.raster == 2;
-        if (point) c.gather_cycles *= 0.1;
+        // 1x1 filters without padding: the channel rides in the instruction's uniform offset and the
+        // lanes read a contiguous run of pixels (stride 1); with a stride the lanes' addresses are
+        // spread over several times the cache lines and the loads cost what gathered ones do
+        if (point && q.stride == 1) c.gather_cycles *= 0.1;
         if (c.split_c1 == 0) c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
     }
     Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
@@ -418,15 +444,17 @@ void model_conv_point(const ConvProblem &q, polydl_model_report *r)
     r->predicted_us = std::max(r->mfma_us, r->mem_us) + r->fixed_us;
     r->workgroups = (int)wgs;
     r->simd_load = per_simd;
-    // working sets: accumulators of a unit; the pixel registers reused by the channel groups; the
-    // filter in LDS reused by every unit; the whole problem
+    // reuses: accumulators of a unit (registers); the pixel registers reused by the channel groups;
+    // the filter in LDS reused by every unit (read once per unit); the tensors themselves
     const double ws[4] = {32.0 * 64 * 4, 64.0 * q.C * 4, wt_bytes, in_bytes + out_bytes + wt_bytes};
+    const double moved[4] = {0, 0, (double)units * 32.0 * q.C * 4, in_bytes + out_bytes + wt_bytes};
     double sizes[4], weights[4];
     for (int i = 0; i < 4; ++i) { sizes[i] = kLevels[i].capacity; weights[i] = 1.0 / kLevels[i].gbytes_per_s; }
-    reuse_bucket(4, ws, 4, sizes, r->level_bytes, &r->mem_bytes);
+    int placed[4];
+    bucket_placed(4, ws, 4, sizes, r->level_bytes, &r->mem_bytes, placed);
     r->eq1_cost = reuse_cost(4, r->level_bytes, r->mem_bytes, weights, 1.0 / kHbmGBs);
     r->n_ws = 4;
-    for (int i = 0; i < 4; ++i) r->ws[i] = ws[i];
+    for (int i = 0; i < 4; ++i) { r->ws[i] = ws[i]; r->ws_level[i] = placed[i]; r->ws_traffic[i] = moved[i]; }
 }
 
 void conv_candidates(const ConvProblem &q, std::vector<ConvCandidate> *out)

@@ -26,5 +26,7 @@
 #define POLYDL_PATCH_BF16_FAMILY(X) \
     X(64, 64, 0, 32, 32)            \
     X(64, 128, 0, 64, 32)           \
+    X(64, 256, 0, 64, 64)           \
     X(128, 64, 0, 64, 32)           \
-    X(128, 128, 0, 64, 64)
+    X(128, 128, 0, 64, 64)          \
+    X(128, 256, 0, 64, 64)

@@ -6,9 +6,9 @@ reuse model, and imports neither the oracle nor the HIP library.
 """
 from .rng import (uniform_pm1, normal, small_ints, to_bf16_bits, bf16_bits_to_f32,
                   splitmix64)
-from .workloads import (ConvShape, RESNET50_SUITE, CONFIG1, CONFIG4, SGEMM_SIZES,
+from .workloads import (ConvShape, RESNET50_SUITE, HELDOUT_SUITE, CONFIG1, CONFIG4, SGEMM_SIZES,
                         PAPER_GEMM_SIZES, conv_inputs, sgemm_inputs, out_hw)
 
 __all__ = ["uniform_pm1", "normal", "small_ints", "to_bf16_bits", "bf16_bits_to_f32",
-           "splitmix64", "ConvShape", "RESNET50_SUITE", "CONFIG1", "CONFIG4",
+           "splitmix64", "ConvShape", "RESNET50_SUITE", "HELDOUT_SUITE", "CONFIG1", "CONFIG4",
            "SGEMM_SIZES", "PAPER_GEMM_SIZES", "conv_inputs", "sgemm_inputs", "out_hw"]

@@ -35,6 +35,29 @@ def RESNET50_SUITE(N=32):
     return [_layer(i, N, C, K, H, R, st) for i, (C, K, H, R, st) in enumerate(_SUITE_TUPLES)]
 
 
+# Layer shapes of ResNet-50 / Inception-style networks that are NOT in the suite above: none of the
+# picker's constants was fitted on them.  (C, K, H, R, stride), pad = (R-1)/2.
+_HELDOUT_TUPLES = [(256, 64, 56, 1, 1), (128, 128, 56, 3, 2), (512, 128, 28, 1, 1), (256, 512, 28, 1, 2),
+                   (2048, 512, 7, 1, 1), (512, 2048, 7, 1, 1), (64, 192, 56, 3, 1), (96, 208, 14, 3, 1),
+                   (128, 512, 28, 1, 1), (1024, 256, 14, 1, 1), (256, 1024, 14, 1, 1), (512, 512, 14, 3, 2),
+                   (3, 32, 149, 3, 2), (48, 64, 28, 5, 1)]
+
+
+# A second set, measured once with the final picker: the first set's sweep was looked at while the
+# model's treatment of 1x1 layers was corrected, so only this one is untouched by any tuning.
+_HELDOUT2_TUPLES = [(128, 128, 28, 1, 1), (256, 256, 14, 1, 1), (512, 512, 7, 1, 1), (512, 1024, 28, 1, 2),
+                    (64, 64, 112, 3, 2), (256, 256, 28, 3, 1), (32, 64, 112, 3, 1), (160, 320, 14, 3, 1),
+                    (1024, 512, 14, 1, 1), (1024, 1024, 7, 3, 1), (16, 96, 56, 1, 1), (24, 144, 56, 1, 1),
+                    (320, 1280, 7, 1, 1), (80, 192, 35, 3, 1)]
+
+
+def HELDOUT_SUITE(N=32, which=1):
+    """Fourteen further CNN layer shapes at batch N (pick quality off the fitting set); which = 1 or 2."""
+    tuples = _HELDOUT_TUPLES if which == 1 else _HELDOUT2_TUPLES
+    return [ConvShape("heldout%d_l%d" % (which, i), N, C, H, H, K, R, R, st, (R - 1) // 2)
+            for i, (C, K, H, R, st) in enumerate(tuples)]
+
+
 CONFIG1 = ConvShape("cfg1_c64k64_56_3x3", 1, 64, 56, 56, 64, 3, 3, 1, 1)
 CONFIG4 = ConvShape("cfg4_c256k256_14_3x3_bias_relu", 32, 256, 14, 14, 256, 3, 3, 1, 1)
 SGEMM_SIZES = [256, 1024, 2048, 4096]

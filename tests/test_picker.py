@@ -166,3 +166,99 @@ def test_argument_errors():
     assert P.lib.polydl_pick_sgemm(0, 1, 1, ctypes.byref(cfg), None) == -2
     bad = P.TileCfg(17, 64, 16, 32, 32, 1, 0, 0, 0, 0)
     assert P.lib.polydl_model_sgemm(8, 8, 8, ctypes.byref(bad), ctypes.byref(rep)) == -3
+
+
+def place_by_hand(ws, sizes):
+    """Algorithm "Compute working set sizes w.r.t cache sizes", keeping where each set went."""
+    room = list(sizes)
+    where = [len(sizes)] * len(ws)
+    for i in sorted(range(len(ws)), key=lambda i: ws[i]):
+        for lv in range(len(sizes)):
+            if ws[i] <= room[lv]:
+                room[lv] -= ws[i]
+                where[i] = lv
+                break
+    return where
+
+
+@pytest.mark.parametrize("layer", range(8))
+def test_report_placement_and_data_term_follow_the_bucketing(layer):
+    # every reuse's working set is placed by the bucketing algorithm, and the data term charges the
+    # bytes each reuse moves at the rate of the level it was placed in
+    s = synth.RESNET50_SUITE(32)[layer]
+    shape = tuple(s)[1:]
+    cap, rate, mem_rate = P.model_get_levels()
+    for c in P.conv_candidates(shape):
+        if c.algo != 0:
+            continue
+        rep = P.model_conv2d(shape, c)
+        ws, lvl, moved = list(rep.ws)[:rep.n_ws], list(rep.ws_level)[:rep.n_ws], list(rep.ws_traffic)[:rep.n_ws]
+        assert lvl == place_by_hand(ws, cap)
+        olv, omem = reuse.bucket_working_sets(ws, cap)
+        assert list(rep.level_bytes) == [float(x) for x in olv] and rep.mem_bytes == float(omem)
+        r = lambda lv: rate[lv] if lv < 4 else mem_rate
+        refetch = moved[2] / r(max(2, lvl[2])) * 1e-3 + moved[3] / r(max(2, lvl[3])) * 1e-3
+        assert rep.mem_us >= refetch * (1 - 1e-12)
+        assert rep.mem_us >= moved[4] / r(max(3, lvl[4])) * 1e-3 * (1 - 1e-12)
+
+
+def test_moving_a_working_set_across_a_capacity_changes_the_data_term_and_the_ranking():
+    # a pointwise layer with a long reduction and many column tiles: the A panel of a tile row is
+    # re-fetched by every column tile.  With the real L2 (4 MB) the column-step working set of every
+    # tile fits L2; with an L2 of 2 MB the large tiles' working sets fall through to the Infinity
+    # Cache, their re-fetches are charged at its (here: much lower) rate, and the ranking changes
+    # from the largest tile to the largest one whose working set still fits.
+    shape = (8, 2048, 28, 28, 2048, 1, 1, 1, 0)
+    cap, rate, mem_rate = P.model_get_levels()
+    try:
+        slow = list(rate)
+        slow[3] = 500.0                                  # make what falls out of L2 expensive
+        P.model_set_levels(cap, slow, mem_rate)
+        before = {tuple(c.as_dict().values()): P.model_conv2d(shape, c) for c in P.conv_candidates(shape) if c.algo == 0}
+        pick_before, _ = P.pick_conv2d(shape)
+        small = list(cap)
+        small[2] = 2 << 20
+        P.model_set_levels(small, slow, mem_rate)
+        after = {tuple(c.as_dict().values()): P.model_conv2d(shape, c) for c in P.conv_candidates(shape) if c.algo == 0}
+        pick_after, _ = P.pick_conv2d(shape)
+    finally:
+        P.model_set_levels(cap, rate, mem_rate)
+    moved_out = [k for k in before if before[k].ws_level[2] == 2 and after[k].ws_level[2] == 3]
+    stayed = [k for k in before if before[k].ws_level[2] == 2 and after[k].ws_level[2] == 2]
+    assert moved_out and stayed
+    for k in moved_out:
+        assert after[k].mem_us > before[k].mem_us          # the same bytes, charged at a slower level
+    for k in stayed:
+        assert after[k].mem_us == before[k].mem_us
+    assert pick_after.as_dict() != pick_before.as_dict()
+    assert pick_before.bm * pick_before.bn > pick_after.bm * pick_after.bn
+    assert tuple(pick_before.as_dict().values()) in moved_out
+    assert after[tuple(pick_after.as_dict().values())].ws_level[2] == 2   # the new pick keeps its A panel in L2
+    # and the table is back
+    assert P.model_get_levels() == (cap, rate, mem_rate)
+
+
+def test_level_table_validation():
+    cap, rate, mem_rate = P.model_get_levels()
+    with pytest.raises(P.PolydlError):
+        P.model_set_levels([cap[1], cap[0], cap[2], cap[3]], rate, mem_rate)   # not ascending
+    with pytest.raises(P.PolydlError):
+        P.model_set_levels(cap, [0.0] + rate[1:], mem_rate)
+    with pytest.raises(P.PolydlError):
+        P.model_set_levels(cap, rate, -1.0)
+    assert P.model_get_levels() == (cap, rate, mem_rate)
+
+
+def test_candidate_lists_come_from_the_library():
+    shape = tuple(synth.RESNET50_SUITE(32)[4])[1:]
+    cands = P.conv_candidates(shape)
+    assert len(cands) > 50 and {c.algo for c in cands} == {0, 1}
+    assert len({tuple(c.as_dict().values()) for c in cands}) == len(cands)
+    pick, _ = P.pick_conv2d(shape)
+    assert tuple(pick.as_dict().values()) in {tuple(c.as_dict().values()) for c in cands}
+    sg = P.sgemm_candidates(512, 384, 1000)
+    pick, _ = P.pick_sgemm(512, 384, 1000)
+    assert tuple(pick.as_dict().values()) in {tuple(c.as_dict().values()) for c in sg}
+    bf = P.conv_candidates_bf16(shape)
+    pick, _ = P.pick_conv2d_bf16(shape)
+    assert bf and tuple(pick.as_dict().values()) in {tuple(c.as_dict().values()) for c in bf}
