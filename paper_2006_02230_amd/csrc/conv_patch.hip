@@ -88,8 +88,10 @@ struct ConvPatchKArgs {
     float *partials;      // split_k > 1: [tile][split][BM*BN] accumulator tiles in register order
     unsigned *counters;   // split_k > 1: per tile, how many of its reduction parts have finished
     int nbuf;        // LDS stage buffers: 2, or 1 when a workgroup runs a single stage
-    int single;      // 1: the whole reduction is ONE unit (CB == 1); the upper half-wave, which
-                     // would carry the pair's second unit, multiplies by a zero kept in LDS
+    int single;      // 1: the whole reduction is ONE unit (CB == 1): the upper half-wave, which would
+                     // carry the pair's second unit, takes the NEXT TAP of the same unit instead (two taps
+                     // per matrix instruction; a last odd tap, and every tap of a filter whose size is
+                     // not known at compile time, multiplies a zero kept in LDS)
 };
 
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, uint32_t magic, uint32_t ones_if_d1)
@@ -292,7 +294,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi) a_base[bi] = (wm0 + 32 * bi + li) * p.LDA + (p.single ? 0 : lh * p.RSp);
     const int zero_unit = p.nbuf * p.b_stage;      // relative to Bs
-    const int bmul = (p.single && lh) ? 0 : 1;
+    const int bmul = (p.single && lh) ? 0 : 1;   // run-time filter sizes only, see the main loop
     if (tid == 0) {
         unit_t z = {};
         Bs[zero_unit] = z;                          // visible after the first barrier below
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             px_img[bj] = img;
             px_pq[bj] = pq;
         }
-        b_base[bj] = (p.single && lh) ? zero_unit : base + lh * chs;
+        b_base[bj] = p.single ? base : base + lh * chs;
     }
 
     v16f acc[MB][NB];
@@ -395,7 +397,42 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 
         const unit_t *A = As + buf * a_stage;
         const unit_t *B = Bs + buf * p.b_stage;
-        if constexpr (RC == 1 && SC == 1) {
+        bool done = false;   // uniform
+        if constexpr (E::BYTES == 16 && RC > 0) if (p.single) {
+            done = true;
+            // A reduction of one unit: the two halves of the matrix instruction's reduction take two
+            // TAPS of that unit -- lanes 0-31 tap t, lanes 32-63 tap t+1 -- instead of two units.  The
+            // upper half of a last odd tap multiplies the zero column behind the filter row (LDA > D)
+            // with the zero unit.
+            const int zb = zero_unit - buf * p.b_stage;   // the zero unit, relative to this stage's patch
+#pragma unroll
+            for (int t = 0; t < RC * SC; t += 2) {
+                const bool tail = t + 1 >= RC * SC;
+                const int r0 = t / SC, s0 = t % SC;
+                const int r1 = tail ? 0 : (t + 1) / SC, s1 = tail ? 0 : (t + 1) % SC;
+                const int a_off = t + lh;
+                const int b_off = lh ? r1 * p.Wp + s1 : r0 * p.Wp + s0;
+                typename E::frag_t fa[MB], fb[NB];
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi) fa[bi] = E::read(A + a_base[bi] + a_off);
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj) fb[bj] = E::read(B + ((tail && lh) ? zb : b_base[bj] + b_off));
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+                    for (int bj = 0; bj < NB; ++bj) acc[bi][bj] = E::mfma(fa[bi], fb[bj], acc[bi][bj]);
+            }
+        }
+        if constexpr (E::BYTES == 16 && RC == 0) if (p.single) {
+            done = true;
+            // filter size known only at run time: tap by tap, the upper half on the zero unit
+            int bz[NB];
+#pragma unroll
+            for (int bj = 0; bj < NB; ++bj) bz[bj] = lh ? zero_unit - buf * p.b_stage : b_base[bj];
+            patch_pair<E, T, RC, SC>(A, B, a_base, bz, 0, 0, p.Rp, p.S, p.Wp, acc, bmul);
+        }
+        if (done) {
+        } else if constexpr (RC == 1 && SC == 1) {
             // 1x1 filters: a pair is a single tap, so unroll over pairs instead
             int cp = 0;
             for (; cp + 4 <= npairs; cp += 4) {

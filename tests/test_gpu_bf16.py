@@ -44,8 +44,13 @@ SHAPES = [
     synth.ConvShape("s2", 2, 32, 17, 15, 70, 3, 3, 2, 1),
     synth.ConvShape("1x1", 3, 64, 7, 7, 130, 1, 1, 1, 0),
     synth.ConvShape("1x1s2", 2, 40, 14, 14, 64, 1, 1, 2, 0),
-    synth.ConvShape("rect", 1, 8, 9, 20, 5, 2, 5, 1, 2),
+    synth.ConvShape("rect", 1, 8, 9, 20, 5, 2, 5, 1, 2),        # one unit, filter size not compiled in
+    synth.ConvShape("c8_3x3", 2, 8, 12, 12, 40, 3, 3, 1, 1),    # one unit, nine taps: four pairs and an odd one
+    synth.ConvShape("c5_1x1", 2, 5, 9, 9, 33, 1, 1, 1, 0),      # one unit, one tap
+    synth.ConvShape("c6_1x7", 1, 6, 8, 30, 20, 1, 7, 1, 3),     # one unit, seven taps in a row
 ]
+
+ONE_UNIT = [s for s in SHAPES if s.C <= 8]
 
 
 @pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
@@ -98,6 +103,30 @@ def test_bf16_small_integers_exact(P, s):
                 continue
             assert np.array_equal(got.astype(np.float64), want), v
     P.set_tile_override(None)
+
+
+@pytest.mark.parametrize("s", ONE_UNIT, ids=lambda s: s.name)
+def test_one_unit_reductions_exact(P, s):
+    # at most eight channels: the two halves of the matrix instruction take two taps of the one unit;
+    # every compiled tile, whole and split reductions, small integers bit for bit
+    x, w, b = synth.conv_inputs(s, 54, "ints", bias=True)
+    xb, wb = synth.to_bf16_bits(x), synth.to_bf16_bits(w)
+    want, _ = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
+    x8, w8 = P.nchw_to_nchwc_bf16(dev16(xb), 8), P.kcrs_to_kcrsck_bf16(dev16(wb), 8, 1)
+    ran = 0
+    for v in P.variants(2):
+        for split_k in (1, 3):
+            v.split_k, v.cb = split_k, 0
+            P.set_tile_override(v)
+            try:
+                got = host(P.conv2d_fwd_bf16_blocked(x8, w8, s.C, dev32(b), stride=s.stride, pad=s.pad, act="relu"))
+            except P.PolydlError as e:
+                assert e.status == -3
+                continue
+            assert np.array_equal(got.astype(np.float64), want), v
+            ran += 1
+    P.set_tile_override(None)
+    assert ran > 0
 
 
 @pytest.mark.parametrize("layer", range(8))
