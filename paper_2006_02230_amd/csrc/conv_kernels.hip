@@ -254,23 +254,7 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
         if (__builtin_amdgcn_readfirstlane(s_arrived) != (unsigned)parts - 1u) return;   // not the last part
         if (tid == 0)               // leave the counter at zero for the next launch
             __hip_atomic_store(p.counters + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int bi = 0; bi < T::MB; ++bi)
-#pragma unroll
-            for (int bj = 0; bj < T::NB; ++bj)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
-        for (int sp = 0; sp < parts; ++sp) {
-            const float *part = tile0 + (size_t)sp * TILE;
-#pragma unroll
-            for (int bi = 0; bi < T::MB; ++bi)
-#pragma unroll
-                for (int bj = 0; bj < T::NB; ++bj)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc[bi][bj][r] += __hip_atomic_load(part + ((bi * T::NB + bj) * 16 + r) * NT + tid,
-                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        sum_partial_tiles<T>(tile0, parts, TILE, tid, acc);
     }
     // epilogue.  The lane owns NB adjacent pixels starting at colg for 16*MB output channels.
     // Addresses are a per-lane byte offset from the first image the tile touches plus a uniform

@@ -315,6 +315,41 @@ __device__ __forceinline__ void gemm_mainloop(float *lds, AL &al, BL &bl, v16f (
     }
 }
 
+// Sum of the `parts` partial accumulator tiles of one output tile, in index order (so the result
+// does not depend on which part arrived last).  Tiles lie TILE floats apart, each in register
+// order (thread-contiguous).  The loads are device-scope.  (Requesting part i+1 before part i is
+// added measured no faster: other workgroups fill the compute unit while the last one of a tile sums.)
+template <class T>
+__device__ __forceinline__ void sum_partial_tiles(const float *tile0, int parts, size_t TILE, int tid,
+                                                  v16f (&acc)[T::MB][T::NB])
+{
+    constexpr int R = T::MB * T::NB * 16, NT = T::NT;
+    auto fetch = [&](float (&dst)[R], int sp) {
+        const float *part = tile0 + (size_t)sp * TILE + tid;
+#pragma unroll
+        for (int i = 0; i < R; ++i) dst[i] = __hip_atomic_load(part + (size_t)i * NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    auto add = [&](const float (&src)[R]) {
+#pragma unroll
+        for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[bi][bj][r] += src[(bi * T::NB + bj) * 16 + r];
+    };
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < T::NB; ++bj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+    float a[R];
+    for (int sp = 0; sp < parts; ++sp) {
+        fetch(a, sp);
+        add(a);
+    }
+}
+
 // Row (inside the workgroup tile) of accumulator register r of row block bi for this lane: a
 // 32x32 result keeps column lane%32 in every register and row 8*(r/4) + 4*(lane/32) + r%4 in
 // register r.  With the column permutation above the lane's NB blocks are the NB adjacent
