@@ -25,12 +25,12 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "fa779a9ab7e660bf3b3aca7189b4eb0e6964271e0bc8260af9aa7332ec5db9d2", "batch": 32, "fetch_bytes": 733920506, "write_bytes": 457864632}
+HBM_TRAFFIC = {"csrc_sha256": "8cbf03461fdb35f62ec13cedf52764989a8a3f575f1ef6be970ba9e0204ea7b8", "batch": 32, "fetch_bytes": 701217723, "write_bytes": 422691432}
 
 
 # L2 fetch + write-back bytes of config 4 from two rocprofv3 --pmc runs of `bench.py --copy-probe --counter-pass
 # fusion` (same scaling as above): the fused launch, and the convolution + bias + activation launches it replaces.
-FUSION_TRAFFIC = {"csrc_sha256": "", "fused_bytes": 0, "separate_bytes": 0}
+FUSION_TRAFFIC = {"csrc_sha256": "8cbf03461fdb35f62ec13cedf52764989a8a3f575f1ef6be970ba9e0204ea7b8", "fused_bytes": 120224697, "separate_bytes": 145994995}
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
 

@@ -380,7 +380,10 @@ double model_conv_bf16(const ConvProblem &q, const polydl_tile_cfg &cfg, int thr
     double eff = 0.25, t_round = 3.0, t_lat = 0.8, rate = 60000.0, c1 = 0.1;
     if (mb * nb == 2) { eff = 0.4; t_round = 4.0; c1 = 0.2; }
     else if (mb * nb == 4) { eff = 0.4; t_round = 4.0; t_lat = 0.4; rate = 31000.0; c1 = 0.4; }
-    const double t_stage = std::max(std::ceil(cb / 2.0) * RSp * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
+    // matrix instructions of a stage per accumulator block: one per tap and pair of units; a
+    // reduction of a single unit takes two taps per instruction instead
+    const double steps = q.C == 1 ? std::ceil(RSp / 2.0) : std::ceil(cb / 2.0) * RSp;
+    const double t_stage = std::max(steps * mb * nb * 32.0 * std::ceil(waves_per_wg / kSimdsPerCU) /
                                         kClockHz * 1e6 / eff,
                                     (cfg.bm * cb * RSp + cb * conv_patch_rows(q, cfg.bn) * wp) * 16.0 / rate);
     const double per_cu = tiles * parts / kCUs;

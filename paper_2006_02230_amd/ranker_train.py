@@ -269,7 +269,11 @@ def main():
     ap.add_argument("--import-sweeps", nargs="+", default=[])
     ap.add_argument("--train", action="store_true")
     ap.add_argument("--report", default="")
-    ap.add_argument("--report-command", default="", help="text of the commands, quoted in the report")
+    ap.add_argument("--report-command",
+                    default="    python bench.py --batch B --sweep --sweep-out nB.json --no-cpu --no-sgemm --no-bf16 --no-fusion --no-cold   (B = 16, 32, 64, 128)\n"
+                            "    python -m paper_2006_02230_amd.ranker_train --import-sweeps n16.json n32.json n64.json n128.json\n"
+                            "    python -m paper_2006_02230_amd.ranker_train --train --report profiles/conv_suite_fp32_learned_ranking.md\n",
+                    help="text of the commands, quoted in the report")
     ap.add_argument("--report-note", default="", help="a closing paragraph for the report")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--epochs", type=int, default=30)
