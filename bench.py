@@ -89,6 +89,9 @@ def main():
                          "fused call and the three separate kernels of config 4, 'bf16' = the bf16 suite")
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--sweep", action="store_true", help="also time every compiled variant per layer")
+    ap.add_argument("--filters", default="tap", choices=["tap", "kcrs"],
+                    help="'tap': every layer's filter is also given as its [K][R][S][C] copy, made once before "
+                         "the timed region (polydl_conv2d_fwd_tap); 'kcrs': KCRS only (polydl_conv2d_fwd_act)")
     ap.add_argument("--suite", default="resnet", choices=["resnet", "heldout", "heldout2"],
                     help="'heldout', 'heldout2': two sets of fourteen other CNN layer shapes (pick quality off the "
                          "fitting set; not the headline workload)")
@@ -172,18 +175,21 @@ def main():
             continue
         x, w, b = synth.conv_inputs(s, seed=100 + i, dist="normal", bias=True)
         Pq, Qq = synth.out_hw(s)
-        layers.append(dict(shape=s, P=Pq, Q=Qq, x=torch.from_numpy(x).cuda(), w=torch.from_numpy(w).cuda(),
+        dw = torch.from_numpy(w).cuda()
+        layers.append(dict(shape=s, P=Pq, Q=Qq, x=torch.from_numpy(x).cuda(), w=dw,
+                           wt=P.filter_tap_copy(dw) if args.filters == "tap" else None,
                            b=torch.from_numpy(b).cuda(),
                            out=torch.empty((s.N, s.K, Pq, Qq), dtype=torch.float32, device="cuda"),
                            index=i, flops=conv_flops(s, Pq, Qq), bytes=conv_bytes(s, Pq, Qq), host=(x, w, b)))
 
-    def run_layer(L):
+    def run_layer(L, tap=True):
         s = L["shape"]
-        P.conv2d_fwd(L["x"], L["w"], L["b"], out=L["out"], stride=s.stride, pad=s.pad, act="relu")
+        P.conv2d_fwd(L["x"], L["w"], L["b"], out=L["out"], stride=s.stride, pad=s.pad, act="relu",
+                     w_tap=L["wt"] if tap else None)
 
-    def step():
+    def step(tap=True):
         for L in layers:
-            run_layer(L)
+            run_layer(L, tap)
 
     P.set_tile_override(forced)
     # the GPU's clocks take tens of milliseconds of load to reach their steady state; a short --warmup
@@ -254,13 +260,14 @@ def main():
             # the same call over a rotation of distinct operand sets larger than the 256 MB last-level
             # cache taken twice, so that no call finds its operands or its output lines cached
             nsets = max(2, int(-(-COLD_ROTATION_BYTES // L["bytes"])))
-            sets = [(L["x"].clone(), L["w"].clone(), L["b"].clone(), torch.empty_like(L["out"])) for _ in range(nsets)]
+            sets = [(L["x"].clone(), L["w"].clone(), L["b"].clone(), torch.empty_like(L["out"]),
+                     None if L["wt"] is None else L["wt"].clone()) for _ in range(nsets)]
             turn = [0]
 
             def run_cold(L=L, sets=sets, turn=turn):
-                x, w, b, o = sets[turn[0] % len(sets)]
+                x, w, b, o, wt = sets[turn[0] % len(sets)]
                 turn[0] += 1
-                P.conv2d_fwd(x, w, b, out=o, stride=L["shape"].stride, pad=L["shape"].pad, act="relu")
+                P.conv2d_fwd(x, w, b, out=o, stride=L["shape"].stride, pad=L["shape"].pad, act="relu", w_tap=wt)
 
             cms = time_calls(torch, run_cold, max(reps, nsets))
             rows[-1].update(cold_us=round(cms * 1e3, 2), cold_sets=nsets,
@@ -272,7 +279,7 @@ def main():
             shape = tuple(L["shape"])[1:]
             cands = []
             t_sweep = time.perf_counter()
-            for v in P.conv_candidates(shape):
+            for v in P.conv_candidates(shape, tap=L["wt"] is not None):
                 try:
                     P.set_tile_override(v)
                     run_layer(L)
@@ -316,11 +323,30 @@ def main():
                 rows[-1].update(learned_tile=lcfg.as_dict(), learned_us=round(lms * 1e3, 2),
                                 learned_over_best=round(best["us"] / (lms * 1e3), 4),
                                 learned_wins=[lwins, lgames], learned_pick_seconds=round(t_learn, 4))
-            sweep_dump.append(dict(layer=i, shape=list(shape), picked=pcfg.as_dict(), picked_us=round(ms * 1e3, 2),
+            sweep_dump.append(dict(layer=i, shape=list(shape), picked=tile, picked_us=round(ms * 1e3, 2),
                                    candidates=cands))
     if args.no_layer_rows:
         kern_ms_sum = e0.elapsed_time(e1) / args.steps
     achieved = total_flops / (kern_ms_sum * 1e-3) / 1e12
+
+    # the same suite without the filter copies (polydl_conv2d_fwd_act on NCHW / KCRS alone): the step
+    # timed the same way, and each layer's launch time
+    kcrs_only = None
+    if args.filters == "tap" and not args.no_layer_rows:
+        for _ in range(min(args.warmup, 20)):
+            step(tap=False)
+        torch.cuda.synchronize()
+        tk = time.perf_counter()
+        for _ in range(args.steps):
+            step(tap=False)
+        torch.cuda.synchronize()
+        k_ms = (time.perf_counter() - tk) * 1e3 / args.steps
+        k_us = []
+        for L in layers:
+            k_us.append(round(time_calls(torch, lambda L=L: run_layer(L, tap=False), 30) * 1e3, 2))
+        kcrs_only = dict(ms_per_step=round(k_ms, 4), value=round(total_flops / (k_ms * 1e-3) / 1e12, 3),
+                         layers_us=k_us, achieved=round(total_flops / (sum(k_us) * 1e-6) / 1e12, 3),
+                         frac=round(total_flops / (sum(k_us) * 1e-6) / 1e12 / FP32_MFMA_PEAK_TFLOPS, 4))
 
     sg = []
     if not args.no_sgemm:
@@ -638,7 +664,7 @@ def main():
 
     traffic = None
     if (HBM_TRAFFIC["csrc_sha256"] == csrc_digest() and args.batch == HBM_TRAFFIC["batch"] and len(chosen) == 8
-            and args.suite == "resnet"
+            and args.suite == "resnet" and args.filters == HBM_TRAFFIC.get("filters", "kcrs")
             and forced is None):
         traffic = HBM_TRAFFIC["fetch_bytes"] + HBM_TRAFFIC["write_bytes"]
     result = {
@@ -652,6 +678,10 @@ def main():
                                if args.suite == "resnet" else
                                ("held-out CNN layer shapes (not the headline workload), fp32 NCHW, N=%d, layers %s"
                                 % (args.batch, str(chosen))),
+                   "filters": ("KCRS, and the same filter as [K][R][S][C] (KCRSck with bc = C, bk = 1) made once "
+                               "before the timed region and passed with it (polydl_conv2d_fwd_tap); the row "
+                               "kcrs_only times the suite without the copies") if args.filters == "tap"
+                              else "KCRS only (polydl_conv2d_fwd_act)",
                    "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4),
                    "clock_warm_ms": args.clock_warm_ms},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
@@ -663,6 +693,7 @@ def main():
                                "layers, nominal 2*N*K*P*Q*C*R*S flops / sum of per-layer mean launch durations)"},
         "cpu_baseline": cpu,
         "layers": rows,
+        "kcrs_only": kcrs_only,
         "sgemm": sg,
         "bf16": bf,
         "fusion": fusion,

@@ -71,7 +71,9 @@ typedef struct polydl_tile_cfg {
     int bm, bn, bk;   /* workgroup tile: bm x bn outputs, bk reduction elements per stage      */
     int wm, wn;       /* wave tile (multiples of 32); the workgroup has (bm/wm)*(bn/wn) waves  */
     int split_k;      /* >= 1: the reduction is cut into this many parts (one workgroup each);  */
-    int layout;       /* 0: read NCHW / KCRS directly; 1: via blocked NCHWc / KCRSck copies    */
+    int layout;       /* 0: read NCHW / KCRS directly; 1: via blocked NCHWc / KCRSck copies;
+                         2: gather kernel reading the filter's [K][R][S][C] copy, reduction walked
+                         tap by tap (polydl_conv2d_fwd_tap)                                      */
     int raster;       /* 0: workgroups walk M fastest; 1: chunked per XCD, grouped for L2 reuse;
                          2 (convolution, algo 0, split_k 1): order 0, and when the tile count
                          leaves a last round of workgroups that at most half of the compute units
@@ -133,6 +135,24 @@ int polydl_conv2d_fwd_pre_act(int N, int C, int H, int W, int K, int R, int S, i
 int polydl_conv2d_fwd_noalloc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                               const float *in, const float *wt, const float *bias, float *out,
                               int act /* polydl_act */, void *stream);
+
+/* Convolution with the filter also given in a blocked layout (figure "The 2-D Convolution code":
+ * the listing's filter is blocked; section "Microkernel Specification": the order of the reduction
+ * is free).  wt_tap is the same filter as [K][R][S][C], that is KCRSck with bc = C and bk = 1,
+ * written by polydl_kcrs_to_kcrsck(K, C, R, S, C, 1, wt, wt_tap, stream): K*C*R*S floats of device
+ * memory owned by the caller, 16-byte aligned, prepared once per filter and reused while wt does
+ * not change (the library keeps no copy and cannot tell a stale one).  With it, the gather kernel
+ * can walk the reduction tap by tap (all channels of a tap, then the next tap), so that a whole
+ * stage of the reduction shares one tap: the padding test and the address distance are then found
+ * once per stage instead of once per element.  Used when R*S is 2..63 and C is a multiple of the
+ * stage depth (16); otherwise, or with wt_tap NULL or aligned to less, the call is
+ * polydl_conv2d_fwd_act.  The picker chooses among the same variants, the gather ones priced for
+ * the cheaper addressing (tile layout 2); the other kernels read wt.  Result: the same sum in
+ * another order, the same tolerance.  Arguments, ownership and errors otherwise as
+ * polydl_conv2d_fwd_act. */
+int polydl_conv2d_fwd_tap(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                          const float *in, const float *wt, const float *wt_tap, const float *bias, float *out,
+                          int act /* polydl_act */, void *stream);
 
 /* ---- matrix product ------------------------------------------------------------------------
  * C[i][j] += sum_k A[i][k] * B[k][j]   (alpha = beta = 1, the reading taken of section "GEMM").
@@ -355,8 +375,9 @@ int polydl_get_last_tile(polydl_tile_cfg *cfg);
 /* The candidate lists the pickers rank, for an exhaustive sweep over exactly the same space
  * (section "Experimental Evaluation": the picked variant against the best of all variants).
  * polydl_conv2d_candidates: kind 0 = what polydl_pick_conv2d ranks (fp32: kernel, tile, stage depth,
- *   split factor, leftover-tile switch), kind 2 = what polydl_pick_conv2d_bf16 ranks (C counts
- *   channels).  polydl_sgemm_candidates: what polydl_pick_sgemm ranks.
+ *   split factor, leftover-tile switch), kind 3 = the same when polydl_conv2d_fwd_tap is given
+ *   the filter copy (gather variants in tile layout 2 where it applies), kind 2 = what
+ *   polydl_pick_conv2d_bf16 ranks (C counts channels).  polydl_sgemm_candidates: what polydl_pick_sgemm ranks.
  * *count receives the number of candidates; the first min(*count, max_cfgs) are written to cfgs
  * (host memory; cfgs may be NULL when max_cfgs is 0).  Errors as the matching pick function. */
 int polydl_conv2d_candidates(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int kind,

@@ -4,7 +4,7 @@ The Python layer only marshals arguments (device pointers, sizes, the current HI
 libpolydl.so; every arithmetic step runs in the HIP kernels.  There is no CPU fallback: if the
 library has not been built, importing this package raises.
 """
-from .binding import (lib, PolydlError, TileCfg, ACT, conv2d_fwd, conv2d_fwd_noalloc, sgemm, set_tile_override,
+from .binding import (lib, PolydlError, TileCfg, ACT, conv2d_fwd, conv2d_fwd_noalloc, filter_tap_copy, sgemm, set_tile_override,
                       get_last_tile, variants, status_string, LIB_PATH, nchw_to_nchwc,
                       nchwc_to_nchw, kcrs_to_kcrsck, bias_add, activation, ModelReport,
                       reuse_bucket, reuse_cost, model_get_levels, model_set_levels, model_conv2d, model_sgemm, pick_conv2d, pick_sgemm,
@@ -14,7 +14,7 @@ from .binding import (lib, PolydlError, TileCfg, ACT, conv2d_fwd, conv2d_fwd_noa
                       ranker_load, ranker_stats_conv2d, ranker_play, ranker_tournament, pick_conv2d_learned,
                       RANKER_STATS, RANKER_PARAMS_PATH, reuse_analyse)
 
-__all__ = ["lib", "PolydlError", "TileCfg", "ACT", "conv2d_fwd", "conv2d_fwd_noalloc", "sgemm", "set_tile_override",
+__all__ = ["lib", "PolydlError", "TileCfg", "ACT", "conv2d_fwd", "conv2d_fwd_noalloc", "filter_tap_copy", "sgemm", "set_tile_override",
            "get_last_tile", "variants", "status_string", "LIB_PATH", "nchw_to_nchwc", "nchwc_to_nchw",
            "kcrs_to_kcrsck", "bias_add", "activation", "ModelReport", "reuse_bucket", "reuse_cost",
            "model_get_levels", "model_set_levels", "model_conv2d", "model_sgemm", "pick_conv2d", "pick_sgemm", "conv_candidates",

@@ -64,6 +64,8 @@ lib.polydl_conv2d_fwd_pre_act.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _i, _p]
 lib.polydl_conv2d_fwd_pre_act.restype = _i
 lib.polydl_conv2d_fwd_noalloc.argtypes = [_i] * 9 + [_p, _p, _p, _p, _i, _p]
 lib.polydl_conv2d_fwd_noalloc.restype = _i
+lib.polydl_conv2d_fwd_tap.argtypes = [_i] * 9 + [_p, _p, _p, _p, _p, _i, _p]
+lib.polydl_conv2d_fwd_tap.restype = _i
 lib.polydl_sgemm.argtypes = [_i, _i, _i, _p, _p, _p, _p]
 lib.polydl_sgemm_ex.argtypes = [_i, _i, _i, ctypes.c_float, _p, _p, ctypes.c_float, _p, _p]
 lib.polydl_sgemm_ex.restype = _i
@@ -217,9 +219,17 @@ def conv2d_fwd_bf16(x, w, bias=None, out=None, stride=1, pad=0, act=None, worksp
     return out
 
 
-def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None, pre_act=None):
+def filter_tap_copy(w, stream=None, out=None):
+    """The [K][R][S][C] copy of a KCRS filter that conv2d_fwd(..., w_tap=) takes: polydl_kcrs_to_kcrsck
+    with bc = C, bk = 1."""
+    K, C, R, S = w.shape
+    return kcrs_to_kcrsck(w, C, 1, stream=stream, out=out).view(K, R, S, C)
+
+
+def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None, pre_act=None, w_tap=None):
     """polydl_conv2d_fwd_act on torch device tensors x (NCHW), w (KCRS); returns out (NKPQ).
-    With pre_act given, polydl_conv2d_fwd_pre_act: the convolution of pre_act(x)."""
+    With pre_act given, polydl_conv2d_fwd_pre_act: the convolution of pre_act(x).
+    With w_tap given (filter_tap_copy(w)), polydl_conv2d_fwd_tap."""
     import torch
     N, C, H, W = x.shape
     K, C2, R, S = w.shape
@@ -229,7 +239,15 @@ def conv2d_fwd(x, w, bias=None, out=None, stride=1, pad=0, act=None, stream=None
     Q = (W + 2 * pad - S) // stride + 1
     if out is None:
         out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.float32, device=x.device)
-    if pre_act is None:
+    if w_tap is not None:
+        if pre_act is not None:
+            raise ValueError("w_tap and pre_act do not combine")
+        if tuple(w_tap.shape) != (K, R, S, C):
+            raise ValueError("w_tap must be [K][R][S][C]")
+        st = lib.polydl_conv2d_fwd_tap(N, C, H, W, K, R, S, stride, pad, _dev(x, "x"), _dev(w, "w"),
+                                       _dev(w_tap, "w_tap"), _dev(bias, "bias"), _dev(out, "out"), ACT[act],
+                                       _stream_ptr(stream))
+    elif pre_act is None:
         st = lib.polydl_conv2d_fwd_act(N, C, H, W, K, R, S, stride, pad, _dev(x, "x"), _dev(w, "w"),
                                        _dev(bias, "bias"), _dev(out, "out"), ACT[act], _stream_ptr(stream))
     else:
@@ -534,10 +552,12 @@ def _candidates(call, where):
     return [TileCfg(*[getattr(arr[i], f) for f, _ in TileCfg._fields_]) for i in range(n.value)]
 
 
-def conv_candidates(shape):
-    """polydl_conv2d_candidates, kind 0: every variant polydl_pick_conv2d ranks for this problem."""
+def conv_candidates(shape, tap=False):
+    """polydl_conv2d_candidates, kind 0: every variant polydl_pick_conv2d ranks for this problem;
+    tap=True, kind 3: the variants ranked when the filter's [K][R][S][C] copy is given."""
     dims = [int(v) for v in shape]
-    return _candidates(lambda m, a, n: lib.polydl_conv2d_candidates(*dims, 0, m, a, n), "polydl_conv2d_candidates")
+    kind = 3 if tap else 0
+    return _candidates(lambda m, a, n: lib.polydl_conv2d_candidates(*dims, kind, m, a, n), "polydl_conv2d_candidates")
 
 
 def sgemm_candidates(M, N, K):

@@ -195,7 +195,7 @@ static int sgemm_impl(int M, int N, int K, float alpha, const float *A, const fl
 
 static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                      const float *in, const float *wt, const float *bias, float *out, int pre_act, int act,
-                     void *stream, const ScratchArena *arena = nullptr)
+                     void *stream, const ScratchArena *arena = nullptr, const float *wt_tap = nullptr)
 {
     if (pre_act != POLYDL_ACT_NONE && pre_act != POLYDL_ACT_RELU && pre_act != POLYDL_ACT_RELU6)
         return POLYDL_ERR_UNSUPPORTED;
@@ -208,6 +208,8 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     if (!on_gfx950()) return POLYDL_ERR_NO_DEVICE;
     const int64_t Kg = (int64_t)C * R * S, CHW = (int64_t)C * H * W;
     ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, in, wt, bias, out, act, pre_act, arena};
+    // a filter copy aligned to less than 16 bytes is ignored: every kernel then reads wt
+    q.has_tap = wt_tap && !((uintptr_t)wt_tap & 15);
     polydl_tile_cfg cfg;
     bool forced;
     {
@@ -216,7 +218,8 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         cfg = g_override;
     }
     if (!forced) {
-        const std::array<int, 10> key = {N, C, H, W, K, R, S, stride, pad, pre_act != POLYDL_ACT_NONE};
+        const std::array<int, 10> key = {N, C, H, W, K, R, S, stride, pad,
+                                         (pre_act != POLYDL_ACT_NONE ? 1 : 0) | (q.has_tap ? 2 : 0)};
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_conv_plans.find(key);
         if (it != g_conv_plans.end()) {
@@ -240,7 +243,7 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
         if (!b) return POLYDL_ERR_UNSUPPORTED;
         cfg = b->cfg;
     }
-    if (cfg.layout != 0) return POLYDL_ERR_UNSUPPORTED;
+    if (cfg.layout != 0 && !(cfg.layout == 2 && cfg.algo == 0)) return POLYDL_ERR_UNSUPPORTED;
     if (cfg.algo == 2) {
         if (!is_conv_point_cfg(cfg) || !conv_point_fits(q) || !point_aligned) return POLYDL_ERR_UNSUPPORTED;
         hipError_t pe = conv_point_launch(q, (hipStream_t)stream);
@@ -270,6 +273,10 @@ static int conv_impl(int N, int C, int H, int W, int K, int R, int S, int stride
     const int64_t span_out = (v->bn / (P * Q) + 2) * (int64_t)K * P * Q * 4;
     if (span >= 0x7FFFFFF0ll || span_out >= 0x7FFFFFF0ll || (int64_t)v->bm * Kg * 4 >= 0x7FFFFFF0ll)
         return POLYDL_ERR_UNSUPPORTED;
+    if (cfg.layout == 2) {
+        if (!q.has_tap || !gather_tap_major_fits(q, v->bk)) return POLYDL_ERR_UNSUPPORTED;
+        q.wt_tap = wt_tap;
+    }
     hipError_t e = v->conv(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
     if (e != hipSuccess) return launch_failed(e);
     std::lock_guard<std::mutex> lk(g_mu);
@@ -316,6 +323,14 @@ int polydl_conv2d_fwd_noalloc(int N, int C, int H, int W, int K, int R, int S, i
         return POLYDL_ERR_LAUNCH;
     }
     return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, POLYDL_ACT_NONE, act, stream, &arena);
+}
+
+int polydl_conv2d_fwd_tap(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                          const float *in, const float *wt, const float *wt_tap, const float *bias, float *out,
+                          int act, void *stream)
+{
+    return conv_impl(N, C, H, W, K, R, S, stride, pad, in, wt, bias, out, POLYDL_ACT_NONE, act, stream, nullptr,
+                     wt_tap);
 }
 
 int polydl_sgemm(int M, int N, int K, const float *A, const float *B, float *C, void *stream)
@@ -776,11 +791,12 @@ int polydl_conv2d_candidates(int N, int C, int H, int W, int K, int R, int S, in
     if (!count || (max_cfgs > 0 && !cfgs)) return POLYDL_ERR_NULL_POINTER;
     if (max_cfgs < 0) return POLYDL_ERR_BAD_DIMENSION;
     std::vector<polydl_tile_cfg> list;
-    if (kind == 0) {
+    if (kind == 0 || kind == 3) {
         int64_t P, Q;
         if (!conv_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return POLYDL_ERR_BAD_DIMENSION;
         if (!conv_in_range(N, C, H, W, K, R, S, stride, pad, P, Q)) return POLYDL_ERR_UNSUPPORTED;
         ConvProblem q{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q, nullptr, nullptr, nullptr, nullptr, 0};
+        q.has_tap = kind == 3;
         std::vector<ConvCandidate> cands;
         conv_candidates(q, &cands);
         for (const ConvCandidate &c : cands) list.push_back(c.cfg);
@@ -819,7 +835,8 @@ int polydl_set_tile_override(const polydl_tile_cfg *cfg)
                                       : (cfg->algo == 1 ? (find_patch_variant(*cfg) != nullptr ||
                                                            find_patch_bf16_variant(*cfg) != nullptr)
                                                         : (cfg->algo == 0 && find_variant(*cfg) != nullptr));
-    if (!known || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 1 || cfg->raster < 0 ||
+    if (!known || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 2 || (cfg->layout == 2 && cfg->algo != 0) ||
+        cfg->raster < 0 ||
         cfg->raster > 2 || (cfg->raster == 2 && cfg->algo != 0) || cfg->cb < 0 || (cfg->cb & 1))
         return POLYDL_ERR_UNSUPPORTED;
     g_override = *cfg;

@@ -20,6 +20,7 @@ struct ConvKArgs {
     int C, H, W, K, R, S, stride, pad, P, Q;
     int PQ, RS, HW, CHW;
     int Kg, Ng;                 // reduction length C*R*S, number of output pixels N*P*Q
+    uint32_t magic_C;           // GATHER_TAPMAJOR: exact division of a reduction index by C (C > 1)
     uint32_t magic_RS, magic_S; // exact division of a reduction index by R*S and by S,
     uint32_t one_RS, one_S;     // see fast_div(): magic multiplier and the all-ones mask for d == 1
     uint32_t recip_PQ, recip_Q; // for div_by(): pixel index -> (image, row, column)
@@ -66,12 +67,21 @@ __device__ __forceinline__ uint32_t outside_bits(int lo, int hi, int n)
 //               (set: outside the image) in one / two registers and the byte offset of tap (0,0);
 //               the tap's distance is uniform and rides in the uniform offset, so a load costs a
 //               bit extract and a merge of that bit into the top of the offset.
-enum { GATHER_ANY = 0, GATHER_POINT = 1, GATHER_TAPS1 = 2, GATHER_TAPS2 = 3 };
+//  GATHER_TAPMAJOR  filters of 2 .. 63 taps whose channel count is a multiple of the stage depth, with
+//               a second copy of the filter in the blocked layout [K][R][S][C] (KCRSck with
+//               bc = C, bk = 1): the reduction is walked tap by tap, all channels of a tap before
+//               the next tap (the order is free, section "Microkernel Specification"), so a whole
+//               stage shares one tap: its validity bit and its distance are found once per stage,
+//               not per element, and the channel rides in the uniform offset.  In that copy the
+//               filter rows are contiguous in the walked order, so they load as in a plain GEMM.
+enum { GATHER_ANY = 0, GATHER_POINT = 1, GATHER_TAPS1 = 2, GATHER_TAPS2 = 3, GATHER_TAPMAJOR = 4 };
+
 
 template <class T, int MODE>
 struct BLoaderIm2col {
     static constexpr bool POINT = MODE == GATHER_POINT;
-    static constexpr bool TAPS = MODE == GATHER_TAPS1 || MODE == GATHER_TAPS2;
+    static constexpr bool TAPMAJOR = MODE == GATHER_TAPMAJOR;
+    static constexpr bool TAPS = MODE == GATHER_TAPS1 || MODE == GATHER_TAPS2 || TAPMAJOR;
     static constexpr int LAST_BIT = MODE == GATHER_TAPS1 ? 31 : 63;   // never a tap: always set
     static constexpr int KSTEP = T::NT / T::BN;  // reduction rows covered by one pass of the workgroup
     static constexpr int ITERS = T::BK / KSTEP;
@@ -81,12 +91,12 @@ struct BLoaderIm2col {
     int pix_off;      // element offset of tap (0,0), channel 0 of this pixel from the descriptor base
     uint32_t rmask, smask;   // GATHER_TAPS*: the tap bits 0-31 and 32-63
     int krow0, lds_off;
-    int RS, S, HW, W, pre_act;
-    uint32_t magic_RS, magic_S, one_RS, one_S;
+    int RS, S, HW, W, pre_act, C;
+    uint32_t magic_RS, magic_S, one_RS, one_S, magic_C;
 
     __device__ __forceinline__ void init(const ConvKArgs &p, int tid, int n0)
     {
-        RS = p.RS; S = p.S; HW = p.HW; W = p.W; pre_act = p.pre_act;
+        RS = p.RS; S = p.S; HW = p.HW; W = p.W; pre_act = p.pre_act; C = p.C; magic_C = p.magic_C;
         magic_RS = p.magic_RS; magic_S = p.magic_S; one_RS = p.one_RS; one_S = p.one_S;
         const int col = tid % T::BN;
         krow0 = __builtin_amdgcn_readfirstlane(tid / T::BN);
@@ -128,6 +138,7 @@ struct BLoaderIm2col {
             rmask = 0xFFFFFFFFu; smask = 0xFFFFFFFFu;
         }
         if constexpr (TAPS) { if (MODE == GATHER_TAPS1) rmask |= 1u << 31; else smask |= 1u << 31; }
+        (void)C; (void)magic_C;
         if constexpr (POINT) pix_off = colg < p.Ng ? pix_off * 4 : (int)kOobOffset;   // bytes, or out of range
     }
     template <int SET>
@@ -140,6 +151,22 @@ struct BLoaderIm2col {
             for (int i = 0; i < ITERS; ++i) {
                 int kg = min(k0 + krow0 + i * KSTEP, kend - 1);  // wave-uniform
                 regs[SET][i] = buf_load1(rsrc, (uint32_t)pix_off, (uint32_t)(kg * HW) * 4u);
+            }
+            return;
+        }
+        if constexpr (TAPMAJOR) {
+            // one tap for the whole stage: its bit and its distance once, the channel in the uniform offset
+            const uint32_t kk = k0 < kend ? (uint32_t)k0 : 0u;
+            const uint32_t tap = __umulhi(kk, magic_C), c0 = kk - tap * (uint32_t)C;
+            const uint32_t r = fast_div(tap, magic_S, one_S), sx = tap - r * (uint32_t)S;
+            const uint32_t t = k0 < kend ? tap : (uint32_t)LAST_BIT;
+            const uint32_t word = t < 32u ? rmask : smask;
+            const uint32_t off = (uint32_t)pix_off | (((word >> (t & 31u)) & 1u) << 31);
+            uint32_t koff = ((c0 + (uint32_t)krow0) * (uint32_t)HW + r * (uint32_t)W + sx) * 4u;
+#pragma unroll
+            for (int i = 0; i < ITERS; ++i) {
+                regs[SET][i] = buf_load1(rsrc, off, koff);
+                koff += (uint32_t)(KSTEP * HW) * 4u;
             }
             return;
         }
@@ -313,6 +340,7 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     a.PQ = q.P * q.Q; a.RS = q.R * q.S; a.HW = q.H * q.W; a.CHW = q.C * q.H * q.W;
     a.Kg = q.C * q.R * q.S;
     a.Ng = q.N * a.PQ;
+    a.magic_C = div_magic((uint32_t)q.C);
     a.magic_RS = div_magic((uint32_t)a.RS);
     a.magic_S = div_magic((uint32_t)q.S);
     a.one_RS = a.RS == 1 ? 0xFFFFFFFFu : 0u;
@@ -357,10 +385,19 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
         }
     }
     const bool avec = (a.Kg % 4 == 0) && ((uintptr_t)q.wt % 16 == 0);
+    // tile layout 2: the filter comes as [K][R][S][C], 16-byte aligned (its rows load as vectors)
+    const bool tapmajor = q.wt_tap != nullptr;
+    if (tapmajor) {
+        if (!gather_tap_major_fits(q, T::BK) || ((uintptr_t)q.wt_tap & 15)) return hipErrorInvalidValue;
+        a.wt = q.wt_tap;
+    }
     const int mode = (q.R == 1 && q.S == 1 && q.pad == 0) ? GATHER_POINT
+                     : tapmajor ? GATHER_TAPMAJOR
                      : a.RS <= 31 ? GATHER_TAPS1 : a.RS <= 63 ? GATHER_TAPS2 : GATHER_ANY;
 #define POLYDL_GO(AV, MODE) le = launch_kernel((conv_kernel<T, AV, MODE>), grid, block, 0, stream, a)
-    if (avec) {
+    if (mode == GATHER_TAPMAJOR) {
+        POLYDL_GO(4, GATHER_TAPMAJOR);
+    } else if (avec) {
         if (mode == GATHER_POINT) POLYDL_GO(4, GATHER_POINT);
         else if (mode == GATHER_TAPS1) POLYDL_GO(4, GATHER_TAPS1);
         else if (mode == GATHER_TAPS2) POLYDL_GO(4, GATHER_TAPS2);

@@ -35,7 +35,19 @@ struct ConvProblem {
     int act;
     int pre_act = 0;       // polydl_act applied to every input element as it is read (gather kernel only)
     const ScratchArena *arena = nullptr;   // split reductions: nullptr = the library's per-stream buffers
+    // fp32: the caller also holds the filter as [K][R][S][C] (tile layout 2, gather kernel only).  The
+    // launchers read wt_tap instead of wt when it is set; the picker only looks at has_tap.
+    const float *wt_tap = nullptr;
+    bool has_tap = false;
 };
+
+// Whether the gather kernel can walk the reduction tap by tap (tile layout 2; bk = stage depth): 2..63 taps,
+// whole stages inside one tap, and C * (C*R*S) below 2^32 for its exact division by C.
+inline bool gather_tap_major_fits(const ConvProblem &q, int bk)
+{
+    const int64_t RS = (int64_t)q.R * q.S;
+    return RS >= 2 && RS <= 63 && q.C % bk == 0 && RS * q.C * q.C < (1ll << 32);
+}
 
 // One compiled variant: its tile parameters and the launchers instantiated for it.
 struct Variant {

@@ -52,6 +52,9 @@ void model_set_levels(const double *capacity, const double *gbytes_per_s, double
     kHbmGBs = mem_gbytes_per_s;
 }
 static const double kClockHz = 2.4e9;
+// Gather cost per element with the filter copy of tile layout 2, relative to layout 0 (fitted to a
+// sweep of the 3x3 layers of the ResNet-50-shaped suite).
+static const double kTapMajorGather = 0.5, kTapMajorGather11 = 0.3, kTapMajorGather21 = 0.6;
 static const int kSimdsPerCU = 4, kXcds = 8;
 // compute units of the current device (256 on an MI355X; also the answer when no device is visible)
 #define kCUs (compute_units())
@@ -343,6 +346,9 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         // lanes read a contiguous run of pixels (stride 1); with a stride the lanes' addresses are
         // spread over several times the cache lines and the loads cost what gathered ones do
         if (point && q.stride == 1) c.gather_cycles *= 0.1;
+        // tap by tap over the [K][R][S][C] filter copy: one tap per stage, so the validity bit and
+        // the distance are worked out per stage and not per element
+        if (cfg.layout == 2) c.gather_cycles *= mbn == 11 ? kTapMajorGather11 : (mbn == 21 ? kTapMajorGather21 : kTapMajorGather);
         if (c.split_c1 == 0) c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
     }
     Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
@@ -493,6 +499,7 @@ void conv_candidates(const ConvProblem &q, std::vector<ConvCandidate> *out)
         for (int sk : kSplits) {
             if (sk > stages) break;
             cand.cfg = {v.bm, v.bn, v.bk, v.wm, v.wn, sk, 0, 0, 0, 0};
+            if (q.has_tap && gather_tap_major_fits(q, v.bk)) cand.cfg.layout = 2;   // never slower than layout 0
             model_conv(q, cand.cfg, v.threads, 0, &cand.rep);
             out->push_back(cand);
             // the same with the leftover tiles of the last round split (wave tiles up to 64x32:
