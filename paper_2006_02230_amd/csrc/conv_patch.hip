@@ -390,20 +390,15 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
     load_stage(t_begin, 0);
     wait_vmcnt0();   // vmcnt(0): this wave's direct-to-LDS loads have landed
     __syncthreads();
-    for (int t = t_begin; t < t_end; ++t) {
-        const int buf = (t - t_begin) & 1;
-        // buffer buf^1 was last read in stage t-1, which every wave has left (barrier below)
-        if (t + 1 < t_end) load_stage(t + 1, buf ^ 1);
-
-        const unit_t *A = As + buf * a_stage;
-        const unit_t *B = Bs + buf * p.b_stage;
-        bool done = false;   // uniform
-        if constexpr (E::BYTES == 16 && RC > 0) if (p.single) {
-            done = true;
-            // A reduction of one unit: the two halves of the matrix instruction's reduction take two
-            // TAPS of that unit -- lanes 0-31 tap t, lanes 32-63 tap t+1 -- instead of two units.  The
-            // upper half of a last odd tap multiplies the zero column behind the filter row (LDA > D)
-            // with the zero unit.
+    // The one-unit form below gets a stage loop of its own instead of a branch inside the common
+    // loop: with two alternative bodies in one loop the compiler keeps the accumulators in two
+    // register sets and copies all of them across twice per stage.
+    // A reduction of one unit, filter size compiled in: the two halves of the matrix instruction's
+    // reduction take two TAPS of that unit -- lanes 0-31 tap t, lanes 32-63 tap t+1 -- instead of two
+    // units.  The upper half of a last odd tap multiplies the zero column behind the filter row
+    // (LDA > D) with the zero unit.
+    auto one_unit_taps = [&](const unit_t *A, const unit_t *B, int buf) {
+        if constexpr (RC > 0) {
             const int zb = zero_unit - buf * p.b_stage;   // the zero unit, relative to this stage's patch
 #pragma unroll
             for (int t = 0; t < RC * SC; t += 2) {
@@ -422,17 +417,16 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
 #pragma unroll
                     for (int bj = 0; bj < NB; ++bj) acc[bi][bj] = E::mfma(fa[bi], fb[bj], acc[bi][bj]);
             }
-        }
-        if constexpr (E::BYTES == 16 && RC == 0) if (p.single) {
-            done = true;
+        } else {
             // filter size known only at run time: tap by tap, the upper half on the zero unit
             int bz[NB];
 #pragma unroll
             for (int bj = 0; bj < NB; ++bj) bz[bj] = lh ? zero_unit - buf * p.b_stage : b_base[bj];
             patch_pair<E, T, RC, SC>(A, B, a_base, bz, 0, 0, p.Rp, p.S, p.Wp, acc, bmul);
         }
-        if (done) {
-        } else if constexpr (RC == 1 && SC == 1) {
+    };
+    auto pairs = [&](const unit_t *A, const unit_t *B, int) {
+        if constexpr (RC == 1 && SC == 1) {
             // 1x1 filters: a pair is a single tap, so unroll over pairs instead
             int cp = 0;
             for (; cp + 4 <= npairs; cp += 4) {
@@ -446,8 +440,26 @@ __global__ __launch_bounds__(T::NT) void conv_patch_kernel(ConvPatchKArgs p)
             for (int cp = 0; cp < npairs; ++cp)
                 patch_pair<E, T, RC, SC>(A, B, a_base, b_base, cp * 2 * p.RSp, cp * 2 * chs, p.Rp, p.S, p.Wp, acc, bmul);
         }
-        wait_vmcnt0();   // vmcnt(0)
-        __syncthreads();
+    };
+    bool one_unit = false;   // uniform
+    if constexpr (E::BYTES == 16) one_unit = p.single != 0;
+    if (one_unit) {
+        for (int t = t_begin; t < t_end; ++t) {
+            const int buf = (t - t_begin) & 1;
+            // buffer buf^1 was last read in stage t-1, which every wave has left (barrier below)
+            if (t + 1 < t_end) load_stage(t + 1, buf ^ 1);
+            one_unit_taps(As + buf * a_stage, Bs + buf * p.b_stage, buf);
+            wait_vmcnt0();   // vmcnt(0)
+            __syncthreads();
+        }
+    } else {
+        for (int t = t_begin; t < t_end; ++t) {
+            const int buf = (t - t_begin) & 1;
+            if (t + 1 < t_end) load_stage(t + 1, buf ^ 1);
+            pairs(As + buf * a_stage, Bs + buf * p.b_stage, buf);
+            wait_vmcnt0();   // vmcnt(0)
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: bias, activation, store NKPQ ------------------------------------------------

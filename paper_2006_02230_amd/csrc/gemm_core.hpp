@@ -308,11 +308,17 @@ __device__ __forceinline__ void gemm_mainloop(float *lds, AL &al, BL &bl, v16f (
     al.template store<0>(As, tid);
     bl.template store<0>(Bs, tid);
     __syncthreads();
-    for (int k0 = kbegin; k0 < kend; k0 += 2 * T::BK) {
+    // Stages go in pairs, both halves unconditionally, and an odd last stage is peeled off: with a
+    // conditional second half inside the loop the compiler has to assume at the loop head that the
+    // loads of the first half may still be in flight into the registers the head overwrites, and it
+    // waits there for loads that were issued only one stage earlier.
+    int k0 = kbegin;
+    for (; k0 + T::BK < kend; k0 += 2 * T::BK) {
         gemm_stage<T, 0>(As, Bs, al, bl, acc, k0, kend, tid, wm0, wn0);
-        if (k0 + T::BK < kend)   // workgroup-uniform
-            gemm_stage<T, 1>(As, Bs, al, bl, acc, k0 + T::BK, kend, tid, wm0, wn0);
+        gemm_stage<T, 1>(As, Bs, al, bl, acc, k0 + T::BK, kend, tid, wm0, wn0);
     }
+    if (k0 < kend)   // workgroup-uniform
+        gemm_stage<T, 0>(As, Bs, al, bl, acc, k0, kend, tid, wm0, wn0);
 }
 
 // Sum of the `parts` partial accumulator tiles of one output tile, in index order (so the result
