@@ -348,7 +348,10 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         if (point && q.stride == 1) c.gather_cycles *= 0.1;
         // tap by tap over the [K][R][S][C] filter copy: one tap per stage, so the validity bit and
         // the distance are worked out per stage and not per element
-        if (cfg.layout == 2) c.gather_cycles *= mbn == 11 ? kTapMajorGather11 : (mbn == 21 ? kTapMajorGather21 : kTapMajorGather);
+        // (with a stride the lanes' addresses spread over twice the cache lines and the cost of
+        // the load is in the memory pipeline, which the cheaper addressing does not touch)
+        if (cfg.layout == 2 && q.stride == 1)
+            c.gather_cycles *= mbn == 11 ? kTapMajorGather11 : (mbn == 21 ? kTapMajorGather21 : kTapMajorGather);
         if (c.split_c1 == 0) c.split_c1 = 0.1;   // scratch tiles, as in the patch kernel
     }
     Shape s = conv_shape(q, cfg.algo, cfg.bn, std::max(2, cfg.cb));
