@@ -25,12 +25,12 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "8cbf03461fdb35f62ec13cedf52764989a8a3f575f1ef6be970ba9e0204ea7b8", "batch": 32, "fetch_bytes": 701217723, "write_bytes": 422691432}
+HBM_TRAFFIC = {"csrc_sha256": "10533b4e66c20f18ccb899a353ef2f0ff53a4ba03295cd9448cbc9a9b7335242", "batch": 32, "filters": "tap", "fetch_bytes": 454743694, "write_bytes": 354928104}
 
 
 # L2 fetch + write-back bytes of config 4 from two rocprofv3 --pmc runs of `bench.py --copy-probe --counter-pass
 # fusion` (same scaling as above): the fused launch, and the convolution + bias + activation launches it replaces.
-FUSION_TRAFFIC = {"csrc_sha256": "8cbf03461fdb35f62ec13cedf52764989a8a3f575f1ef6be970ba9e0204ea7b8", "fused_bytes": 120224697, "separate_bytes": 145994995}
+FUSION_TRAFFIC = {"csrc_sha256": "10533b4e66c20f18ccb899a353ef2f0ff53a4ba03295cd9448cbc9a9b7335242", "fused_bytes": 110016186, "separate_bytes": 135784468}
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
 
@@ -297,6 +297,7 @@ def main():
             t_pick = time.perf_counter()
             pcfg, prep = P.pick_conv2d(shape)
             t_pick = time.perf_counter() - t_pick
+            prep = P.model_conv2d(shape, P.TileCfg(**tile))     # the prediction for the variant that ran
             # ablation: what each part of the model would have picked alone, on the same timings --
             # equation (1) over the placed working sets; the data term (equation (1) weighted by the
             # bytes that move); the matrix-core term
@@ -314,7 +315,13 @@ def main():
             if os.path.exists(P.RANKER_PARAMS_PATH):
                 P.ranker_load()
                 t_learn = time.perf_counter()
-                lcfg, _, lwins, lgames = P.pick_conv2d_learned(shape)
+                if L["wt"] is None:
+                    lcfg, _, lwins, lgames = P.pick_conv2d_learned(shape)
+                else:
+                    # the same tournament over the candidates ranked with the filter copy
+                    lc = P.conv_candidates(shape, tap=True)
+                    w_l, order_l = P.ranker_tournament([P.ranker_stats_conv2d(shape, c) for c in lc])
+                    lcfg, lwins, lgames = lc[order_l[0]], w_l[order_l[0]], 2 * (len(lc) - 1)
                 t_learn = time.perf_counter() - t_learn
                 P.set_tile_override(lcfg)
                 run_layer(L)

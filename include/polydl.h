@@ -78,7 +78,8 @@ typedef struct polydl_tile_cfg {
                          2 (convolution, algo 0, split_k 1): order 0, and when the tile count
                          leaves a last round of workgroups that at most half of the compute units
                          take part in, each tile of that round is cut into parts along the
-                         reduction (summed through scratch tiles in a fixed order) */
+                         reduction (summed through scratch tiles in a fixed order);
+                         3: the same cut with the tiles in order 1 (what the picker ranks)   */
     int algo;         /* convolution only.  0: im2col columns gathered element by element from
                          HBM (any shape); 1: input rows staged once per workgroup in LDS and the
                          taps formed on the LDS read (bk is ignored, the stage is cb channels);

@@ -184,7 +184,7 @@ static int sgemm_impl(int M, int N, int K, float alpha, const float *A, const fl
     if ((uint64_t)v->bk * (uint64_t)N * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;
     if ((uint64_t)v->bm * (uint64_t)N * 4 >= 0x7FFFFFF0ull) return POLYDL_ERR_UNSUPPORTED;   // and of C (bm rows)
     uint64_t tiles = (uint64_t)((M + v->bm - 1) / v->bm) * (uint64_t)((N + v->bn - 1) / v->bn);
-    if (tiles >= 0x7FFFFFFFull || cfg.split_k > 65535 || cfg.raster == 2) return POLYDL_ERR_UNSUPPORTED;
+    if (tiles >= 0x7FFFFFFFull || cfg.split_k > 65535 || cfg.raster >= 2) return POLYDL_ERR_UNSUPPORTED;
     SgemmProblem q{M, N, K, A, B, C, alpha, beta};
     hipError_t e = v->sgemm(q, cfg.split_k < 1 ? 1 : cfg.split_k, cfg.raster, (hipStream_t)stream);
     if (e != hipSuccess) return launch_failed(e);
@@ -837,7 +837,7 @@ int polydl_set_tile_override(const polydl_tile_cfg *cfg)
                                                         : (cfg->algo == 0 && find_variant(*cfg) != nullptr));
     if (!known || cfg->split_k < 1 || cfg->layout < 0 || cfg->layout > 2 || (cfg->layout == 2 && cfg->algo != 0) ||
         cfg->raster < 0 ||
-        cfg->raster > 2 || (cfg->raster == 2 && cfg->algo != 0) || cfg->cb < 0 || (cfg->cb & 1))
+        cfg->raster > 3 || (cfg->raster >= 2 && cfg->algo != 0) || cfg->cb < 0 || (cfg->cb & 1))
         return POLYDL_ERR_UNSUPPORTED;
     g_override = *cfg;
     g_have_override = true;

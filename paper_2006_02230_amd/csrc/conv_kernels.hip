@@ -357,8 +357,8 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
     int stages_per = (stages + split_k - 1) / split_k;
     a.k_per_split = stages_per * T::BK;
     a.split_k = (stages + stages_per - 1) / stages_per;
-    const bool tail = raster == 2;   // tile order of raster 0, leftover tiles split
-    a.raster = tail ? 0 : raster;
+    const bool tail = raster >= 2;   // rasters 2 and 3: tile order of raster 0 and 1, leftover tiles split
+    a.raster = raster & 1;
     a.act = q.act;
     a.pre_act = q.pre_act;
     a.partials = nullptr;
@@ -372,7 +372,7 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
         hipError_t e = splitk_scratch(stream, q.arena, bytes, tiles, &a.partials, &a.counters);
         if (e != hipSuccess) return e;
     } else {
-        // raster 2: an unsplit grid whose last round would leave most compute units idle has the
+        // rasters 2, 3: an unsplit grid whose last round would leave most compute units idle has the
         // tiles of that round split
         const TailSplit ts = tail ? tail_split(tiles, stages, compute_units()) : TailSplit{0, 1, stages};
         if (ts.parts > 1) {

@@ -152,8 +152,9 @@ def test_resnet_suite_batch64_full_size(P, layer):
 
 @pytest.mark.parametrize("layer", [0, 2, 4, 7])
 def test_leftover_tile_split_full_size(P, layer):
-    # raster 2 at full size on the layers where the picker ranks it (batch 32 and 64): the whole
-    # tiles and the tiles cut along the reduction, every output
+    # raster 3 (what the picker ranks: leftover tiles cut, XCD-aware order) at full size on the layers
+    # where it is ranked (batch 32 and 64): the whole tiles and the tiles cut along the reduction,
+    # every output
     for N in (32, 64):
         s = synth.RESNET50_SUITE(N)[layer]
         x, w, b = synth.conv_inputs(s, seed=100 + layer, dist="normal", bias=True)
@@ -161,7 +162,7 @@ def test_leftover_tile_split_full_size(P, layer):
         for v in P.variants(0):
             if v.algo != 0 or v.wm * v.wn > 64 * 32:
                 continue
-            v.raster, v.split_k = 2, 1
+            v.raster, v.split_k = 3, 1
             got = try_variant(P, v, s, x, w, b, act="relu")
             if got is None:
                 continue
@@ -296,7 +297,7 @@ LEFTOVER = [
 
 @pytest.mark.parametrize("s", LEFTOVER, ids=lambda s: s.name)
 def test_leftover_tiles_split(P, s):
-    # raster 2: the tiles beyond the last full round of the compute units are cut along the reduction
+    # rasters 2 and 3: the tiles beyond the last full round of the compute units are cut along the reduction
     x, w, b = synth.conv_inputs(s, seed=43, dist="normal", bias=True)
     want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
     xi, wi, bi = synth.conv_inputs(s, seed=44, dist="ints", bias=True)
@@ -305,15 +306,16 @@ def test_leftover_tiles_split(P, s):
     for v in P.variants(0):
         if v.algo != 0:
             continue
-        v.raster, v.split_k = 2, 1
-        got = try_variant(P, v, s, x, w, b, act="relu")
-        if got is None:
-            continue
-        assert oracle.scaled_error(got, want, ab) <= FP32_TOL, v
-        assert np.array_equal(try_variant(P, v, s, x, w, b, act="relu"), got), v     # fixed summation order
-        got_i = try_variant(P, v, s, xi, wi, bi)
-        assert np.array_equal(got_i.astype(np.float64), want_i), v
-        ran += 1
+        for raster in (2, 3):       # the leftover tiles cut, tiles dealt in plain and in XCD-aware order
+            v.raster, v.split_k = raster, 1
+            got = try_variant(P, v, s, x, w, b, act="relu")
+            if got is None:
+                continue
+            assert oracle.scaled_error(got, want, ab) <= FP32_TOL, v
+            assert np.array_equal(try_variant(P, v, s, x, w, b, act="relu"), got), v     # fixed summation order
+            got_i = try_variant(P, v, s, xi, wi, bi)
+            assert np.array_equal(got_i.astype(np.float64), want_i), v
+            ran += 1
     assert ran > 0
     P.set_tile_override(None)
 

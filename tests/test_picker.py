@@ -138,6 +138,12 @@ def test_leftover_tiles_in_the_model():
     # a grid of less than one round is the split factor's business: left alone
     shape_most = (4, 64, 56, 56, 64, 3, 3, 1, 1)      # 196 tiles
     assert P.model_conv2d(shape_most, cut).predicted_us == pytest.approx(P.model_conv2d(shape_most, plain).predicted_us)
+    # the order in which the tiles are dealt to the XCDs (rasters 1 and 3) does not enter the prediction
+    plain1, cut1 = P.TileCfg(64, 64, 16, 32, 32, 1, 0, 1, 0, 0), P.TileCfg(64, 64, 16, 32, 32, 1, 0, 3, 0, 0)
+    assert P.model_conv2d(shape, plain1).predicted_us == pytest.approx(P.model_conv2d(shape, plain).predicted_us)
+    assert P.model_conv2d(shape, cut1).predicted_us == pytest.approx(P.model_conv2d(shape, cut).predicted_us)
+    # and the gather candidates the picker ranks are all in the XCD-aware order
+    assert all(c.raster in (1, 3) for c in P.conv_candidates(shape) if c.algo == 0)
 
 
 def test_bf16_pick_is_a_compiled_variant_and_the_model_agrees():

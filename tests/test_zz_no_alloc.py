@@ -48,7 +48,7 @@ def test_two_calls_share_the_fixed_scratch(P):
     for s, seed in ((big, 91), (small, 92)):
         x, w, b = synth.conv_inputs(s, seed=seed, dist="normal", bias=True)
         ref, got, tile = both(P, s, x, w, b, "relu")
-        assert tile["split_k"] > 1 or tile["raster"] == 2, tile
+        assert tile["split_k"] > 1 or tile["raster"] >= 2, tile
         assert np.array_equal(got, ref), (s.name, tile)
         want, ab = oracle.conv2d_fwd(x, w, bias=b, stride=s.stride, pad=s.pad, act="relu")
         assert oracle.scaled_error(got, want, ab) <= FP32_TOL, (s.name, tile)
