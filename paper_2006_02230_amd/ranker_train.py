@@ -237,7 +237,8 @@ def write_report(res, path, command, note=""):
         if c["algo"] == 1:
             return "patch %dx%d/%dx%d cb %d split %d" % (c["bm"], c["bn"], c["wm"], c["wn"], c["cb"], c["split_k"])
         return "gather %dx%dx%d/%dx%d split %d%s" % (c["bm"], c["bn"], c["bk"], c["wm"], c["wn"], c["split_k"],
-                                                     " tail" if c["raster"] == 2 else "")
+                                                     (" tail" if c["raster"] >= 2 else "") +
+                                                     (" tap" if c["layout"] == 2 else ""))
     o = ["# Learned ranking (pairwise network + tournament) against the sweep: fp32 convolution suite\n",
          "Commands (the sweeps on the MI355X, the rest on the host):\n", command, ""]
     o.append("Pairs of variants of one problem more than 1 %% apart, ordered correctly by the network: "
