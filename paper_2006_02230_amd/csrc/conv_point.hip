@@ -39,20 +39,120 @@ __device__ __forceinline__ v2f buf_load2(__amdgpu_buffer_rsrc_t r, uint32_t byte
     return __builtin_bit_cast(v2f, v);
 }
 
+// What a finished unit leaves behind until it is stored: its two accumulator blocks, the lane's 16
+// bias values of its channel group, the lane's output offset and the group's first channel.
+struct PointUnit {
+    v16f acc[2];
+    v4f bias[4];
+    uint32_t vo;
+    int k0;
+};
+
+// Stores first .. first + count - 1 (of 16) of a finished unit: accumulator registers 4q .. 4q+3 are
+// four consecutive channels, the lane's two pixels of a channel row go out as one 8-byte store.
+// Called from fully unrolled loops only, so every index is a constant.
 template <int ACT>
-__device__ __forceinline__ void point_store(__amdgpu_buffer_rsrc_t ro, uint32_t vo, uint32_t row_bytes, int k0,
-                                            const v4f (&bias)[4], const v16f (&acc)[2])
+__device__ __forceinline__ void point_store(__amdgpu_buffer_rsrc_t ro, uint32_t row_bytes, const PointUnit &u,
+                                            int first, int count)
 {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        // accumulator registers 4q .. 4q+3 are four consecutive channels
-        const int kq = k0 + 8 * q;
+    for (int r = first; r < first + count; ++r) {
+        const int q = r >> 2, i = r & 3;
+        v2f v = {act_of<ACT>(u.acc[0][r] + u.bias[q][i]), act_of<ACT>(u.acc[1][r] + u.bias[q][i])};
+        buf_store2(ro, u.vo, (uint32_t)(u.k0 + 8 * q + i) * row_bytes, v);
+    }
+}
+
+// The products of one unit into `cur` and, PENDING, the 16 stores of the unit finished before it
+// (`old`) dealt out between the groups of eight matrix instructions: a wave's stores leave while
+// its own next matrix instructions run instead of after them, in a phase of their own in which
+// the matrix core of the SIMD has nothing to do unless another wave happens to be out of step.
+template <int C8, int ACT, bool PENDING>
+__device__ __forceinline__ void point_unit(const v4f *a_base, int K, const v2f (&b)[C8 * 4], PointUnit &cur,
+                                           __amdgpu_buffer_rsrc_t ro, uint32_t row_bytes, const PointUnit &old)
+{
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cur.acc[nb][r] = 0.f;
+    constexpr int PER = 16 / C8;   // stores per group of eight matrix instructions
+#pragma unroll
+    for (int sg = 0; sg < C8; ++sg) {
+        const v4f a = a_base[sg * 2 * K];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = 4 * q + i;
-            v2f v = {act_of<ACT>(acc[0][r] + bias[q][i]), act_of<ACT>(acc[1][r] + bias[q][i])};
-            buf_store2(ro, vo, (uint32_t)(kq + i) * row_bytes, v);
+            cur.acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].x, cur.acc[0], 0, 0, 0);
+            cur.acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].y, cur.acc[1], 0, 0, 0);
         }
+        if constexpr (PENDING) {
+            point_store<ACT>(ro, row_bytes, old, sg * PER, PER);
+            // keep the stores where they are: left alone, the scheduler moves them all behind the
+            // last matrix instruction
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// A wave's run of units [u, end).  Two unit records take turns: while one collects the products of
+// unit i, the other, holding unit i - 1, is stored.
+template <int C8, int ACT>
+__device__ __forceinline__ void point_run(const ConvPointKArgs &p, const v4f *At, uint32_t u, uint32_t end, int half, int j)
+{
+    const int K = p.K, C = C8 * 8;
+    const uint32_t HW = p.HW, total = (uint32_t)p.N * HW;
+    const __amdgpu_buffer_rsrc_t ri = make_rsrc(p.in, (uint64_t)total * C * 4);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc(p.out, (uint64_t)total * K * 4);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (uint64_t)K * 4 : 0);
+    const uint32_t row_bytes = HW * 4u;
+
+    uint32_t g;
+    uint32_t tile = div_by(u, (uint32_t)p.groups, p.recip_groups, g);
+    uint32_t have = 0xFFFFFFFFu, vo = kOobOffset;
+    v2f b[C8 * 4];
+    // pixels of a new tile, the unit's output offset and channel group, its bias values (zeros
+    // without a bias; they are needed only when the unit is stored, one unit later)
+    auto open_unit = [&](PointUnit &cur) {
+        if (tile != have) {
+            // the lane's two pixels: 2j and 2j+1 of the tile, in one image since H*W is even
+            const uint32_t pix0 = tile * 64u + 2u * j;
+            uint32_t x;
+            const uint32_t n = div_by(pix0, HW, p.recip_HW, x);
+            const bool ok = pix0 < total;
+            const uint32_t vi = ok ? ((n * C + half) * HW + x) * 4u : kOobOffset;
+            vo = ok ? ((n * K + 4u * half) * HW + x) * 4u : kOobOffset;
+#pragma unroll
+            for (int s = 0; s < C8 * 4; ++s) b[s] = buf_load2(ri, vi, (uint32_t)(2 * s) * row_bytes);
+            have = tile;
+        }
+        cur.vo = vo;
+        cur.k0 = (int)g * 32;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cur.bias[q] = buf_load4(rb, (uint32_t)(g * 32 + 8 * q + 4 * half) * 4u);
+    };
+    auto next_unit = [&]() {
+        if (++g == (uint32_t)p.groups) { g = 0; ++tile; }
+    };
+    PointUnit A, B;
+    uint32_t left = end - u;
+    open_unit(A);
+    point_unit<C8, ACT, false>(At + half * K + g * 32 + j, K, b, A, ro, row_bytes, A);
+    next_unit();
+    --left;
+    while (left >= 2) {
+        open_unit(B);
+        point_unit<C8, ACT, true>(At + half * K + g * 32 + j, K, b, B, ro, row_bytes, A);
+        next_unit();
+        open_unit(A);
+        point_unit<C8, ACT, true>(At + half * K + g * 32 + j, K, b, A, ro, row_bytes, B);
+        next_unit();
+        left -= 2;
+    }
+    if (left == 1) {
+        open_unit(B);
+        point_unit<C8, ACT, true>(At + half * K + g * 32 + j, K, b, B, ro, row_bytes, A);
+        point_store<ACT>(ro, row_bytes, B, 0, 16);
+    } else {
+        point_store<ACT>(ro, row_bytes, A, 0, 16);
     }
 }
 
@@ -87,65 +187,12 @@ __global__ __launch_bounds__(256, 2) void conv_point_kernel(const ConvPointKArgs
     __syncthreads();
 
     const uint32_t w = blockIdx.x * 4u + wave;
-    uint32_t u = w * p.per + (w < p.rem ? w : p.rem);
+    const uint32_t u = w * p.per + (w < p.rem ? w : p.rem);
     const uint32_t end = u + p.per + (w < p.rem ? 1u : 0u);
     if (u >= end) return;
-
-    const uint32_t HW = p.HW, total = (uint32_t)p.N * HW;
-    const __amdgpu_buffer_rsrc_t ri = make_rsrc(p.in, (uint64_t)total * C * 4);
-    const __amdgpu_buffer_rsrc_t ro = make_rsrc(p.out, (uint64_t)total * K * 4);
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (uint64_t)K * 4 : 0);
-    const uint32_t row_bytes = HW * 4u;
-
-    uint32_t g;
-    uint32_t tile = div_by(u, (uint32_t)p.groups, p.recip_groups, g);
-    uint32_t have = 0xFFFFFFFFu, vo = kOobOffset;
-    v2f b[C8 * 4];
-    // the lane's 16 bias values of a channel group (zeros without a bias)
-    v4f bias[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) bias[q] = buf_load4(rb, (uint32_t)(g * 32 + 8 * q + 4 * half) * 4u);
-    for (; u < end; ++u) {
-        if (tile != have) {
-            // the lane's two pixels: 2j and 2j+1 of the tile, in one image since H*W is even
-            const uint32_t pix0 = tile * 64u + 2u * j;
-            uint32_t x;
-            const uint32_t n = div_by(pix0, HW, p.recip_HW, x);
-            const bool ok = pix0 < total;
-            const uint32_t vi = ok ? ((n * C + half) * HW + x) * 4u : kOobOffset;
-            vo = ok ? ((n * K + 4u * half) * HW + x) * 4u : kOobOffset;
-#pragma unroll
-            for (int s = 0; s < C8 * 4; ++s) b[s] = buf_load2(ri, vi, (uint32_t)(2 * s) * row_bytes);
-            have = tile;
-        }
-        // the next unit's bias values travel while this unit's products are formed
-        const uint32_t gn = g + 1 == (uint32_t)p.groups ? 0u : g + 1;
-        v4f bias_next[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) bias_next[q] = buf_load4(rb, (uint32_t)(gn * 32 + 8 * q + 4 * half) * 4u);
-        v16f acc[2];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
-        const v4f *a_base = At + half * K + g * 32 + j;
-#pragma unroll
-        for (int sg = 0; sg < C8; ++sg) {
-            const v4f a = a_base[sg * 2 * K];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].x, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[4 * sg + i].y, acc[1], 0, 0, 0);
-            }
-        }
-        const int k0 = (int)g * 32;
-        if (p.act == POLYDL_ACT_NONE) point_store<POLYDL_ACT_NONE>(ro, vo, row_bytes, k0, bias, acc);
-        else if (p.act == POLYDL_ACT_RELU) point_store<POLYDL_ACT_RELU>(ro, vo, row_bytes, k0, bias, acc);
-        else point_store<POLYDL_ACT_RELU6>(ro, vo, row_bytes, k0, bias, acc);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) bias[q] = bias_next[q];
-        if (++g == (uint32_t)p.groups) { g = 0; ++tile; }
-    }
+    if (p.act == POLYDL_ACT_NONE) point_run<C8, POLYDL_ACT_NONE>(p, At, u, end, half, j);
+    else if (p.act == POLYDL_ACT_RELU) point_run<C8, POLYDL_ACT_RELU>(p, At, u, end, half, j);
+    else point_run<C8, POLYDL_ACT_RELU6>(p, At, u, end, half, j);
 }
 
 bool conv_point_fits(const ConvProblem &q)
