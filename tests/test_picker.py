@@ -268,3 +268,27 @@ def test_candidate_lists_come_from_the_library():
     bf = P.conv_candidates_bf16(shape)
     pick, _ = P.pick_conv2d_bf16(shape)
     assert bf and tuple(pick.as_dict().values()) in {tuple(c.as_dict().values()) for c in bf}
+
+
+def test_candidates_with_the_filter_copy():
+    # kind 3 of polydl_conv2d_candidates: gather variants walk the [K][R][S][C] copy tap by tap (tile
+    # layout 2) exactly where that applies -- 2..63 taps and a channel count that is a multiple of
+    # the variant's stage depth -- and nothing else changes
+    def gather(shape, tap):
+        return [c for c in P.conv_candidates(shape, tap=tap) if c.algo == 0]
+    s33 = (32, 128, 28, 28, 128, 3, 3, 1, 1)
+    assert all(c.layout == 0 for c in gather(s33, False))
+    assert all(c.layout == 2 for c in gather(s33, True))
+    assert len(P.conv_candidates(s33, tap=True)) == len(P.conv_candidates(s33))
+    # 24 channels: a multiple of 8 but not of 16, so only the variant with stage depth 8 can
+    c24 = gather((8, 24, 14, 14, 64, 3, 3, 1, 1), True)
+    assert {c.layout for c in c24 if c.bk == 8} == {2} and {c.layout for c in c24 if c.bk == 16} == {0}
+    for shape in ((32, 3, 224, 224, 64, 7, 7, 2, 3),        # three channels
+                  (32, 64, 56, 56, 64, 1, 1, 1, 0),          # one tap
+                  (4, 16, 20, 20, 16, 8, 8, 1, 0)):          # 64 taps
+        assert all(c.layout == 0 for c in gather(shape, True)), shape
+    # the cheaper gather is priced for stride 1 only
+    t0, t2 = P.TileCfg(64, 64, 16, 32, 32, 1, 0, 1, 0, 0), P.TileCfg(64, 64, 16, 32, 32, 1, 2, 1, 0, 0)
+    assert P.model_conv2d(s33, t2).predicted_us < P.model_conv2d(s33, t0).predicted_us
+    s2 = (32, 128, 56, 56, 128, 3, 3, 2, 1)
+    assert P.model_conv2d(s2, t2).predicted_us == pytest.approx(P.model_conv2d(s2, t0).predicted_us)
