@@ -17,7 +17,7 @@
  *     nothing is enqueued and no output byte is written;
  *   - tensors are dense, contiguous float32 unless stated; input and output must not overlap;
  *   - memory of its own: a convolution or matrix product whose reduction is split over
- *     several workgroups (split_k > 1, or the leftover tiles of raster 2) keeps partial tiles
+ *     several workgroups (split_k > 1, or the leftover tiles of rasters 2 and 3) keeps partial tiles
  *     and arrival counters in a device buffer the library allocates with hipMalloc on first
  *     need, one per (device, stream), and keeps until the process ends.  When a later problem
  *     needs more, a larger buffer is allocated (this waits for the device) and the smaller one is
