@@ -74,14 +74,25 @@ __device__ __forceinline__ uint32_t outside_bits(int lo, int hi, int n)
 //               stage shares one tap: its validity bit and its distance are found once per stage,
 //               not per element, and the channel rides in the uniform offset.  In that copy the
 //               filter rows are contiguous in the walked order, so they load as in a plain GEMM.
-enum { GATHER_ANY = 0, GATHER_POINT = 1, GATHER_TAPS1 = 2, GATHER_TAPS2 = 3, GATHER_TAPMAJOR = 4 };
+//  GATHER_TABLE  filters of at most 63 taps with a short reduction (C*R*S + 2 stages at most kTableRows
+//               rows; the stem layer): as GATHER_TAPS2, but the (c, r, s) split of a reduction row is
+//               not redone by every wave for every element.  The workgroup writes (distance of the
+//               row's tap and channel in bytes, tap number) of every row into LDS once; a load then
+//               reads its row's entry (one address per stage, constant offsets), adds the distance
+//               to the lane's offset and shifts the lane's 64 tap bits by the tap number.  Same
+//               vector instructions per element as GATHER_TAPS2, a tenth of its scalar ones: the one
+//               scalar unit of a compute unit serves four SIMDs, and at 18 scalar instructions per
+//               matrix instruction (the stem layer) it, not the matrix cores, set the pace.
+enum { GATHER_ANY = 0, GATHER_POINT = 1, GATHER_TAPS1 = 2, GATHER_TAPS2 = 3, GATHER_TAPMAJOR = 4, GATHER_TABLE = 5 };
+constexpr int kTableRows = 512;   // 4 KB of LDS
 
 
 template <class T, int MODE>
 struct BLoaderIm2col {
     static constexpr bool POINT = MODE == GATHER_POINT;
     static constexpr bool TAPMAJOR = MODE == GATHER_TAPMAJOR;
-    static constexpr bool TAPS = MODE == GATHER_TAPS1 || MODE == GATHER_TAPS2 || TAPMAJOR;
+    static constexpr bool TABLE = MODE == GATHER_TABLE;
+    static constexpr bool TAPS = MODE == GATHER_TAPS1 || MODE == GATHER_TAPS2 || TAPMAJOR || TABLE;
     static constexpr int LAST_BIT = MODE == GATHER_TAPS1 ? 31 : 63;   // never a tap: always set
     static constexpr int KSTEP = T::NT / T::BN;  // reduction rows covered by one pass of the workgroup
     static constexpr int ITERS = T::BK / KSTEP;
@@ -93,6 +104,26 @@ struct BLoaderIm2col {
     int krow0, lds_off;
     int RS, S, HW, W, pre_act, C;
     uint32_t magic_RS, magic_S, one_RS, one_S, magic_C;
+    const uint2 *tab;   // GATHER_TABLE: per reduction row (byte distance, tap number), in LDS
+
+    // GATHER_TABLE: the workgroup fills the table (rows at or past the end of the reduction get the
+    // bit that is always set); the caller puts a barrier between this and the first load.
+    __device__ __forceinline__ void fill_table(const ConvKArgs &p, int tid, uint2 *t)
+    {
+        tab = t;
+        if constexpr (TABLE) {
+            for (int kg = tid; kg < kTableRows; kg += T::NT) {
+                uint2 e = {0u, (uint32_t)LAST_BIT};
+                if (kg < p.Kg) {
+                    const uint32_t c = fast_div((uint32_t)kg, p.magic_RS, p.one_RS), rs = (uint32_t)kg - c * (uint32_t)p.RS;
+                    const uint32_t r = fast_div(rs, p.magic_S, p.one_S), sx = rs - r * (uint32_t)p.S;
+                    e.x = (c * (uint32_t)p.HW + r * (uint32_t)p.W + sx) * 4u;
+                    e.y = rs;
+                }
+                t[kg] = e;
+            }
+        }
+    }
 
     __device__ __forceinline__ void init(const ConvKArgs &p, int tid, int n0)
     {
@@ -170,6 +201,20 @@ struct BLoaderIm2col {
             }
             return;
         }
+        if constexpr (TABLE) {
+            // one LDS address per stage; the rows of this thread lie KSTEP entries apart.  Rows at or
+            // past kend are either past the reduction's end (entry: always outside) or belong to a
+            // look-ahead stage of a split reduction, whose values are never multiplied.
+            const uint2 *row = tab + (k0 + krow0);
+            const uint64_t taps = ((uint64_t)smask << 32) | rmask;
+#pragma unroll
+            for (int i = 0; i < ITERS; ++i) {
+                const uint2 e = row[i * KSTEP];
+                const uint32_t outside = (uint32_t)(taps >> e.y);      // bit 0 counts: the shift below drops the rest
+                regs[SET][i] = buf_load1(rsrc, ((uint32_t)pix_off + e.x) | (outside << 31));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
             uint32_t kg = (uint32_t)(k0 + krow0 + i * KSTEP);  // wave-uniform
@@ -242,8 +287,11 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
 
     ALoader<T, AVEC> al;
     BLoaderIm2col<T, MODE> bl;
+    __shared__ uint2 ktab[MODE == GATHER_TABLE ? kTableRows : 1];
+    bl.fill_table(p, tid, ktab);
     al.init(p.wt, tid, m0, p.K, p.Kg, p.Kg);
     bl.init(p, tid, n0);
+    if constexpr (MODE == GATHER_TABLE) __syncthreads();
 
     v16f acc[T::MB][T::NB];
 #pragma unroll
@@ -391,19 +439,25 @@ static hipError_t conv_launch(const ConvProblem &q, int split_k, int raster, hip
         if (!gather_tap_major_fits(q, T::BK) || ((uintptr_t)q.wt_tap & 15)) return hipErrorInvalidValue;
         a.wt = q.wt_tap;
     }
+    // the table covers every row a load can ask for: the reduction rounded up to whole stages and the
+    // two stages the loads run ahead
+    const bool table = a.RS <= 63 && (stages + 2) * T::BK <= kTableRows;
     const int mode = (q.R == 1 && q.S == 1 && q.pad == 0) ? GATHER_POINT
                      : tapmajor ? GATHER_TAPMAJOR
+                     : table ? GATHER_TABLE
                      : a.RS <= 31 ? GATHER_TAPS1 : a.RS <= 63 ? GATHER_TAPS2 : GATHER_ANY;
 #define POLYDL_GO(AV, MODE) le = launch_kernel((conv_kernel<T, AV, MODE>), grid, block, 0, stream, a)
     if (mode == GATHER_TAPMAJOR) {
         POLYDL_GO(4, GATHER_TAPMAJOR);
     } else if (avec) {
         if (mode == GATHER_POINT) POLYDL_GO(4, GATHER_POINT);
+        else if (mode == GATHER_TABLE) POLYDL_GO(4, GATHER_TABLE);
         else if (mode == GATHER_TAPS1) POLYDL_GO(4, GATHER_TAPS1);
         else if (mode == GATHER_TAPS2) POLYDL_GO(4, GATHER_TAPS2);
         else POLYDL_GO(4, GATHER_ANY);
     } else {
         if (mode == GATHER_POINT) POLYDL_GO(1, GATHER_POINT);
+        else if (mode == GATHER_TABLE) POLYDL_GO(1, GATHER_TABLE);
         else if (mode == GATHER_TAPS1) POLYDL_GO(1, GATHER_TAPS1);
         else if (mode == GATHER_TAPS2) POLYDL_GO(1, GATHER_TAPS2);
         else POLYDL_GO(1, GATHER_ANY);
