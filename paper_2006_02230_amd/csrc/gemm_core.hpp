@@ -239,13 +239,17 @@ struct BLoaderRows {
 };
 
 // ---- the MFMA stage: consume one LDS stage, WM x WN x BK per wave ----------------------------
+// krem: reduction rows of this stage that exist (the last stage of a reduction may be short; its
+// other rows are zeros in A).  A chunk of eight rows that lies wholly past the end is skipped
+// (uniform branch): the stem layer's reduction of 147 ends three rows into its tenth stage.
 template <class T>
 __device__ __forceinline__ void mma_stage(const float *__restrict__ As, const float *__restrict__ Bs,
-                                          v16f (&acc)[T::MB][T::NB], int wm0, int wn0, int lane)
+                                          v16f (&acc)[T::MB][T::NB], int wm0, int wn0, int lane, int krem)
 {
     const int li = lane & 31, lh = lane >> 5;
 #pragma unroll
     for (int kc = 0; kc < T::BK / 8; ++kc) {
+        if (kc > 0 && kc * 8 >= krem) break;
         v4f a[T::MB];
 #pragma unroll
         for (int bi = 0; bi < T::MB; ++bi)
@@ -287,7 +291,7 @@ __device__ __forceinline__ void gemm_stage(float *As, float *Bs, AL &al, BL &bl,
     // register set HALF is free (its stage is in LDS buffer HALF): fetch stage k + 2*BK into it
     al.template load<HALF>(k + 2 * T::BK, kend);
     bl.template load<HALF>(k + 2 * T::BK, kend);
-    mma_stage<T>(As + HALF * T::A_STAGE, Bs + HALF * T::B_STAGE, acc, wm0, wn0, tid & 63);
+    mma_stage<T>(As + HALF * T::A_STAGE, Bs + HALF * T::B_STAGE, acc, wm0, wn0, tid & 63, kend - k);
     // stage k + BK sits in the other set: copy it to the other LDS buffer
     al.template store<HALF ^ 1>(As + (HALF ^ 1) * T::A_STAGE, tid);
     bl.template store<HALF ^ 1>(Bs + (HALF ^ 1) * T::B_STAGE, tid);
