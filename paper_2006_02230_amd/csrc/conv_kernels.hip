@@ -285,7 +285,9 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
     const int kbegin = part * kps;
     const int kend = min(p.Kg, kbegin + kps);
 
-    ALoader<T, AVEC> al;
+    // AVEC = 1 stands for filter rows that are not a multiple of four floats long or not 16-byte
+    // aligned: vector loads all the same, with the reduction's tail masked
+    ALoader<T, 4, AVEC == 1> al;
     BLoaderIm2col<T, MODE> bl;
     __shared__ uint2 ktab[MODE == GATHER_TABLE ? kTableRows : 1];
     bl.fill_table(p, tid, ktab);

@@ -109,8 +109,12 @@ struct Tile {
 // ---- A operand: row-major [Mg][lda], reduction index contiguous ------------------------------
 // VEC = 4: 128-bit loads (needs lda % 4 == 0 and a 16-byte aligned base); VEC = 1: dword loads.
 // The descriptor is rebuilt per stage at A + m0*lda + k0, so offsets stay below BM*lda*4 bytes.
-template <class T, int VEC>
+// KTAIL (VEC = 4 only): rows need not be a multiple of four long nor 16-byte aligned -- buffer loads
+// of four dwords only need dword alignment -- so a vector may reach past the end of the reduction
+// into the next row; in the (one) stage where that can happen those components are zeroed.
+template <class T, int VEC, bool KTAIL = false>
 struct ALoader {
+    static_assert(!KTAIL || VEC == 4, "the tail form is for vector loads");
     static constexpr int UNITS = T::BM * T::BK / VEC;  // load units in one stage
     static constexpr int ITERS = (UNITS + T::NT - 1) / T::NT;
     static constexpr int UPR = T::BK / VEC;            // units per tile row
@@ -152,6 +156,15 @@ struct ALoader {
                 regs[SET][4 * i] = v.x; regs[SET][4 * i + 1] = v.y; regs[SET][4 * i + 2] = v.z; regs[SET][4 * i + 3] = v.w;
             } else {
                 regs[SET][i] = buf_load1(rsrc, off);
+            }
+        }
+        if constexpr (KTAIL) {
+            if (krem < T::BK) {   // uniform: the stage the reduction ends in
+#pragma unroll
+                for (int i = 0; i < ITERS; ++i)
+#pragma unroll
+                    for (int j = 1; j < 4; ++j)
+                        if (kcol[i] + j >= krem) regs[SET][4 * i + j] = 0.f;
             }
         }
     }
