@@ -112,7 +112,10 @@ struct BLoaderIm2col {
     {
         tab = t;
         if constexpr (TABLE) {
-            for (int kg = tid; kg < kTableRows; kg += T::NT) {
+            // every row a load can ask for: the reduction rounded up to whole stages and the two
+            // stages the loads run ahead (the launcher checked that the table holds them)
+            const int rows = ((p.Kg + T::BK - 1) / T::BK + 2) * T::BK;
+            for (int kg = tid; kg < rows; kg += T::NT) {
                 uint2 e = {0u, (uint32_t)LAST_BIT};
                 if (kg < p.Kg) {
                     const uint32_t c = fast_div((uint32_t)kg, p.magic_RS, p.one_RS), rs = (uint32_t)kg - c * (uint32_t)p.RS;
