@@ -25,12 +25,12 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "9f671eb1932ed074cd0e540559a39de8c4f21b23f055721226c6f020087a7aae", "batch": 32, "filters": "tap", "fetch_bytes": 448890922, "write_bytes": 354881464}
+HBM_TRAFFIC = {"csrc_sha256": "7267b0b2bca3268c6e71b1ecd68fbd55605ca73720b03a8f83bc4cff8707216c", "batch": 32, "filters": "tap", "fetch_bytes": 450714141, "write_bytes": 355277520}
 
 
 # L2 fetch + write-back bytes of config 4 from two rocprofv3 --pmc runs of `bench.py --copy-probe --counter-pass
 # fusion` (same scaling as above): the fused launch, and the convolution + bias + activation launches it replaces.
-FUSION_TRAFFIC = {"csrc_sha256": "9f671eb1932ed074cd0e540559a39de8c4f21b23f055721226c6f020087a7aae", "fused_bytes": 110019309, "separate_bytes": 135802842}
+FUSION_TRAFFIC = {"csrc_sha256": "7267b0b2bca3268c6e71b1ecd68fbd55605ca73720b03a8f83bc4cff8707216c", "fused_bytes": 109954043, "separate_bytes": 135729005}
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
 
