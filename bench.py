@@ -25,12 +25,12 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "7267b0b2bca3268c6e71b1ecd68fbd55605ca73720b03a8f83bc4cff8707216c", "batch": 32, "filters": "tap", "fetch_bytes": 450714141, "write_bytes": 355277520}
+HBM_TRAFFIC = {"csrc_sha256": "1d5ea90dbccbcddc2293f2fa9bc13fbc58e9b49c1dd3708c204f0a080b286606", "batch": 32, "filters": "tap", "fetch_bytes": 449837446, "write_bytes": 355190112}
 
 
 # L2 fetch + write-back bytes of config 4 from two rocprofv3 --pmc runs of `bench.py --copy-probe --counter-pass
 # fusion` (same scaling as above): the fused launch, and the convolution + bias + activation launches it replaces.
-FUSION_TRAFFIC = {"csrc_sha256": "7267b0b2bca3268c6e71b1ecd68fbd55605ca73720b03a8f83bc4cff8707216c", "fused_bytes": 109954043, "separate_bytes": 135729005}
+FUSION_TRAFFIC = {"csrc_sha256": "1d5ea90dbccbcddc2293f2fa9bc13fbc58e9b49c1dd3708c204f0a080b286606", "fused_bytes": 109946383, "separate_bytes": 135714774}
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
 
@@ -92,8 +92,8 @@ def main():
     ap.add_argument("--filters", default="tap", choices=["tap", "kcrs"],
                     help="'tap': every layer's filter is also given as its [K][R][S][C] copy, made once before "
                          "the timed region (polydl_conv2d_fwd_tap); 'kcrs': KCRS only (polydl_conv2d_fwd_act)")
-    ap.add_argument("--suite", default="resnet", choices=["resnet", "heldout", "heldout2"],
-                    help="'heldout', 'heldout2': two sets of fourteen other CNN layer shapes (pick quality off the "
+    ap.add_argument("--suite", default="resnet", choices=["resnet", "heldout", "heldout2", "heldout3"],
+                    help="'heldout', 'heldout2', 'heldout3': three sets of fourteen other CNN layer shapes (pick quality off the "
                          "fitting set; not the headline workload)")
     ap.add_argument("--sweep-out", default="", help="with --sweep: write every candidate's time to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -160,7 +160,7 @@ def main():
         return
 
     suite = (synth.RESNET50_SUITE(args.batch) if args.suite == "resnet"
-             else synth.HELDOUT_SUITE(args.batch, 1 if args.suite == "heldout" else 2))
+             else synth.HELDOUT_SUITE(args.batch, {"heldout": 1, "heldout2": 2, "heldout3": 3}[args.suite]))
     if args.suite != "resnet":
         args.no_bf16 = args.no_fusion = args.no_sgemm = True
     chosen = [int(t) for t in args.layers.split(",") if t != ""] or list(range(len(suite)))

@@ -333,9 +333,9 @@ void model_conv(const ConvProblem &q, const polydl_tile_cfg &cfg, int threads, i
         c.kernel_fixed_us = 5.0;
         c.gather_elems = (double)cfg.bk * cfg.bn / threads;
         switch (mbn) {
-        case 11: c.regs = 62;  c.eff_sat = 0.85; c.t_lat_us = 0.6; c.t_round_us = 2; c.gather_cycles = 32; break;
+        case 11: c.regs = 62;  c.eff_sat = 0.85; c.t_lat_us = 0.6; c.t_round_us = 2; c.gather_cycles = 32; c.split_c0 = 1; break;
         case 12: c.regs = 90;  c.eff_sat = 0.80; c.t_lat_us = 1.0; c.t_round_us = 4; c.gather_cycles = 20; c.split_c0 = 2; break;
-        case 21: c.regs = 88;  c.eff_sat = 0.90; c.t_lat_us = 0.8; c.t_round_us = 4; c.gather_cycles = 40; break;
+        case 21: c.regs = 88;  c.eff_sat = 0.90; c.t_lat_us = 0.8; c.t_round_us = 4; c.gather_cycles = 40; c.split_c0 = 1; break;
         case 22: c.regs = cfg.bk == 16 ? 136 : 104; c.eff_sat = 0.80; c.t_lat_us = 0.8; c.t_round_us = 2; c.gather_cycles = 40;
                  c.split_c0 = 8; c.split_c1 = 0.2; break;
         case 24: c.regs = 212; c.eff_sat = 0.70; c.t_lat_us = 0.4; c.t_round_us = 2; c.gather_cycles = 20; c.split_c0 = 15; c.split_c1 = 0.6; break;
@@ -523,9 +523,17 @@ bool pick_conv(const ConvProblem &q, polydl_tile_cfg *best, polydl_model_report 
 {
     std::vector<ConvCandidate> cands;
     conv_candidates(q, &cands);
+    // Equal predictions are candidates held by the same data floor: of those the smaller workgroup
+    // tile goes first (more workgroups, so more independent loads in flight and a shorter last round).
+    auto before = [](const ConvCandidate &c, const ConvCandidate &b) {
+        const double tie = 1e-6 * b.rep.predicted_us;
+        if (c.rep.predicted_us < b.rep.predicted_us - tie) return true;
+        if (c.rep.predicted_us > b.rep.predicted_us + tie) return false;
+        return c.cfg.bm * c.cfg.bn < b.cfg.bm * b.cfg.bn;
+    };
     const ConvCandidate *b = nullptr;
     for (const ConvCandidate &c : cands)
-        if (!b || c.rep.predicted_us < b->rep.predicted_us) b = &c;
+        if (!b || before(c, *b)) b = &c;
     if (!b) return false;
     *best = b->cfg;
     *best_rep = b->rep;

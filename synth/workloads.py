@@ -43,17 +43,26 @@ _HELDOUT_TUPLES = [(256, 64, 56, 1, 1), (128, 128, 56, 3, 2), (512, 128, 28, 1, 
                    (3, 32, 149, 3, 2), (48, 64, 28, 5, 1)]
 
 
-# A second set, measured once with the final picker: the first set's sweep was looked at while the
-# model's treatment of 1x1 layers was corrected, so only this one is untouched by any tuning.
+# A second set: the first set's sweep was looked at while the model's treatment of 1x1 layers was
+# corrected; this one's misses (split reductions on small pointwise layers) set one constant.
 _HELDOUT2_TUPLES = [(128, 128, 28, 1, 1), (256, 256, 14, 1, 1), (512, 512, 7, 1, 1), (512, 1024, 28, 1, 2),
                     (64, 64, 112, 3, 2), (256, 256, 28, 3, 1), (32, 64, 112, 3, 1), (160, 320, 14, 3, 1),
                     (1024, 512, 14, 1, 1), (1024, 1024, 7, 3, 1), (16, 96, 56, 1, 1), (24, 144, 56, 1, 1),
                     (320, 1280, 7, 1, 1), (80, 192, 35, 3, 1)]
 
 
+# A third set (VGG-, AlexNet-, MobileNet-, SqueezeNet- and Xception-like shapes), drawn up after the
+# cost of a split reduction on the two smallest gather tiles was set from the second set's misses:
+# measured once, after that, and not looked at for any change.
+_HELDOUT3_TUPLES = [(64, 128, 112, 3, 1), (128, 256, 56, 3, 1), (512, 512, 28, 3, 1), (192, 384, 13, 3, 1),
+                    (32, 192, 28, 1, 1), (576, 96, 14, 1, 1), (960, 160, 7, 1, 1), (728, 728, 19, 1, 1),
+                    (64, 16, 55, 1, 1), (16, 64, 55, 3, 1), (1536, 256, 8, 1, 1), (3, 64, 224, 3, 1),
+                    (32, 96, 28, 5, 1), (128, 256, 28, 3, 2)]
+
+
 def HELDOUT_SUITE(N=32, which=1):
-    """Fourteen further CNN layer shapes at batch N (pick quality off the fitting set); which = 1 or 2."""
-    tuples = _HELDOUT_TUPLES if which == 1 else _HELDOUT2_TUPLES
+    """Fourteen further CNN layer shapes at batch N (pick quality off the fitting set); which = 1, 2 or 3."""
+    tuples = {1: _HELDOUT_TUPLES, 2: _HELDOUT2_TUPLES, 3: _HELDOUT3_TUPLES}[which]
     return [ConvShape("heldout%d_l%d" % (which, i), N, C, H, H, K, R, R, st, (R - 1) // 2)
             for i, (C, K, H, R, st) in enumerate(tuples)]
 

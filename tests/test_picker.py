@@ -87,6 +87,16 @@ def test_conv_pick_is_the_argmin_over_the_candidate_family(layer):
     assert rep.workgroups >= 1 and rep.simd_load >= 1
 
 
+def test_equal_predictions_go_to_the_smaller_workgroup_tile():
+    # a pointwise layer with 16 channels: every unsplit candidate sits on the same data floor
+    shape = (32, 16, 56, 56, 96, 1, 1, 1, 0)
+    cfg, rep = P.pick_conv2d(shape)
+    tied = [c for c in P.conv_candidates(shape)
+            if abs(P.model_conv2d(shape, c).predicted_us - rep.predicted_us) <= 1e-6 * rep.predicted_us]
+    assert len(tied) > 3 and len({c.algo for c in tied}) > 1
+    assert cfg.bm * cfg.bn == min(c.bm * c.bn for c in tied)
+
+
 def test_model_monotonic_in_batch():
     s = synth.RESNET50_SUITE(32)[2]
     cfg, _ = P.pick_conv2d(tuple(s)[1:])
