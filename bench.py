@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "1d5ea90dbccbcddc2293f2fa9bc13fbc58e9b49c1dd3708c204f0a080b286606", "batch": 32, "filters": "tap", "fetch_bytes": 449837446, "write_bytes": 355190112}
+HBM_TRAFFIC = {"csrc_sha256": "1d5ea90dbccbcddc2293f2fa9bc13fbc58e9b49c1dd3708c204f0a080b286606", "batch": 32, "filters": "tap", "fetch_bytes": 432573140, "write_bytes": 349929632}
 
 
 # L2 fetch + write-back bytes of config 4 from two rocprofv3 --pmc runs of `bench.py --copy-probe --counter-pass
