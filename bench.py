@@ -25,12 +25,12 @@ HBM_PEAK_GBS = 8000.0
 # fetch and write-back counters of two rocprofv3 --pmc runs, each scaled by what the same counter
 # reads for a plain 256 MiB elementwise copy.  Valid only for the kernel sources they were taken
 # with: their digest is kept beside them and the bench line reports null when it no longer matches.
-HBM_TRAFFIC = {"csrc_sha256": "1d5ea90dbccbcddc2293f2fa9bc13fbc58e9b49c1dd3708c204f0a080b286606", "batch": 32, "filters": "tap", "fetch_bytes": 432573140, "write_bytes": 349929632}
+HBM_TRAFFIC = {"csrc_sha256": "ca308b75c528b96f8d363a677445d90f14efc25b0ef3d95c21e6ee9a9820a0e3", "batch": 32, "filters": "tap", "fetch_bytes": 431151611, "write_bytes": 349757488}
 
 
 # L2 fetch + write-back bytes of config 4 from two rocprofv3 --pmc runs of `bench.py --copy-probe --counter-pass
 # fusion` (same scaling as above): the fused launch, and the convolution + bias + activation launches it replaces.
-FUSION_TRAFFIC = {"csrc_sha256": "1d5ea90dbccbcddc2293f2fa9bc13fbc58e9b49c1dd3708c204f0a080b286606", "fused_bytes": 109946383, "separate_bytes": 135714774}
+FUSION_TRAFFIC = {"csrc_sha256": "ca308b75c528b96f8d363a677445d90f14efc25b0ef3d95c21e6ee9a9820a0e3", "fused_bytes": 109952017, "separate_bytes": 135724285}
 
 COLD_ROTATION_BYTES = 640 * 1000 * 1000
 
@@ -76,6 +76,61 @@ def time_calls(torch, fn, reps, batches=3):
     return out[len(out) // 2]
 
 
+def vendor_rows(torch, P, synth, layers):
+    """The same layers and GEMMs through the ROCm libraries PyTorch calls (MIOpen, rocBLAS/hipBLASLt), timed
+    like the per-layer rows.  Context only: nothing here enters value or roofline."""
+    F = torch.nn.functional
+    torch.backends.cudnn.benchmark = True        # let MIOpen search its kernels for each shape
+    torch.backends.cudnn.allow_tf32 = False
+    torch.backends.cuda.matmul.allow_tf32 = False
+    fp32 = []
+    for L in layers:
+        s = L["shape"]
+        ref = F.relu(F.conv2d(L["x"], L["w"], L["b"], stride=s.stride, padding=s.pad))   # first call: the search
+        run = lambda: P.conv2d_fwd(L["x"], L["w"], L["b"], out=L["out"], stride=s.stride, pad=s.pad, act="relu",
+                                   w_tap=L["wt"])
+        run()
+        diff = float((L["out"] - ref).abs().max())
+        del ref
+        conv_ms = time_calls(torch, lambda: F.conv2d(L["x"], L["w"], None, stride=s.stride, padding=s.pad), 30)
+        full_ms = time_calls(torch, lambda: F.relu_(F.conv2d(L["x"], L["w"], L["b"], stride=s.stride, padding=s.pad)), 30)
+        ours_ms = time_calls(torch, run, 30)
+        fp32.append(dict(layer=L["index"], vendor_conv_us=round(conv_ms * 1e3, 1),
+                         vendor_conv_bias_relu_us=round(full_ms * 1e3, 1), polydl_us=round(ours_ms * 1e3, 1),
+                         max_abs_diff=diff))
+    bf16 = []
+    for i, s in enumerate(synth.RESNET50_SUITE(64)):
+        x = torch.randn(s.N, s.C, s.H, s.W, device="cuda").bfloat16()
+        w = (torch.randn(s.K, s.C, s.R, s.S, device="cuda") * (2.0 / (s.C * s.R * s.S)) ** 0.5).bfloat16()
+        b = torch.zeros(s.K, device="cuda").bfloat16()
+        row = dict(layer=i)
+        for name, fmt in (("nchw", torch.contiguous_format), ("nhwc", torch.channels_last)):
+            xc, wc = x.contiguous(memory_format=fmt), w.contiguous(memory_format=fmt)
+            F.conv2d(xc, wc, b, stride=s.stride, padding=s.pad)
+            ms = time_calls(torch, lambda: F.relu_(F.conv2d(xc, wc, b, stride=s.stride, padding=s.pad)), 30)
+            row["vendor_%s_us" % name] = round(ms * 1e3, 1)
+        bf16.append(row)
+    sg = []
+    for n in synth.SGEMM_SIZES:
+        A = torch.randn(n, n, device="cuda"); B = torch.randn(n, n, device="cuda"); C = torch.zeros(n, n, device="cuda")
+        reps = 20 if n >= 4096 else 50
+        v_ms = time_calls(torch, lambda: torch.matmul(A, B, out=C), reps)
+        o_ms = time_calls(torch, lambda: P.sgemm(A, B, C, beta=0.0), reps)
+        sg.append(dict(n=n, vendor_us=round(v_ms * 1e3, 1), vendor_tflops=round(2.0 * n ** 3 / v_ms / 1e9, 1),
+                       polydl_us=round(o_ms * 1e3, 1), polydl_tflops=round(2.0 * n ** 3 / o_ms / 1e9, 1)))
+    return dict(note="ROCm libraries as PyTorch %s calls them (MIOpen %s with its kernel search on; torch.matmul), "
+                     "same box, same process; bf16 rows: bf16 output, batch 64, to set beside the bf16 block "
+                     "(which writes fp32)" % (torch.__version__, torch.backends.cudnn.version()),
+                fp32_layers=fp32,
+                fp32_sum_us=dict(vendor_conv=round(sum(r["vendor_conv_us"] for r in fp32), 1),
+                                 vendor_conv_bias_relu=round(sum(r["vendor_conv_bias_relu_us"] for r in fp32), 1),
+                                 polydl=round(sum(r["polydl_us"] for r in fp32), 1)),
+                bf16_layers_n64=bf16,
+                bf16_sum_us=dict(vendor_nchw=round(sum(r["vendor_nchw_us"] for r in bf16), 1),
+                                 vendor_nhwc=round(sum(r["vendor_nhwc_us"] for r in bf16), 1)),
+                sgemm=sg)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +160,10 @@ def main():
     ap.add_argument("--no-layer-rows", action="store_true", help="skip the per-layer timing loops (counter runs)")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache per-layer timings")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--vendor", action="store_true",
+                    help="also time the ROCm libraries on the same operands, as context beside the CPU baseline: "
+                         "MIOpen through torch.nn.functional.conv2d (+ in-place ReLU) per layer, fp32 at --batch "
+                         "and bf16 at batch 64, and torch.matmul for the square SGEMM sizes")
     ap.add_argument("--layers", default="", help="comma list of suite layers to run (default: all eight); "
                     "a subset is for profiling one kernel and changes the workload the line reports")
     ap.add_argument("--tile", default="", help="force a variant bm,bn,bk,wm,wn[,split_k[,layout[,raster]]] (profiling)")
@@ -669,6 +728,10 @@ def main():
                    sample="fp64 oracle conv+bias+ReLU on the first %d of %d images of every layer, %d passes "
                           "(%.1f GFLOP in %.1f s)" % (nsub, args.batch, passes, done_flops / 1e9, t_cpu))
 
+    vendor = None
+    if args.vendor:
+        vendor = vendor_rows(torch, P, synth, layers)
+
     traffic = None
     if (HBM_TRAFFIC["csrc_sha256"] == csrc_digest() and args.batch == HBM_TRAFFIC["batch"] and len(chosen) == 8
             and args.suite == "resnet" and args.filters == HBM_TRAFFIC.get("filters", "kcrs")
@@ -707,6 +770,7 @@ def main():
         "config1": cfg1,
         "bnorm_relu": bn,
         "layouts": lay,
+        "vendor": vendor,
         "event_ms_per_step": round(e0.elapsed_time(e1) / args.steps, 4),
         "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 4),
         "value_graph": None if graph_ms is None else round(total_flops / (graph_ms * 1e-3) / 1e12, 3),

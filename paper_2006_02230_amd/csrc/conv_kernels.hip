@@ -306,7 +306,7 @@ __global__ __launch_bounds__(T::NT) void conv_kernel(ConvKArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
 
-    gemm_mainloop<T>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
+    gemm_mainloop<T, false>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
 
     // With the reduction of a tile split over several workgroups every part leaves its accumulator tile in scratch
     // memory (thread-contiguous, device-scope stores); the part that arrives last adds all parts

@@ -95,6 +95,12 @@ struct Tile {
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
     static constexpr int NT = WAVES_M * WAVES_N * 64;
     static constexpr int MB = WM / 32, NB = WN / 32;  // 32x32 MFMA blocks per wave tile
+    // Waves per SIMD the SGEMM kernel's register allocation is held to: the eight-block wave tiles need 128
+    // accumulator registers and end a handful of registers above the 256 that still let two
+    // waves share a SIMD; bounded, the few excess values (epilogue addresses) go to scratch.
+    static constexpr int MIN_WAVES = MB * NB >= 8 ? 2 : 1;
+    // where SGEMM runs the split stage schedule (gemm_stage): two chunks per stage, two blocks and more
+    static constexpr bool SPLIT_STAGE = BK == 16 && MB * NB >= 2;
     static constexpr int LDA = BK + 4;                 // LDS row pitch of the A stage [BM][LDA]
     static constexpr int LDB = BN + 4;                 // LDS row pitch of the B stage [BK][LDB]
     static constexpr int A_STAGE = BM * LDA, B_STAGE = BK * LDB;
@@ -252,9 +258,63 @@ struct BLoaderRows {
 };
 
 // ---- the MFMA stage: consume one LDS stage, WM x WN x BK per wave ----------------------------
-// krem: reduction rows of this stage that exist (the last stage of a reduction may be short; its
-// other rows are zeros in A).  A chunk of eight rows that lies wholly past the end is skipped
-// (uniform branch): the stem layer's reduction of 147 ends three rows into its tenth stage.
+// Two schedules.  The plain one: per chunk of eight reduction rows read the fragments, multiply;
+// copy the next stage to LDS; barrier.  The split one, see gemm_stage: the stage is multiplied in
+// two phases of one chunk each, the fragments of a phase are read from LDS one phase ahead into
+// StageFrags.  SGEMM runs the split schedule on wave tiles of two 32x32 blocks and more, where one
+// to three waves share a SIMD (measured at 2048^3 and 4096^3: 2-8 % faster on the 128x64, 128x128 and
+// larger tiles, no change with 32x32 wave tiles, slower with a single chunk per stage).  The
+// convolution kernels keep the plain one: over the suite and 28 further layer shapes the split
+// schedule gave the same total (single layers 8 % faster or 6 % slower), because many waves share
+// a SIMD there and the gather loaders' address arithmetic mixes less freely with the matrix
+// instructions once the scheduling fences are in.
+template <class T>
+struct StageFrags {
+    static constexpr int NC = T::BK / 8;
+    v4f a[NC][T::MB];          // rows wm0 + 32*bi + lane%32, reduction 8*kc + 4*(lane/32) + {0..3}
+    float b[NC][4][T::NB];     // reduction 8*kc + 4*(lane/32) + t, the lane's NB adjacent columns
+};
+
+// fragments of chunk kc: one 128-bit read per row block, one read of NB adjacent columns per rank-2 step
+template <class T>
+__device__ __forceinline__ void read_chunk(const float *__restrict__ As, const float *__restrict__ Bs,
+                                           v4f (&a)[T::MB], float (&b)[4][T::NB], int kc, int wm0, int wn0, int lane)
+{
+    const int li = lane & 31, lh = lane >> 5;
+#pragma unroll
+    for (int bi = 0; bi < T::MB; ++bi)
+        a[bi] = *reinterpret_cast<const v4f *>(As + (wm0 + 32 * bi + li) * T::LDA + kc * 8 + 4 * lh);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float *p = Bs + (kc * 8 + 4 * lh + t) * T::LDB + wn0 + T::NB * li;
+        if constexpr (T::NB == 4) {
+            v4f v = *reinterpret_cast<const v4f *>(p);
+            b[t][0] = v.x; b[t][1] = v.y; b[t][2] = v.z; b[t][3] = v.w;
+        } else if constexpr (T::NB == 2) {
+            v2f v = *reinterpret_cast<const v2f *>(p);
+            b[t][0] = v.x; b[t][1] = v.y;
+        } else {
+            b[t][0] = *p;
+        }
+    }
+}
+
+template <class T>
+__device__ __forceinline__ void mma_chunk(const v4f (&a)[T::MB], const float (&b)[4][T::NB], v16f (&acc)[T::MB][T::NB])
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int bi = 0; bi < T::MB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < T::NB; ++bj)
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bi][t], b[t][bj], acc[bi][bj], 0, 0, 0);
+}
+
+// The plain schedule's stage.  krem: reduction rows of this stage that exist (the last stage of a
+// reduction may be short; its other rows are zeros in A).  A chunk of eight rows that lies wholly
+// past the end is skipped (uniform branch): the stem layer's reduction of 147 ends three rows into
+// its tenth stage.
 template <class T>
 __device__ __forceinline__ void mma_stage(const float *__restrict__ As, const float *__restrict__ Bs,
                                           v16f (&acc)[T::MB][T::NB], int wm0, int wn0, int lane, int krem)
@@ -295,28 +355,57 @@ __device__ __forceinline__ void mma_stage(const float *__restrict__ As, const fl
 // matrix cores: while stage t is multiplied out of LDS buffer t&1, the registers of set (t+1)&1
 // already hold stage t+1 and the loads of stage t+2 are issued into set t&1.  A load therefore
 // has two full stages of MFMA work (several thousand cycles) to come back from HBM before its
-// data is copied to LDS at the end of the following stage; one barrier per stage publishes the
-// copy.  A loader that runs past kend fills with zeros, so the tail needs no special case.
-template <class T, int HALF, class AL, class BL>
+// data is copied to LDS during the following stage; one barrier per stage publishes the copy.  A
+// loader that runs past kend fills with zeros, so the tail needs no special case.
+//
+// Split schedule: the barrier sits in the MIDDLE of the stage, between its two chunks.  Before it
+// a wave reads the fragments of the second chunk and copies stage t+1 to the other LDS buffer;
+// after it the wave still has the whole second chunk to multiply with operands that are already
+// in registers, and reads the first chunk of stage t+1 (published by that barrier) underneath.
+// So no matrix instruction waits for a barrier and then for an LDS read behind it.  Why the
+// buffers do not collide: buffer b is read by stage t only -- first chunk after the barrier of
+// stage t-1, second chunk before the barrier of stage t, where every wave waits for its own LDS
+// reads before it arrives -- and written (with stage t+2) before the barrier of stage t+1, i.e.
+// after every wave has passed the barrier of stage t.  The scheduling fences keep the compiler
+// from moving the second chunk's matrix instructions up across the barrier, where nothing but
+// memory order holds them, and from sinking the LDS reads down to their first use.
+template <class T, int HALF, bool SPLIT, class AL, class BL>
 __device__ __forceinline__ void gemm_stage(float *As, float *Bs, AL &al, BL &bl, v16f (&acc)[T::MB][T::NB],
-                                           int k, int kend, int tid, int wm0, int wn0)
+                                           StageFrags<T> &f, int k, int kend, int tid, int wm0, int wn0)
 {
-    // register set HALF is free (its stage is in LDS buffer HALF): fetch stage k + 2*BK into it
-    al.template load<HALF>(k + 2 * T::BK, kend);
-    bl.template load<HALF>(k + 2 * T::BK, kend);
-    mma_stage<T>(As + HALF * T::A_STAGE, Bs + HALF * T::B_STAGE, acc, wm0, wn0, tid & 63, kend - k);
-    // stage k + BK sits in the other set: copy it to the other LDS buffer
-    al.template store<HALF ^ 1>(As + (HALF ^ 1) * T::A_STAGE, tid);
-    bl.template store<HALF ^ 1>(Bs + (HALF ^ 1) * T::B_STAGE, tid);
-    __syncthreads();
+    const int lane = tid & 63;
+    if constexpr (!SPLIT) {
+        // register set HALF is free (its stage is in LDS buffer HALF): fetch stage k + 2*BK into it
+        al.template load<HALF>(k + 2 * T::BK, kend);
+        bl.template load<HALF>(k + 2 * T::BK, kend);
+        mma_stage<T>(As + HALF * T::A_STAGE, Bs + HALF * T::B_STAGE, acc, wm0, wn0, lane, kend - k);
+        // stage k + BK sits in the other set: copy it to the other LDS buffer
+        al.template store<HALF ^ 1>(As + (HALF ^ 1) * T::A_STAGE, tid);
+        bl.template store<HALF ^ 1>(Bs + (HALF ^ 1) * T::B_STAGE, tid);
+        __syncthreads();
+    } else {
+        read_chunk<T>(As + HALF * T::A_STAGE, Bs + HALF * T::B_STAGE, f.a[1], f.b[1], 1, wm0, wn0, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        al.template load<HALF>(k + 2 * T::BK, kend);
+        bl.template load<HALF>(k + 2 * T::BK, kend);
+        mma_chunk<T>(f.a[0], f.b[0], acc);
+        al.template store<HALF ^ 1>(As + (HALF ^ 1) * T::A_STAGE, tid);
+        bl.template store<HALF ^ 1>(Bs + (HALF ^ 1) * T::B_STAGE, tid);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        read_chunk<T>(As + (HALF ^ 1) * T::A_STAGE, Bs + (HALF ^ 1) * T::B_STAGE, f.a[0], f.b[0], 0, wm0, wn0, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kend - k > 8) mma_chunk<T>(f.a[1], f.b[1], acc);   // uniform: a short last stage ends in its first chunk
+    }
 }
 
-template <class T, class AL, class BL>
+template <class T, bool SPLIT, class AL, class BL>
 __device__ __forceinline__ void gemm_mainloop(float *lds, AL &al, BL &bl, v16f (&acc)[T::MB][T::NB],
                                               int kbegin, int kend, int tid, int wm0, int wn0)
 {
     float *As = lds;
     float *Bs = lds + 2 * T::A_STAGE;
+    StageFrags<T> f;   // used by the split schedule only
     // stage 0 -> LDS buffer 0, stage 1 -> register set 1
     al.template load<0>(kbegin, kend);
     bl.template load<0>(kbegin, kend);
@@ -325,17 +414,18 @@ __device__ __forceinline__ void gemm_mainloop(float *lds, AL &al, BL &bl, v16f (
     al.template store<0>(As, tid);
     bl.template store<0>(Bs, tid);
     __syncthreads();
+    if constexpr (SPLIT) read_chunk<T>(As, Bs, f.a[0], f.b[0], 0, wm0, wn0, tid & 63);
     // Stages go in pairs, both halves unconditionally, and an odd last stage is peeled off: with a
     // conditional second half inside the loop the compiler has to assume at the loop head that the
     // loads of the first half may still be in flight into the registers the head overwrites, and it
     // waits there for loads that were issued only one stage earlier.
     int k0 = kbegin;
     for (; k0 + T::BK < kend; k0 += 2 * T::BK) {
-        gemm_stage<T, 0>(As, Bs, al, bl, acc, k0, kend, tid, wm0, wn0);
-        gemm_stage<T, 1>(As, Bs, al, bl, acc, k0 + T::BK, kend, tid, wm0, wn0);
+        gemm_stage<T, 0, SPLIT>(As, Bs, al, bl, acc, f, k0, kend, tid, wm0, wn0);
+        gemm_stage<T, 1, SPLIT>(As, Bs, al, bl, acc, f, k0 + T::BK, kend, tid, wm0, wn0);
     }
     if (k0 < kend)   // workgroup-uniform
-        gemm_stage<T, 0>(As, Bs, al, bl, acc, k0, kend, tid, wm0, wn0);
+        gemm_stage<T, 0, SPLIT>(As, Bs, al, bl, acc, f, k0, kend, tid, wm0, wn0);
 }
 
 // Sum of the `parts` partial accumulator tiles of one output tile, in index order (so the result

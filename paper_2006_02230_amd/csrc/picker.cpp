@@ -422,7 +422,8 @@ void model_sgemm(const SgemmProblem &q, const polydl_tile_cfg &cfg, int threads,
     c.loop_eff = 0.84;
     c.wg_overhead_cycles = 3000;
     c.kernel_fixed_us = 6.0;
-    c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 1 : ((cfg.wm * cfg.wn == 64 * 64) ? 2 : 4);
+    // from the kernels' register counts (the eight-block wave tiles are held to 256 registers)
+    c.max_waves_per_simd = (cfg.wm * cfg.wn > 64 * 64) ? 2 : ((cfg.wm * cfg.wn == 64 * 64) ? 3 : 4);
     model(s, c, r);
     if (cfg.split_k > 1) {   // every part writes its tile to scratch once, the last one reads them all back
         // plus the hand-over itself (store, count, read back), which no amount of bandwidth shortens

@@ -22,7 +22,7 @@ struct SgemmKArgs {
 // AVEC / BVEC: 4 when the operand allows 128-bit loads, else 1.  CVEC: the lane's NB adjacent
 // output columns are read and written as one vector when N % NB == 0 and C is 16-byte aligned.
 template <class T, int AVEC, int BVEC, bool CVEC>
-__global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
+__global__ __launch_bounds__(T::NT, T::MIN_WAVES) void sgemm_kernel(SgemmKArgs p)
 {
     __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(SgemmKArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
 
-    if (kbegin < kend) gemm_mainloop<T>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
+    if (kbegin < kend) gemm_mainloop<T, T::SPLIT_STAGE>(lds, al, bl, acc, kbegin, kend, tid, wm0, wn0);
 
     // With the reduction split over blockIdx.y every part leaves its accumulator tile in scratch
     // memory (thread-contiguous, device-scope stores); the part that arrives last adds all parts
