@@ -61,6 +61,22 @@ def test_all_variants_small_integers_exact(P, M, N, K):
     P.set_tile_override(None)
 
 
+@pytest.mark.parametrize("K", [2, 7, 9, 15, 16, 24, 25, 31, 32, 33, 40, 48, 56])
+def test_reduction_lengths_around_stage_and_chunk_boundaries(P, K):
+    # a stage is 8 or 16 reduction rows in chunks of eight; stages run in pairs with an odd one peeled
+    # off, and a last chunk that lies wholly past the end is skipped: every such boundary, exactly
+    M, N = 130, 200
+    A, B, C0 = synth.sgemm_inputs(M, N, K, seed=40 + K, dist="ints", c0="random")
+    want, _ = oracle.gemm(A, B, C0)
+    for v in P.variants(1):
+        for split_k in (1, 2):
+            v.split_k = split_k
+            P.set_tile_override(v)
+            got = run_sgemm(P, A, B, C0)
+            assert np.array_equal(got.astype(np.float64), want), (v, K)
+    P.set_tile_override(None)
+
+
 def test_identity_gives_exact_copy(P):
     M = N = K = 192
     A, _, C0 = synth.sgemm_inputs(M, N, K, seed=9, c0="random")
